@@ -1,0 +1,226 @@
+"""ctypes front-end of the CPU oracle (oracle/fmoe_oracle.cpp).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by bench.py's
+cpu_baseline leg.  The product package never imports this module.  Only argument marshalling
+lives here; the arithmetic is in the C++ file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+_f32p = C.POINTER(C.c_float)
+_f64p = C.POINTER(C.c_double)
+_i32p = C.POINTER(C.c_int32)
+_u8p = C.POINTER(C.c_uint8)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            from . import build as _b
+            _b.build()
+        _lib = C.CDLL(_LIB_PATH)
+        _lib.orc_exp_canon.restype = C.c_float
+        _lib.orc_exp_canon.argtypes = [C.c_float]
+        _lib.orc_sum_canon.restype = C.c_float
+        _lib.orc_sum_canon.argtypes = [_f32p, C.c_int]
+        _lib.orc_dot_canon.restype = C.c_float
+        _lib.orc_dot_canon.argtypes = [_f32p, _f32p, C.c_int]
+        _lib.orc_round_store.restype = C.c_float
+        _lib.orc_round_store.argtypes = [C.c_double, C.c_int]
+    return _lib
+
+
+def _p(a: Optional[np.ndarray], ty):
+    if a is None:
+        return None
+    return a.ctypes.data_as(ty)
+
+
+def _f32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _u8(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.uint8)
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
+def exp_canon(x: float) -> np.float32:
+    return np.float32(lib().orc_exp_canon(C.c_float(float(x))))
+
+
+def sum_canon(v) -> np.float32:
+    v = _f32(v)
+    return np.float32(lib().orc_sum_canon(_p(v, _f32p), int(v.size)))
+
+
+def dot_canon(a, b) -> np.float32:
+    a, b = _f32(a), _f32(b)
+    assert a.size == b.size
+    return np.float32(lib().orc_dot_canon(_p(a, _f32p), _p(b, _f32p), int(a.size)))
+
+
+def round_store(v: float, is_bf16: bool) -> np.float32:
+    return np.float32(lib().orc_round_store(C.c_double(float(v)), int(is_bf16)))
+
+
+def route(x, is_visual, router_w, router_bias, k_text, k_visual, renormalize=True, shadow=False):
+    """Eq.1-3, Eq.5.  Returns probs [T,E] f32, topk_idx [T,Kmax] i32, topk_gate [T,Kmax] f32
+    (and the fp64 shadow probabilities when shadow=True)."""
+    x, router_w, router_bias, is_visual = _f32(x), _f32(router_w), _f32(router_bias), _u8(is_visual)
+    T, d = x.shape
+    E = router_w.shape[0]
+    assert router_w.shape[1] == d and is_visual.shape[0] == T
+    Kmax = max(k_text, k_visual)
+    probs = np.empty((T, E), np.float32)
+    idx = np.empty((T, Kmax), np.int32)
+    gate = np.empty((T, Kmax), np.float32)
+    p64 = np.empty((T, E), np.float64) if shadow else None
+    rc = lib().orc_route(_p(x, _f32p), _p(is_visual, _u8p), T, d, E, _p(router_w, _f32p),
+                         _p(router_bias, _f32p), int(k_text), int(k_visual), int(bool(renormalize)),
+                         _p(probs, _f32p), _p(idx, _i32p), _p(gate, _f32p), _p(p64, _f64p))
+    if rc != 0:
+        raise ValueError("orc_route: bad arguments")
+    return (probs, idx, gate, p64) if shadow else (probs, idx, gate)
+
+
+def prune(probs, is_visual, cu_seqlens, retention, window, alpha=1.0, gamma=0.0, sim_mode=0,
+          attn=None):
+    """Sec. 3.2 (scores, budget, drop).  Returns kept_idx [T'] i32 ascending, new_cu_seqlens [B+1],
+    window scores C (sequences concatenated)."""
+    probs, is_visual, cu, attn = _f32(probs), _u8(is_visual), _i32(cu_seqlens), _f32(attn)
+    T, E = probs.shape
+    B = cu.shape[0] - 1
+    offs = np.empty(B + 1, np.int32)
+    nwin = lib().orc_window_counts(_p(is_visual, _u8p), _p(cu, _i32p), B, int(window), _p(offs, _i32p))
+    kept = np.empty(max(T, 1), np.int32)
+    new_cu = np.empty(B + 1, np.int32)
+    scores = np.empty(max(nwin, 1), np.float32)
+    n = lib().orc_prune(_p(probs, _f32p), _p(is_visual, _u8p), _p(cu, _i32p), B, T, E,
+                        C.c_float(retention), int(window), C.c_float(alpha), C.c_float(gamma),
+                        int(sim_mode), _p(attn, _f32p), _p(kept, _i32p), _p(new_cu, _i32p),
+                        _p(scores, _f32p))
+    if n < 0:
+        raise ValueError("orc_prune: bad arguments")
+    return kept[:n].copy(), new_cu, scores[:nwin].copy()
+
+
+def permute(topk_idx, kept_idx, E):
+    """Dispatch order: rows sorted by (expert, kept position).  Returns expert_offsets [E+1],
+    perm_src [M], inv_perm [n_kept, Kmax]."""
+    topk_idx = _i32(topk_idx)
+    T, Kmax = topk_idx.shape
+    kept_idx = _i32(kept_idx)
+    n_kept = T if kept_idx is None else int(kept_idx.shape[0])
+    offs = np.empty(E + 1, np.int32)
+    perm = np.empty(max(n_kept * Kmax, 1), np.int32)
+    inv = np.empty((n_kept, Kmax), np.int32)
+    M = lib().orc_permute(_p(topk_idx, _i32p), Kmax, _p(kept_idx, _i32p), n_kept, E,
+                          _p(offs, _i32p), _p(perm, _i32p), _p(inv, _i32p))
+    return offs, perm[:M].copy(), inv
+
+
+def expert_ffn(x, kept_idx, expert_offsets, perm_src, w_gate, w_up, w_down, is_bf16, rows_sel=None):
+    """Routed SwiGLU experts on the permuted rows; y [M,d] fp64 (rows not in rows_sel stay 0)."""
+    x, w_gate, w_up, w_down = _f32(x), _f32(w_gate), _f32(w_up), _f32(w_down)
+    kept_idx, offs, perm, rows_sel = _i32(kept_idx), _i32(expert_offsets), _i32(perm_src), _i32(rows_sel)
+    E, F, d = w_gate.shape
+    assert w_down.shape == (E, d, F) and x.shape[1] == d
+    M = int(offs[E])
+    y = np.zeros((M, d), np.float64)
+    lib().orc_expert_ffn(_p(x, _f32p), _p(kept_idx, _i32p), _p(offs, _i32p), _p(perm, _i32p), E, d, F,
+                         int(is_bf16), _p(w_gate, _f32p), _p(w_up, _f32p), _p(w_down, _f32p),
+                         _p(rows_sel, _i32p), 0 if rows_sel is None else int(rows_sel.size),
+                         _p(y, _f64p))
+    return y
+
+
+def shared_ffn(x, kept_idx, n_kept, ws_gate, ws_up, ws_down, is_bf16, pos_sel=None):
+    """Sum of the always-on shared experts per kept token; [n_kept,d] fp64."""
+    x, ws_gate, ws_up, ws_down = _f32(x), _f32(ws_gate), _f32(ws_up), _f32(ws_down)
+    kept_idx, pos_sel = _i32(kept_idx), _i32(pos_sel)
+    Ns, Fs, d = ws_gate.shape
+    y = np.zeros((n_kept, d), np.float64)
+    lib().orc_shared_ffn(_p(x, _f32p), _p(kept_idx, _i32p), int(n_kept), d, Ns, Fs, int(is_bf16),
+                         _p(ws_gate, _f32p), _p(ws_up, _f32p), _p(ws_down, _f32p),
+                         _p(pos_sel, _i32p), 0 if pos_sel is None else int(pos_sel.size), _p(y, _f64p))
+    return y
+
+
+def combine(y, y_shared, inv_perm, topk_gate, kept_idx, d, residual, is_bf16, pos_sel=None):
+    """Eq.4 on the permuted rows.  Returns (out f32 container [n_kept,d], out fp64 unrounded)."""
+    y = np.ascontiguousarray(y, np.float64)
+    y_shared = None if y_shared is None else np.ascontiguousarray(y_shared, np.float64)
+    inv_perm, topk_gate, kept_idx = _i32(inv_perm), _f32(topk_gate), _i32(kept_idx)
+    residual, pos_sel = _f32(residual), _i32(pos_sel)
+    n_kept, Kmax = inv_perm.shape
+    out = np.zeros((n_kept, d), np.float32)
+    out64 = np.zeros((n_kept, d), np.float64)
+    lib().orc_combine(_p(y, _f64p), _p(y_shared, _f64p), _p(inv_perm, _i32p), _p(topk_gate, _f32p),
+                      _p(kept_idx, _i32p), n_kept, Kmax, int(d), _p(residual, _f32p), int(is_bf16),
+                      _p(pos_sel, _i32p), 0 if pos_sel is None else int(pos_sel.size),
+                      _p(out, _f32p), _p(out64, _f64p))
+    return out, out64
+
+
+def token_outputs(x, tokens, topk_idx, topk_gate, w, is_bf16, add_residual=False):
+    """Eq.4 directly for the listed token indices (no permutation).  `w` has the fields of
+    workloads.LayerWeights.  Returns (out f32 container, out fp64)."""
+    x, tokens, topk_idx, topk_gate = _f32(x), _i32(tokens), _i32(topk_idx), _f32(topk_gate)
+    w_gate, w_up, w_down = _f32(w.w_gate), _f32(w.w_up), _f32(w.w_down)
+    ws_gate, ws_up, ws_down = _f32(w.ws_gate), _f32(w.ws_up), _f32(w.ws_down)
+    E, F, d = w_gate.shape
+    Ns, Fs = (0, 0) if ws_gate is None else ws_gate.shape[:2]
+    Kmax = topk_idx.shape[1]
+    n = int(tokens.size)
+    out = np.zeros((n, d), np.float32)
+    out64 = np.zeros((n, d), np.float64)
+    lib().orc_token_outputs(_p(x, _f32p), _p(tokens, _i32p), n, d, E, F, Ns, Fs, int(is_bf16), Kmax,
+                            _p(topk_idx, _i32p), _p(topk_gate, _f32p), _p(w_gate, _f32p),
+                            _p(w_up, _f32p), _p(w_down, _f32p), _p(ws_gate, _f32p), _p(ws_up, _f32p),
+                            _p(ws_down, _f32p), int(bool(add_residual)), _p(out, _f32p), _p(out64, _f64p))
+    return out, out64
+
+
+def layer_forward(x, is_visual, cu_seqlens, w, *, k_text, k_visual, is_bf16, retention=1.0,
+                  window=1, alpha=1.0, gamma=0.0, sim_mode=0, attn=None, add_residual=False,
+                  renormalize=True, do_prune=True, ffn=True):
+    """The whole path: route -> prune -> permute -> experts -> combine (the steps chained, nothing
+    else).  Returns a dict with every intermediate."""
+    T = x.shape[0]
+    E = w.router_w.shape[0]
+    d = x.shape[1]
+    probs, idx, gate = route(x, is_visual, w.router_w, w.router_bias, k_text, k_visual, renormalize)
+    if do_prune and retention < 1.0:
+        kept, new_cu, scores = prune(probs, is_visual, cu_seqlens, retention, window,
+                                     alpha, gamma, sim_mode, attn)
+    else:
+        kept, new_cu, scores = np.arange(T, dtype=np.int32), _i32(cu_seqlens).copy(), None
+    offs, perm, inv = permute(idx, kept, E)
+    res = dict(probs=probs, topk_idx=idx, topk_gate=gate, kept_idx=kept, new_cu_seqlens=new_cu,
+               scores=scores, expert_offsets=offs, perm_src=perm, inv_perm=inv)
+    if ffn:
+        y = expert_ffn(x, kept, offs, perm, w.w_gate, w.w_up, w.w_down, is_bf16)
+        ysh = None
+        if w.ws_gate is not None:
+            ysh = shared_ffn(x, kept, kept.shape[0], w.ws_gate, w.ws_up, w.ws_down, is_bf16)
+        out, out64 = combine(y, ysh, inv, gate, kept, d, x if add_residual else None, is_bf16)
+        res.update(y=y, y_shared=ysh, out=out, out_f64=out64)
+    return res
