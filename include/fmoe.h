@@ -1,0 +1,190 @@
+/* fmoe.h -- C ABI of the MI355X (gfx950) MoE-layer prefill library.
+ *
+ * The library computes one Mixture-of-Experts layer forward over a packed batch of
+ * [visual tokens, text tokens] sequences with the two FastMMoE mechanisms in it:
+ * modality-dependent top-k routing with gate renormalisation (paper Sec. 3.1) and routing-aware
+ * sliding-window visual-token pruning (paper Sec. 3.2).  Symbols follow the paper: H = d_model,
+ * E = routed experts, S_m = d_ffn, K = k_text, K_v = k_visual, N_s = n_shared, W = window.
+ *
+ * Conventions
+ *  - Plain C; every function returns FMOE_OK (0) or a negative fmoe_status; nothing throws or
+ *    aborts.  fmoe_last_error() gives a thread-local message for the last failure.
+ *  - Every tensor pointer is a DEVICE pointer on the context's GPU unless marked [host].
+ *    Tensors are row-major, contiguous, 16-byte aligned, and stay owned by the caller; the
+ *    library only borrows them for the duration of the enqueued work.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *    enqueued asynchronously on it; no call synchronises with the host and no hot call
+ *    (route / prune / permute / expert_ffn / combine / layer_forward) allocates memory.
+ *    Scratch comes from a caller-provided workspace sized by fmoe_workspace_bytes().
+ *  - Data-dependent counts (tokens kept, rows per expert) stay on the device:
+ *    new_cu_seqlens[B] holds the number of kept tokens T'; expert_offsets[E] holds the number
+ *    of routed rows M.
+ *  - "dtype" is the storage type of activations and weights (fp32 or bf16); accumulation is
+ *    always fp32.  Router probabilities, gates and window scores are fp32 in a fixed
+ *    operation order so that expert ids, the permutation and the kept-token set are
+ *    reproducible bit for bit.
+ *  - Shape limits: 1 <= E <= 256, Kmax = max(k_text,k_visual) <= 16 and <= E,
+ *    d_model % 8 == 0, d_ffn % 8 == 0, d_ffn_shared % 8 == 0, T < 2^24, window <= 64.
+ *    Anything else returns FMOE_ERR_UNSUPPORTED.
+ */
+#ifndef FMOE_H_
+#define FMOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FMOE_OK = 0,
+  FMOE_ERR_INVALID_ARG = -1, /* value out of its documented range                  */
+  FMOE_ERR_NULL_PTR = -2,    /* a required pointer is NULL                         */
+  FMOE_ERR_BAD_SHAPE = -3,   /* sizes inconsistent with the context's config       */
+  FMOE_ERR_WORKSPACE = -4,   /* workspace missing, misaligned or too small         */
+  FMOE_ERR_UNSUPPORTED = -5, /* valid request outside the implemented shape limits */
+  FMOE_ERR_HIP = -6          /* a HIP runtime call failed (launch, attribute, ...) */
+} fmoe_status;
+
+typedef enum { FMOE_F32 = 0, FMOE_BF16 = 1 } fmoe_dtype;
+
+typedef struct {
+  int32_t d_model;      /* H                                                    */
+  int32_t n_experts;    /* E, routed (non-shared) experts                       */
+  int32_t d_ffn;        /* S_m, intermediate size of one routed expert          */
+  int32_t n_shared;     /* N_s >= 0 always-on shared experts (Eq.4, first sum)  */
+  int32_t d_ffn_shared; /* intermediate size of one shared expert               */
+  int32_t k_text;       /* K: experts per text token                            */
+  int32_t k_visual;     /* K_v: experts per visual token (0 allowed)            */
+  int32_t renormalize;  /* 1: gates divided by the sum over the kept experts    */
+  int32_t dtype;        /* fmoe_dtype of activations and weights                */
+} fmoe_config;
+
+typedef struct {
+  float retention;    /* r in (0,1]: keep round(r*N_v) visual tokens per sequence; 1 = off */
+  int32_t window;     /* W >= 1 consecutive visual tokens per window (Sec. 3.2.2)          */
+  float alpha;        /* weight of routing similarity in the redundancy score (Eq.13)      */
+  float gamma;        /* merge rate (Eq.14); must be 0: window merging is not implemented  */
+  int32_t sim_mode;   /* 0: similarity to the window mean (Eq.9-10); 1: all pairs (Eq.8)   */
+  int32_t prune_mode; /* 0: none; 1 or 2: prune between routing and the experts            */
+} fmoe_prune_params;
+
+typedef struct fmoe_ctx fmoe_ctx;
+
+/* Library version string, static storage. */
+const char* fmoe_version(void);
+
+/* Message for the calling thread's most recent failure ("" if none). [host] */
+const char* fmoe_last_error(void);
+
+/* Create a context for one layer shape on GPU `device`.  Validates the config against the
+ * shape limits.  The context holds only host-side state and borrowed weight pointers. */
+int fmoe_create(fmoe_ctx** out_ctx, const fmoe_config* config, int device);
+void fmoe_destroy(fmoe_ctx* ctx);
+
+/* Change K and K_v of an existing context (the per-layer l_v switch of Sec. 3.1).
+ * Kmax = max(k_text,k_visual) changes with it, and so do the [*,Kmax] tensor shapes. */
+int fmoe_set_topk(fmoe_ctx* ctx, int32_t k_text, int32_t k_visual);
+
+/* Register the layer's weights (Eq.1, Eq.4).  Pointers are borrowed until the next call or
+ * fmoe_destroy.  router_w [E,H] dtype; router_bias [E] fp32 or NULL (added to the logits
+ * before the softmax); w_gate, w_up [E,S_m,H]; w_down [E,H,S_m]; ws_gate, ws_up
+ * [N_s,S_s,H]; ws_down [N_s,H,S_s] (NULL iff N_s == 0).  An expert is the three-matrix gated
+ * FFN  y = W_down (silu(W_gate x) * (W_up x))  without biases (flop model of App. E).
+ * For bf16 contexts the router matrix is widened once into a private fp32 copy (the only
+ * device allocation the library makes; freed by the next set_weights / destroy). */
+int fmoe_set_weights(fmoe_ctx* ctx, const void* router_w, const float* router_bias,
+                     const void* w_gate, const void* w_up, const void* w_down,
+                     const void* ws_gate, const void* ws_up, const void* ws_down, void* stream);
+
+/* Bytes of workspace that any hot call needs for up to max_tokens tokens in up to max_seqs
+ * sequences with this context (for the Kmax current at the time of the call). [host] */
+size_t fmoe_workspace_bytes(const fmoe_ctx* ctx, int32_t max_tokens, int32_t max_seqs);
+
+/* Eq.1-3 and Eq.5: router logits, softmax, modality-dependent top-k, gates.
+ * x [T,H] dtype; is_visual [T] (non-zero = visual token).
+ * probs [T,E] fp32 or NULL: softmax probabilities of every token.
+ * topk_idx [T,Kmax] int32: the k experts with the highest probability, ordered by
+ * (probability descending, expert index ascending) -- ties go to the lower index -- padded
+ * with -1 (k = k_visual for visual tokens, k_text otherwise).
+ * topk_gate [T,Kmax] fp32: P_j / sum of the listed P (or P_j if renormalize == 0), pad 0. */
+int fmoe_route(fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int32_t T, float* probs,
+               int32_t* topk_idx, float* topk_gate, void* stream);
+
+/* Sec. 3.2: window redundancy scores, budget, drop, compaction -- per sequence.
+ * probs [T,E] fp32 from fmoe_route; cu_seqlens [B+1] int32 (cu[0] = 0, cu[B] = T).
+ * attn_importance [T] fp32 or NULL: per-token attention importance (Eq.7); when given, windows
+ * are dropped in the order (normalised window attention ascending, score descending, index
+ * ascending), otherwise (score descending, index ascending).
+ * Visual tokens of a sequence, in position order, are cut into windows of W (the last may be
+ * shorter; a one-token window scores exactly 1).  eta = floor(r*N_v + 1/2) visual tokens
+ * survive (at least 1 if N_v > 0): whole windows are dropped in order while they fit and the
+ * next window loses its last tokens.  Text tokens always survive.
+ * kept_idx [T capacity] int32: ascending global indices of surviving tokens (first T' valid).
+ * new_cu_seqlens [B+1] int32: per-sequence boundaries after pruning; new_cu_seqlens[B] = T'.
+ * scores [T capacity] fp32 or NULL: the score C of window i of sequence b at
+ * scores[cu_seqlens[b] + i].
+ * x_in / x_merged are reserved for window merging (gamma > 0) and must be NULL. */
+int fmoe_prune(fmoe_ctx* ctx, const fmoe_prune_params* params, const float* probs,
+               const uint8_t* is_visual, const int32_t* cu_seqlens, int32_t B, int32_t T,
+               const float* attn_importance, const void* x_in, int32_t* kept_idx,
+               int32_t* new_cu_seqlens, float* scores, void* x_merged, void* ws, size_t ws_bytes,
+               void* stream);
+
+/* Dispatch order (the paper leaves it to the framework): the rows are all (kept position p,
+ * slot s) pairs with topk_idx >= 0, sorted by (expert ascending, p ascending).
+ * kept_idx [n_kept] or NULL (= all tokens, p == t).  n_kept_dev: optional device int32 that
+ * overrides n_kept (which then is only the capacity) -- pass new_cu_seqlens + B.
+ * expert_offsets [E+1] int32: exclusive scan of rows per expert; expert_offsets[E] = M.
+ * perm_src [n_kept*Kmax capacity] int32: row -> kept position p.
+ * inv_perm [n_kept,Kmax] int32: (p,s) -> row, or -1. */
+int fmoe_permute(fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* kept_idx, int32_t n_kept,
+                 const int32_t* n_kept_dev, int32_t* expert_offsets, int32_t* perm_src,
+                 int32_t* inv_perm, void* ws, size_t ws_bytes, void* stream);
+
+/* The expert FFNs of Eq.4 as a grouped GEMM: for every row r of expert e,
+ * y[r] = FFN_e(x[token(perm_src[r])]); the activation silu(.)*(.) is rounded to dtype between
+ * the two products.  y [n_kept*Kmax capacity, H] dtype.  y_shared [n_kept,H] dtype or NULL iff
+ * N_s == 0: the SUM of the shared experts for every kept token. */
+int fmoe_expert_ffn(fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int32_t n_kept,
+                    const int32_t* n_kept_dev, const int32_t* expert_offsets,
+                    const int32_t* perm_src, void* y, void* y_shared, void* ws, size_t ws_bytes,
+                    void* stream);
+
+/* Eq.4: out[p] = (residual[t]) + y_shared[p] + sum_s topk_gate[t,s] * y[inv_perm[p,s]] with
+ * t = kept_idx[p]; fp32 accumulation in that order, one rounding to dtype.
+ * residual [T,H] dtype or NULL; out [n_kept,H] dtype. */
+int fmoe_combine(fmoe_ctx* ctx, const void* y, const void* y_shared, const int32_t* inv_perm,
+                 const float* topk_gate, const int32_t* kept_idx, int32_t n_kept,
+                 const int32_t* n_kept_dev, const void* residual, void* out, void* stream);
+
+/* The whole layer: route -> prune (if params != NULL and prune_mode != 0 and retention < 1)
+ * -> permute -> expert_ffn -> combine, enqueued back to back.  Equivalent to the five calls.
+ * out [T capacity,H] dtype (first T' rows valid); kept_idx [T]; new_cu_seqlens [B+1];
+ * is_visual_out [T capacity] or NULL: the modality mask of the kept tokens.
+ * add_residual != 0 adds x[t] to the layer output (x <- x + MoE(x)).
+ * Because an MoE layer acts on every token independently, dropping a token before the experts
+ * gives the kept tokens the same outputs as dropping it after the layer; both prune modes
+ * therefore run the experts on the kept tokens only. */
+int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const void* x,
+                       const uint8_t* is_visual, const int32_t* cu_seqlens, int32_t B, int32_t T,
+                       const float* attn_importance, int add_residual, void* out,
+                       int32_t* kept_idx, int32_t* new_cu_seqlens, uint8_t* is_visual_out,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* Instrumentation (not part of the paper's path): per-kernel GPU time of the most recent hot
+ * call.  fmoe_profile_enable(ctx,1) creates one HIP event pair per kernel slot and makes every
+ * later launch on this context record them on its stream; (ctx,0) stops recording.
+ * fmoe_profile_read waits for the recorded events and writes the milliseconds of each slot to
+ * ms[fmoe_profile_slots()] [host] (-1 for slots the last call did not launch), then clears the
+ * "launched" marks.  fmoe_profile_name gives a slot's kernel name. */
+int fmoe_profile_enable(fmoe_ctx* ctx, int enable);
+int fmoe_profile_slots(void);
+const char* fmoe_profile_name(int slot);
+int fmoe_profile_read(fmoe_ctx* ctx, float* ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FMOE_H_ */

@@ -1,0 +1,247 @@
+"""Thin ctypes binding over libfmoe.so (declared in include/fmoe.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.  PyTorch
+supplies device memory and the current stream.  There is no fallback: if the library has not
+been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfmoe.so")
+
+FMOE_F32, FMOE_BF16 = 0, 1
+EXPORTS = ["fmoe_version", "fmoe_last_error", "fmoe_create", "fmoe_destroy", "fmoe_set_topk",
+           "fmoe_set_weights", "fmoe_workspace_bytes", "fmoe_route", "fmoe_prune", "fmoe_permute",
+           "fmoe_expert_ffn", "fmoe_combine", "fmoe_layer_forward", "fmoe_profile_enable",
+           "fmoe_profile_slots", "fmoe_profile_name", "fmoe_profile_read"]
+
+
+class FmoeConfig(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_experts", C.c_int32), ("d_ffn", C.c_int32),
+                ("n_shared", C.c_int32), ("d_ffn_shared", C.c_int32), ("k_text", C.c_int32),
+                ("k_visual", C.c_int32), ("renormalize", C.c_int32), ("dtype", C.c_int32)]
+
+
+class FmoePruneParams(C.Structure):
+    _fields_ = [("retention", C.c_float), ("window", C.c_int32), ("alpha", C.c_float),
+                ("gamma", C.c_float), ("sim_mode", C.c_int32), ("prune_mode", C.c_int32)]
+
+
+class FmoeError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"fmoe error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Load libfmoe.so and declare the prototypes.  Raises if the library is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not built: run `python -m paper_2511_17885_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    lib.fmoe_version.restype = C.c_char_p
+    lib.fmoe_last_error.restype = C.c_char_p
+    lib.fmoe_create.argtypes = [C.POINTER(vp), C.POINTER(FmoeConfig), C.c_int]
+    lib.fmoe_destroy.argtypes = [vp]
+    lib.fmoe_destroy.restype = None
+    lib.fmoe_set_topk.argtypes = [vp, i32, i32]
+    lib.fmoe_set_weights.argtypes = [vp] + [vp] * 8 + [vp]
+    lib.fmoe_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.fmoe_workspace_bytes.restype = sz
+    lib.fmoe_route.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.fmoe_prune.argtypes = [vp, C.POINTER(FmoePruneParams), vp, vp, vp, i32, i32, vp, vp, vp, vp,
+                               vp, vp, vp, sz, vp]
+    lib.fmoe_permute.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.fmoe_expert_ffn.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fmoe_combine.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.fmoe_layer_forward.argtypes = [vp, C.POINTER(FmoePruneParams), vp, vp, vp, i32, i32, vp,
+                                       C.c_int, vp, vp, vp, vp, vp, sz, vp]
+    lib.fmoe_profile_enable.argtypes = [vp, C.c_int]
+    lib.fmoe_profile_slots.argtypes = []
+    lib.fmoe_profile_name.argtypes = [C.c_int]
+    lib.fmoe_profile_name.restype = C.c_char_p
+    lib.fmoe_profile_read.argtypes = [vp, C.POINTER(C.c_float)]
+    for name in EXPORTS:
+        if name not in ("fmoe_version", "fmoe_last_error", "fmoe_destroy", "fmoe_workspace_bytes",
+                        "fmoe_profile_name"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise FmoeError(rc, load().fmoe_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_contiguous()
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def prune_params(retention=1.0, window=1, alpha=1.0, gamma=0.0, sim_mode=0, prune_mode=1):
+    return FmoePruneParams(float(retention), int(window), float(alpha), float(gamma), int(sim_mode),
+                           int(prune_mode))
+
+
+class FMoE:
+    """One MoE layer shape on one GPU.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, *, d_model, n_experts, d_ffn, k_text, k_visual, dtype, n_shared=0,
+                 d_ffn_shared=0, renormalize=True, device=0):
+        self.lib = load()
+        self.torch_dtype = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+        self.cfg = FmoeConfig(d_model, n_experts, d_ffn, n_shared, d_ffn_shared, k_text, k_visual,
+                              int(bool(renormalize)), FMOE_BF16 if dtype == "bf16" else FMOE_F32)
+        self.device = torch.device("cuda", device)
+        self._ctx = C.c_void_p()
+        _check(self.lib.fmoe_create(C.byref(self._ctx), C.byref(self.cfg), device))
+        self._weights = None
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "_ctx", None) and self._ctx.value:
+            self.lib.fmoe_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- shape helpers
+    @property
+    def kmax(self):
+        return max(self.cfg.k_text, self.cfg.k_visual)
+
+    @property
+    def E(self):
+        return self.cfg.n_experts
+
+    @property
+    def d(self):
+        return self.cfg.d_model
+
+    def set_topk(self, k_text, k_visual):
+        _check(self.lib.fmoe_set_topk(self._ctx, k_text, k_visual))
+        self.cfg.k_text, self.cfg.k_visual = k_text, k_visual
+
+    def set_weights(self, router_w, router_bias, w_gate, w_up, w_down, ws_gate=None, ws_up=None,
+                    ws_down=None):
+        self._weights = (router_w, router_bias, w_gate, w_up, w_down, ws_gate, ws_up, ws_down)
+        _check(self.lib.fmoe_set_weights(self._ctx, *[_ptr(t) for t in self._weights], _stream()))
+
+    def workspace_bytes(self, max_tokens, max_seqs=1):
+        return int(self.lib.fmoe_workspace_bytes(self._ctx, max_tokens, max_seqs))
+
+    def workspace(self, max_tokens, max_seqs=1):
+        need = self.workspace_bytes(max_tokens, max_seqs)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def _i32(self, *shape):
+        return torch.empty(shape, dtype=torch.int32, device=self.device)
+
+    def _f32(self, *shape):
+        return torch.empty(shape, dtype=torch.float32, device=self.device)
+
+    # ---- instrumentation
+    def profile_enable(self, on=True):
+        _check(self.lib.fmoe_profile_enable(self._ctx, int(bool(on))))
+
+    def profile_read(self):
+        """{kernel name: milliseconds} for the kernels the last hot call launched."""
+        n = self.lib.fmoe_profile_slots()
+        ms = (C.c_float * n)()
+        _check(self.lib.fmoe_profile_read(self._ctx, ms))
+        return {self.lib.fmoe_profile_name(i).decode(): float(ms[i]) for i in range(n) if ms[i] >= 0}
+
+    # ---- the entry points
+    def route(self, x, is_visual, want_probs=True):
+        T = x.shape[0]
+        K = max(self.kmax, 1)
+        probs = self._f32(T, self.E) if want_probs else None
+        idx, gate = self._i32(T, K), self._f32(T, K)
+        _check(self.lib.fmoe_route(self._ctx, _ptr(x), _ptr(is_visual), T, _ptr(probs), _ptr(idx),
+                                   _ptr(gate), _stream()))
+        return probs, idx[:, :self.kmax], gate[:, :self.kmax]
+
+    def prune(self, params, probs, is_visual, cu_seqlens, attn=None, want_scores=False):
+        T, B = probs.shape[0], cu_seqlens.shape[0] - 1
+        kept, new_cu = self._i32(max(T, 1)), self._i32(B + 1)
+        scores = self._f32(max(T, 1)) if want_scores else None
+        ws = self.workspace(T, B)
+        _check(self.lib.fmoe_prune(self._ctx, C.byref(params), _ptr(probs), _ptr(is_visual),
+                                   _ptr(cu_seqlens), B, T, _ptr(attn), None, _ptr(kept), _ptr(new_cu),
+                                   _ptr(scores), None, _ptr(ws), ws.numel(), _stream()))
+        return kept, new_cu, scores
+
+    def permute(self, topk_idx, kept_idx, n_kept, n_kept_dev=None):
+        K = max(self.kmax, 1)
+        offs, perm, inv = self._i32(self.E + 1), self._i32(max(n_kept * K, 1)), self._i32(max(n_kept, 1), K)
+        ws = self.workspace(n_kept, 1)
+        _check(self.lib.fmoe_permute(self._ctx, _ptr(topk_idx), _ptr(kept_idx), n_kept, _ptr(n_kept_dev),
+                                     _ptr(offs), _ptr(perm), _ptr(inv), _ptr(ws), ws.numel(), _stream()))
+        return offs, perm, inv
+
+    def expert_ffn(self, x, kept_idx, n_kept, expert_offsets, perm_src, n_kept_dev=None):
+        K = max(self.kmax, 1)
+        y = torch.empty((max(n_kept * K, 1), self.d), dtype=self.torch_dtype, device=self.device)
+        ysh = None
+        if self.cfg.n_shared > 0:
+            ysh = torch.empty((max(n_kept, 1), self.d), dtype=self.torch_dtype, device=self.device)
+        ws = self.workspace(n_kept, 1)
+        _check(self.lib.fmoe_expert_ffn(self._ctx, _ptr(x), _ptr(kept_idx), n_kept, _ptr(n_kept_dev),
+                                        _ptr(expert_offsets), _ptr(perm_src), _ptr(y), _ptr(ysh),
+                                        _ptr(ws), ws.numel(), _stream()))
+        return y, ysh
+
+    def combine(self, y, y_shared, inv_perm, topk_gate, kept_idx, n_kept, residual=None,
+                n_kept_dev=None):
+        out = torch.empty((max(n_kept, 1), self.d), dtype=self.torch_dtype, device=self.device)
+        _check(self.lib.fmoe_combine(self._ctx, _ptr(y), _ptr(y_shared), _ptr(inv_perm),
+                                     _ptr(topk_gate), _ptr(kept_idx), n_kept, _ptr(n_kept_dev),
+                                     _ptr(residual), _ptr(out), _stream()))
+        return out
+
+    def layer_forward(self, x, is_visual, cu_seqlens, params=None, attn=None, add_residual=False,
+                      out=None, kept_idx=None, new_cu=None, is_visual_out=None, want_mask=False):
+        """Enqueues the whole layer; returns (out [T cap, d], kept_idx [T cap], new_cu_seqlens
+        [B+1], is_visual_out or None).  new_cu_seqlens[-1] is T' (on the device)."""
+        T, B = x.shape[0], cu_seqlens.shape[0] - 1
+        if out is None:
+            out = torch.empty((max(T, 1), self.d), dtype=self.torch_dtype, device=self.device)
+        if kept_idx is None:
+            kept_idx = self._i32(max(T, 1))
+        if new_cu is None:
+            new_cu = self._i32(B + 1)
+        if is_visual_out is None and want_mask:
+            is_visual_out = torch.empty(max(T, 1), dtype=torch.uint8, device=self.device)
+        ws = self.workspace(T, B)
+        _check(self.lib.fmoe_layer_forward(self._ctx, C.byref(params) if params is not None else None,
+                                           _ptr(x), _ptr(is_visual), _ptr(cu_seqlens), B, T, _ptr(attn),
+                                           int(bool(add_residual)), _ptr(out), _ptr(kept_idx),
+                                           _ptr(new_cu), _ptr(is_visual_out), _ptr(ws), ws.numel(),
+                                           _stream()))
+        return out, kept_idx, new_cu, is_visual_out

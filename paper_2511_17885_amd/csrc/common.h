@@ -1,0 +1,135 @@
+// Internal declarations shared by the library's translation units (host side + device helpers).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fmoe.h"
+
+#define FMOE_MAX_EXPERTS 256
+#define FMOE_MAX_TOPK 16
+#define FMOE_MAX_WINDOW 64
+#define FMOE_PERM_BLOCK 256   // kept positions per block in the permutation kernels
+#define FMOE_TILE_M 64        // rows per grouped-GEMM tile (tile list granularity)
+
+// ---- optional per-kernel timing (instrumentation; off by default)
+enum fmoe_kernel_slot {
+  SLOT_ROUTE = 0, SLOT_ORDINALS, SLOT_SCORES, SLOT_SELECT, SLOT_COMPACT, SLOT_PERM_COUNT,
+  SLOT_PERM_SCAN, SLOT_PERM_SCATTER, SLOT_TILES, SLOT_GEMM1, SLOT_GEMM2, SLOT_SH_TILES,
+  SLOT_SH_GEMM1, SLOT_SH_GEMM2, SLOT_COMBINE, SLOT_COUNT
+};
+struct fmoe_prof {
+  bool on;
+  hipEvent_t beg[SLOT_COUNT], end[SLOT_COUNT];
+  bool used[SLOT_COUNT];
+};
+
+struct fmoe_ctx {
+  fmoe_config cfg;
+  int device;
+  int kmax;
+  const void* router_w;      // caller's [E,H] in dtype
+  const float* router_w32;   // fp32 view used by the router (== router_w for fp32 contexts)
+  float* router_w32_owned;   // private widened copy for bf16 contexts (or nullptr)
+  const float* router_bias;
+  const void *w_gate, *w_up, *w_down;
+  const void *ws_gate, *ws_up, *ws_down;
+  bool weights_set;
+  fmoe_prof* prof;           // nullptr unless fmoe_profile_enable was called
+};
+
+// Brackets one kernel launch with events when profiling is on (host-side cost only then).
+struct fmoe_prof_scope {
+  fmoe_prof* p; int slot; hipStream_t s;
+  fmoe_prof_scope(const fmoe_ctx* ctx, int slot_, hipStream_t s_) : p(ctx->prof), slot(slot_), s(s_) {
+    if (p && p->on) { (void)hipEventRecord(p->beg[slot], s); } else { p = nullptr; }
+  }
+  ~fmoe_prof_scope() {
+    if (p) { (void)hipEventRecord(p->end[slot], s); p->used[slot] = true; }
+  }
+};
+
+// ---- error reporting (api.cpp)
+int fmoe_fail(int code, const char* fmt, ...);
+#define FMOE_HIP_CHECK(expr)                                                              \
+  do {                                                                                    \
+    hipError_t _e = (expr);                                                               \
+    if (_e != hipSuccess)                                                                 \
+      return fmoe_fail(FMOE_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(_e));      \
+  } while (0)
+
+// ---- workspace layout: one carve-up used by every entry point
+struct fmoe_ws_layout {
+  size_t probs, topk_idx, topk_gate;            // layer_forward intermediates
+  size_t vis_tok, vis_ord, seq_nv;              // prune
+  size_t win_s, win_a, drop_from, keep_prefix;  // prune
+  size_t slot_rank, blk_count;                  // permute
+  size_t expert_offsets, perm_src, inv_perm;    // layer_forward intermediates
+  size_t tiles, tile_count;                     // grouped GEMM tile list
+  size_t h, h_shared, y, y_shared;              // FFN intermediates
+  size_t total;
+};
+fmoe_ws_layout fmoe_layout(const fmoe_ctx* ctx, int32_t max_tokens, int32_t max_seqs);
+
+struct fmoe_tile {  // one M-tile of the grouped GEMM
+  int32_t group;    // expert id
+  int32_t row0;     // first row (in the permuted row space)
+  int32_t rows;     // valid rows in the tile (1..FMOE_TILE_M)
+  int32_t pad;
+};
+
+// ---- kernel launchers (each returns a fmoe_status; all work goes to `stream`)
+int launch_widen_bf16(const void* src, float* dst, size_t n, hipStream_t stream);
+
+int launch_route(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int T, float* probs,
+                 int32_t* topk_idx, float* topk_gate, hipStream_t stream);
+
+int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* probs,
+                 const uint8_t* is_visual, const int32_t* cu_seqlens, int B, int T,
+                 const float* attn, int32_t* kept_idx, int32_t* new_cu_seqlens, float* scores_out,
+                 uint8_t* is_visual_out, void* ws, const fmoe_ws_layout& L, hipStream_t stream);
+
+int launch_identity_kept(const uint8_t* is_visual, const int32_t* cu_seqlens, int B, int T,
+                         int32_t* kept_idx, int32_t* new_cu_seqlens, uint8_t* is_visual_out,
+                         hipStream_t stream);
+
+int launch_permute(const fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* kept_idx, int n_cap,
+                   const int32_t* n_dev, int32_t* expert_offsets, int32_t* perm_src,
+                   int32_t* inv_perm, void* ws, const fmoe_ws_layout& L, hipStream_t stream);
+
+int launch_expert_ffn(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int n_cap,
+                      const int32_t* n_dev, const int32_t* expert_offsets, const int32_t* perm_src,
+                      void* y, void* y_shared, void* ws, const fmoe_ws_layout& L,
+                      hipStream_t stream);
+
+int launch_combine(const fmoe_ctx* ctx, const void* y, const void* y_shared, const int32_t* inv_perm,
+                   const float* topk_gate, const int32_t* kept_idx, int n_cap, const int32_t* n_dev,
+                   const void* residual, void* out, hipStream_t stream);
+
+// ---- device helpers
+#if defined(__HIPCC__)
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even; inputs are finite in this library's data paths
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+// number of valid entries: the device-side count if given (clamped to the capacity), else cap
+__device__ __forceinline__ int resolve_count(int cap, const int32_t* n_dev) {
+  if (n_dev == nullptr) return cap;
+  int n = *n_dev;
+  return n < 0 ? 0 : (n > cap ? cap : n);
+}
+#endif

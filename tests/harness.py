@@ -1,0 +1,60 @@
+"""Shared helpers for the GPU parity tests: move a seeded workload to the device, build the
+library context for it, and error metrics.  No method arithmetic lives here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2511_17885_amd import binding
+from paper_2511_17885_amd import workloads as W
+
+TOL = {W.F32: 1e-5, W.BF16: 2e-2}   # max-norm relative error bound per storage dtype
+
+
+def dev(a, dtype=None):
+    if a is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.contiguous()
+
+
+def torch_dtype(wl):
+    return torch.bfloat16 if wl.dtype == W.BF16 else torch.float32
+
+
+def make_layer(wl, layer=0, k_text=None, k_visual=None, renormalize=True):
+    lw = wl.layers[layer]
+    td = torch_dtype(wl)
+    m = binding.FMoE(d_model=wl.d, n_experts=wl.E, d_ffn=wl.F, n_shared=wl.n_shared,
+                     d_ffn_shared=wl.F_shared if wl.n_shared else 0,
+                     k_text=wl.k_text if k_text is None else k_text,
+                     k_visual=wl.k_visual if k_visual is None else k_visual,
+                     dtype=wl.dtype, renormalize=renormalize)
+    m.set_weights(dev(lw.router_w, td), dev(lw.router_bias), dev(lw.w_gate, td), dev(lw.w_up, td),
+                  dev(lw.w_down, td), dev(lw.ws_gate, td), dev(lw.ws_up, td), dev(lw.ws_down, td))
+    return m
+
+
+def inputs(wl):
+    return dev(wl.x, torch_dtype(wl)), dev(wl.is_visual), dev(wl.cu_seqlens)
+
+
+def host(t):
+    if t is None:
+        return None
+    if t.dtype == torch.bfloat16:
+        t = t.float()
+    return t.detach().cpu().numpy()
+
+
+def max_rel_err(got, ref):
+    """max |got - ref| / max |ref| over the tensor (element-wise relative error is meaningless on
+    sums that cancel)."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    scale = np.abs(ref).max()
+    if scale == 0:
+        return float(np.abs(got).max())
+    return float(np.abs(got - ref).max() / scale)

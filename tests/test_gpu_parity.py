@@ -1,0 +1,318 @@
+"""GPU parity: every entry point of libfmoe.so, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Expert ids, probabilities, window scores, kept set and permutation
+must match bit for bit; FFN / combine outputs within the max-norm relative tolerance of the
+storage dtype (1e-5 fp32, 2e-2 bf16)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_17885_amd import binding
+from paper_2511_17885_amd import workloads as W
+from harness import TOL, dev, host, inputs, make_layer, max_rel_err, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(seed, **kw):
+    base = dict(T_v=[40], T_t=[9], d=64, E=8, F=32, k_text=2, k_visual=1, retention=0.5, window=3,
+                dtype=W.F32, n_shared=0, F_shared=None, bias_std=0.0, n_components=0, interleave=False)
+    base.update(kw)
+    return pytest.param(seed, base, id=f"s{seed}-" + "-".join(f"{k}{v}" for k, v in kw.items()
+                                                             if k not in ("T_v", "T_t")))
+
+
+SMALL = [
+    _case(100),
+    _case(101, T_v=[37, 5, 0, 14], T_t=[4, 0, 6, 3], E=12, k_text=4, k_visual=2, interleave=True),
+    _case(102, T_v=[129], T_t=[31], d=200, E=65, F=72, k_text=6, k_visual=3, bias_std=1.0, window=5),
+    _case(103, T_v=[61, 70], T_t=[3, 2], d=128, E=128, F=64, k_text=8, k_visual=4, dtype=W.BF16,
+          bias_std=1.5, n_components=6, window=5),
+    _case(104, T_v=[90], T_t=[10], d=96, E=256, F=40, k_text=16, k_visual=7, dtype=W.BF16, window=4),
+    _case(105, T_v=[50], T_t=[14], d=64, E=6, F=48, k_text=3, k_visual=0, n_shared=2, F_shared=24,
+          dtype=W.BF16, retention=0.25),
+    _case(106, T_v=[0, 0], T_t=[9, 4], E=5, k_text=5, k_visual=2),                      # all text
+    _case(107, T_v=[33, 2], T_t=[0, 0], E=7, k_text=1, k_visual=1, retention=0.75, window=4),  # all visual, N_v < W
+    _case(108, T_v=[300, 77, 1], T_t=[20, 1, 1], d=256, E=64, F=96, k_text=6, k_visual=3, dtype=W.BF16,
+          n_shared=2, F_shared=64, bias_std=1.0, n_components=12, retention=0.5, window=3),
+    _case(109, T_v=[45], T_t=[5], E=9, k_text=3, k_visual=3, retention=0.9, window=1),
+]
+
+
+def _wl(seed, kw):
+    return W.small_random(seed, **kw)
+
+
+def _oracle(wl, **over):
+    kw = dict(k_text=wl.k_text, k_visual=wl.k_visual, is_bf16=wl.dtype == W.BF16,
+              retention=wl.retention, window=wl.window)
+    kw.update(over)
+    return oracle.layer_forward(wl.x, wl.is_visual, wl.cu_seqlens, wl.weights, **kw)
+
+
+# ---------------------------------------------------------------- route
+@pytest.mark.parametrize("seed,kw", SMALL)
+def test_route(seed, kw):
+    wl = _wl(seed, kw)
+    if wl.T == 0:
+        pytest.skip("empty")
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    probs, idx, gate = m.route(x, vis)
+    torch.cuda.synchronize()
+    o_probs, o_idx, o_gate = oracle.route(wl.x, wl.is_visual, wl.weights.router_w,
+                                          wl.weights.router_bias, wl.k_text, wl.k_visual)
+    assert np.array_equal(host(idx), o_idx)
+    assert np.array_equal(host(probs), o_probs)            # same fixed-order fp32 arithmetic
+    assert np.abs(host(gate) - o_gate).max() <= 1e-6
+
+
+def test_route_ties_duplicated_router_rows():
+    wl = W.small_random(110, T_v=[20], T_t=[12], d=64, E=10, F=32, k_text=10, k_visual=4,
+                        retention=0.5, window=3)
+    wl.weights.router_w[7] = wl.weights.router_w[2]
+    wl.weights.router_w[9] = wl.weights.router_w[0]
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    _, idx, gate = m.route(x, vis)
+    o_probs, o_idx, o_gate = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, None, 10, 4)
+    assert np.array_equal(host(idx), o_idx)
+    # all-equal logits: the lowest indices win, in order
+    wl.weights.router_w[:] = 0
+    m = make_layer(wl)
+    _, idx, gate = m.route(x, vis)
+    idx = host(idx)
+    for t in range(wl.T):
+        k = 4 if wl.is_visual[t] else 10
+        assert list(idx[t, :k]) == list(range(k)) and np.all(idx[t, k:] == -1)
+
+
+def test_route_renormalize_off_and_set_topk():
+    wl = W.small_random(111, T_v=[30], T_t=[10], d=64, E=16, F=32, k_text=4, k_visual=2,
+                        retention=0.5, window=3, bias_std=1.0)
+    m = make_layer(wl, renormalize=False)
+    x, vis, cu = inputs(wl)
+    _, idx, gate = m.route(x, vis)
+    o = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias, 4, 2, renormalize=False)
+    assert np.array_equal(host(idx), o[1]) and np.array_equal(host(gate), o[2])
+    m2 = make_layer(wl)
+    m2.set_topk(6, 6)                                       # the per-layer switch of Sec. 3.1
+    _, idx, gate = m2.route(x, vis)
+    o = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias, 6, 6)
+    assert np.array_equal(host(idx), o[1]) and np.abs(host(gate) - o[2]).max() <= 1e-6
+
+
+# ---------------------------------------------------------------- prune
+@pytest.mark.parametrize("seed,kw", SMALL)
+@pytest.mark.parametrize("sim_mode", [0, 1])
+def test_prune(seed, kw, sim_mode):
+    wl = _wl(seed, kw)
+    o_probs, _, _ = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias,
+                                 wl.k_text, wl.k_visual)
+    o_kept, o_cu, o_scores = oracle.prune(o_probs, wl.is_visual, wl.cu_seqlens, wl.retention, wl.window,
+                                          sim_mode=sim_mode)
+    m = make_layer(wl)
+    pp = binding.prune_params(retention=wl.retention, window=wl.window, sim_mode=sim_mode)
+    kept, new_cu, scores = m.prune(pp, dev(o_probs), dev(wl.is_visual), dev(wl.cu_seqlens), want_scores=True)
+    torch.cuda.synchronize()
+    new_cu = host(new_cu)
+    assert np.array_equal(new_cu, o_cu)
+    assert np.array_equal(host(kept)[:new_cu[-1]], o_kept)
+    # scores live at slot cu[b] + i
+    scores = host(scores)
+    got = []
+    for b in range(wl.B):
+        s, e = wl.cu_seqlens[b], wl.cu_seqlens[b + 1]
+        nv = int(wl.is_visual[s:e].sum())
+        got.append(scores[s:s + (nv + wl.window - 1) // wl.window])
+    got = np.concatenate(got) if got else np.zeros(0, np.float32)
+    assert np.array_equal(got, o_scores)
+
+
+@pytest.mark.parametrize("alpha", [0.3, 0.6, 1.0])
+def test_prune_with_attention_importance(alpha):
+    wl = W.small_random(112, T_v=[75, 31], T_t=[6, 5], d=64, E=24, F=32, k_text=4, k_visual=2,
+                        retention=0.5, window=5, n_components=5, interleave=True)
+    rng = np.random.default_rng(5)
+    attn = rng.random(wl.T).astype(np.float32) ** 2
+    o_probs, _, _ = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, None, 4, 2)
+    o_kept, o_cu, _ = oracle.prune(o_probs, wl.is_visual, wl.cu_seqlens, 0.5, 5, alpha=alpha, attn=attn)
+    m = make_layer(wl)
+    pp = binding.prune_params(retention=0.5, window=5, alpha=alpha)
+    kept, new_cu, _ = m.prune(pp, dev(o_probs), dev(wl.is_visual), dev(wl.cu_seqlens), attn=dev(attn))
+    new_cu = host(new_cu)
+    assert np.array_equal(new_cu, o_cu) and np.array_equal(host(kept)[:new_cu[-1]], o_kept)
+
+
+def test_prune_tied_scores_identical_windows():
+    # windows made of identical rows all score exactly alike: the index decides
+    E, Wn, n = 16, 3, 20
+    row = np.random.default_rng(6).random(E).astype(np.float32)
+    row /= row.sum()
+    probs = np.tile(row, (Wn * n, 1))
+    vis = np.ones(Wn * n, np.uint8)
+    cu = np.array([0, Wn * n], np.int32)
+    o_kept, o_cu, o_sc = oracle.prune(probs, vis, cu, 0.5, Wn)
+    assert len(set(o_sc.tolist())) == 1
+    wl = W.small_random(113, T_v=[Wn * n], T_t=[0], d=64, E=E, F=32, k_text=2, k_visual=1,
+                        retention=0.5, window=Wn)
+    m = make_layer(wl)
+    kept, new_cu, _ = m.prune(binding.prune_params(retention=0.5, window=Wn), dev(probs), dev(vis), dev(cu))
+    new_cu = host(new_cu)
+    assert np.array_equal(new_cu, o_cu) and np.array_equal(host(kept)[:new_cu[-1]], o_kept)
+    assert list(o_kept) == list(range(Wn * n // 2, Wn * n))     # the first half of the windows goes
+
+
+# ---------------------------------------------------------------- permute
+@pytest.mark.parametrize("seed,kw", SMALL)
+def test_permute(seed, kw):
+    wl = _wl(seed, kw)
+    o = _oracle(wl, ffn=False)
+    m = make_layer(wl)
+    for kept in (o["kept_idx"], None):
+        n = wl.T if kept is None else len(kept)
+        if n == 0:
+            continue
+        o_offs, o_perm, o_inv = oracle.permute(o["topk_idx"], kept, wl.E)
+        offs, perm, inv = m.permute(dev(o["topk_idx"]), dev(kept), n)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(offs), o_offs)
+        assert np.array_equal(host(perm)[:o_offs[-1]], o_perm)
+        assert np.array_equal(host(inv)[:n], o_inv)
+
+
+def test_permute_many_blocks_and_device_count():
+    wl = W.small_random(114, T_v=[1500], T_t=[100], d=64, E=33, F=32, k_text=5, k_visual=2,
+                        retention=0.5, window=3, bias_std=2.0)
+    o = _oracle(wl, ffn=False)
+    m = make_layer(wl)
+    kept = o["kept_idx"]
+    n = len(kept)
+    kept_cap = np.concatenate([kept, np.zeros(wl.T - n, np.int32)])
+    n_dev = dev(np.array([n], np.int32))
+    offs, perm, inv = m.permute(dev(o["topk_idx"]), dev(kept_cap), wl.T, n_kept_dev=n_dev)
+    assert np.array_equal(host(offs), o["expert_offsets"])
+    assert np.array_equal(host(perm)[:o["expert_offsets"][-1]], o["perm_src"])
+    assert np.array_equal(host(inv)[:n], o["inv_perm"])
+
+
+# ---------------------------------------------------------------- experts + combine
+@pytest.mark.parametrize("seed,kw", SMALL)
+def test_expert_ffn_and_combine(seed, kw):
+    wl = _wl(seed, kw)
+    o = _oracle(wl, add_residual=True)
+    n = len(o["kept_idx"])
+    if n == 0:
+        pytest.skip("empty")
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    kept = dev(o["kept_idx"])
+    y, ysh = m.expert_ffn(x, kept, n, dev(o["expert_offsets"]), dev(o["perm_src"]))
+    torch.cuda.synchronize()
+    M = int(o["expert_offsets"][-1])
+    tol = TOL[wl.dtype]
+    if M > 0:
+        assert max_rel_err(host(y)[:M], o["y"]) <= tol
+    if wl.n_shared:
+        assert max_rel_err(host(ysh)[:n], o["y_shared"]) <= tol
+    out = m.combine(y, ysh, dev(o["inv_perm"]), dev(o["topk_gate"]), kept, n, residual=x)
+    assert max_rel_err(host(out)[:n], o["out_f64"]) <= tol
+
+
+# ---------------------------------------------------------------- whole layer
+@pytest.mark.parametrize("seed,kw", SMALL)
+def test_layer_forward(seed, kw):
+    wl = _wl(seed, kw)
+    o = _oracle(wl, add_residual=True)
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    pp = binding.prune_params(retention=wl.retention, window=wl.window)
+    out, kept, new_cu, vis_out = m.layer_forward(x, vis, cu, pp, add_residual=True, want_mask=True)
+    torch.cuda.synchronize()
+    new_cu = host(new_cu)
+    n = int(new_cu[-1])
+    assert np.array_equal(new_cu, o["new_cu_seqlens"])
+    assert np.array_equal(host(kept)[:n], o["kept_idx"])
+    assert np.array_equal(host(vis_out)[:n], wl.is_visual[o["kept_idx"]])
+    if n:
+        assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
+    # determinism: a second run gives identical bits
+    out2, kept2, _, _ = m.layer_forward(x, vis, cu, pp, add_residual=True)
+    assert torch.equal(out[:n], out2[:n]) and torch.equal(kept[:n], kept2[:n])
+
+
+def test_layer_forward_equals_chained_calls_and_no_prune_path():
+    wl = W.small_random(115, T_v=[200, 90], T_t=[17, 8], d=128, E=32, F=64, k_text=4, k_visual=2,
+                        retention=0.5, window=3, dtype=W.BF16, n_shared=1, F_shared=32, bias_std=1.0,
+                        n_components=8)
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    pp = binding.prune_params(retention=0.5, window=3)
+    out, kept, new_cu, _ = m.layer_forward(x, vis, cu, pp)
+    n = int(host(new_cu)[-1])
+    probs, idx, gate = m.route(x, vis)
+    kept2, new_cu2, _ = m.prune(pp, probs, vis, cu)
+    assert torch.equal(new_cu, new_cu2) and torch.equal(kept[:n], kept2[:n])
+    offs, perm, inv = m.permute(idx.contiguous(), kept2, n)
+    y, ysh = m.expert_ffn(x, kept2, n, offs, perm)
+    out2 = m.combine(y, ysh, inv, gate.contiguous(), kept2, n)
+    assert torch.equal(out[:n], out2[:n])
+    # params = None and retention = 1 both mean: keep everything
+    for p in (None, binding.prune_params(retention=1.0, window=3)):
+        out3, kept3, new_cu3, _ = m.layer_forward(x, vis, cu, p)
+        assert np.array_equal(host(new_cu3), wl.cu_seqlens)
+        assert np.array_equal(host(kept3), np.arange(wl.T))
+        o = _oracle(wl, retention=1.0)
+        assert max_rel_err(host(out3), o["out_f64"]) <= TOL[wl.dtype]
+
+
+# ---------------------------------------------------------------- the benchmark configurations
+def _check_config(wl, sample=None, seed=0):
+    """Decisions on every token; outputs on every kept token, or on a sample of them evaluated
+    one by one with Eq.4 when the whole layer is too slow for the CPU."""
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    pp = binding.prune_params(retention=wl.retention, window=wl.window)
+    out, kept, new_cu, _ = m.layer_forward(x, vis, cu, pp)
+    torch.cuda.synchronize()
+    is_bf16 = wl.dtype == W.BF16
+    o = _oracle(wl, ffn=sample is None)
+    new_cu = host(new_cu)
+    n = int(new_cu[-1])
+    assert np.array_equal(new_cu, o["new_cu_seqlens"])
+    assert np.array_equal(host(kept)[:n], o["kept_idx"])
+    probs, idx, gate = m.route(x, vis)
+    assert np.array_equal(host(idx), o["topk_idx"])
+    assert np.array_equal(host(probs), o["probs"])
+    offs, perm, inv = m.permute(idx.contiguous(), kept, n)
+    assert np.array_equal(host(offs), o["expert_offsets"])
+    assert np.array_equal(host(perm)[:o["expert_offsets"][-1]], o["perm_src"])
+    assert np.array_equal(host(inv)[:n], o["inv_perm"])
+    got = host(out)[:n]
+    if sample is None:
+        assert max_rel_err(got, o["out_f64"]) <= TOL[wl.dtype]
+    else:
+        rng = np.random.default_rng(seed)
+        pos = np.sort(rng.choice(n, size=min(sample, n), replace=False))
+        _, ref = oracle.token_outputs(wl.x, o["kept_idx"][pos], o["topk_idx"], o["topk_gate"],
+                                      wl.weights, is_bf16)
+        scale = np.abs(ref).max()
+        assert np.abs(got[pos] - ref).max() / scale <= TOL[wl.dtype]
+        assert np.isfinite(got).all()
+    return n
+
+
+def test_config1_tiny_fp32():
+    assert _check_config(W.config1()) == 52
+
+
+def test_config2_dsvl2_tiny():
+    assert _check_config(W.config2()) == 768 + 64
+
+
+def test_config3_dsvl2_small_half_retention_sampled():
+    assert _check_config(W.config3(0.5), sample=48) == 1920 + 256
+
+
+def test_config4_internvl35_sampled():
+    assert _check_config(W.config4(), sample=48) == 3968 + 256

@@ -1,0 +1,94 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares, and
+its host-side validation returns error codes without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2511_17885_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2511_17885_amd import build
+        build.build()
+    return binding.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "fmoe.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(fmoe_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert b"gfx950" in lib.fmoe_version()
+
+
+def _cfg(**kw):
+    base = dict(d_model=64, n_experts=8, d_ffn=32, n_shared=0, d_ffn_shared=0, k_text=2, k_visual=1,
+                renormalize=1, dtype=0)
+    base.update(kw)
+    return binding.FmoeConfig(*[base[f[0]] for f in binding.FmoeConfig._fields_])
+
+
+def _create(lib, cfg):
+    ctx = C.c_void_p()
+    rc = lib.fmoe_create(C.byref(ctx), C.byref(cfg), 0)
+    return rc, ctx
+
+
+def test_create_validates_config(lib):
+    rc, ctx = _create(lib, _cfg())
+    assert rc == 0 and ctx.value
+    assert lib.fmoe_workspace_bytes(ctx, 64, 1) > 0
+    assert lib.fmoe_workspace_bytes(ctx, 4096, 8) > lib.fmoe_workspace_bytes(ctx, 64, 1)
+    lib.fmoe_destroy(ctx)
+    for bad, code in [(dict(k_visual=9), -1), (dict(k_text=-1), -1), (dict(d_model=0), -1),
+                      (dict(dtype=7), -1), (dict(n_experts=300), -5), (dict(d_model=100), -5),
+                      (dict(n_shared=1, d_ffn_shared=0), -1), (dict(n_experts=32, k_text=17), -5)]:
+        rc, ctx = _create(lib, _cfg(**bad))
+        assert rc == code, (bad, rc, lib.fmoe_last_error())
+        assert not ctx.value
+        assert lib.fmoe_last_error() != b""
+    assert lib.fmoe_create(None, C.byref(_cfg()), 0) == -2
+
+
+def test_set_topk_and_null_argument_paths(lib):
+    rc, ctx = _create(lib, _cfg())
+    assert rc == 0
+    assert lib.fmoe_set_topk(ctx, 4, 2) == 0
+    assert lib.fmoe_set_topk(ctx, 9, 2) == -1
+    # weights not set -> route refuses before any GPU work
+    assert lib.fmoe_route(ctx, None, None, 4, None, None, None, None) == -1
+    assert b"fmoe_set_weights" in lib.fmoe_last_error()
+    # set_weights: NULL required pointer, stray shared weights
+    assert lib.fmoe_set_weights(ctx, None, None, None, None, None, None, None, None, None) == -2
+    # prune argument validation (host side only)
+    pp = binding.prune_params(retention=0.5, window=3)
+    assert lib.fmoe_prune(ctx, None, None, None, None, 1, 4, None, None, None, None, None, None, None, 0, None) == -2
+    bad = binding.prune_params(retention=1.5, window=3)
+    assert lib.fmoe_prune(ctx, C.byref(bad), None, None, None, 1, 4, None, None, None, None, None, None, None, 0, None) == -1
+    bad = binding.prune_params(retention=0.5, window=0)
+    assert lib.fmoe_prune(ctx, C.byref(bad), None, None, None, 1, 4, None, None, None, None, None, None, None, 0, None) == -1
+    bad = binding.prune_params(retention=0.5, window=3, gamma=0.05)
+    assert lib.fmoe_prune(ctx, C.byref(bad), None, None, None, 1, 4, None, None, None, None, None, None, None, 0, None) == -5
+    assert lib.fmoe_prune(ctx, C.byref(pp), None, None, None, 1, 4, None, None, None, None, None, None, None, 0, None) == -2
+    # permute: missing workspace
+    dummy = C.c_void_p(0x1000)
+    assert lib.fmoe_permute(ctx, dummy, None, 8, None, dummy, dummy, dummy, None, 0, None) == -4
+    assert lib.fmoe_permute(ctx, dummy, None, -1, None, dummy, dummy, dummy, None, 0, None) == -1
+    assert lib.fmoe_permute(ctx, dummy, None, 8, None, dummy, dummy, dummy, C.c_void_p(0x10000), 16, None) == -4
+    lib.fmoe_destroy(ctx)
+    assert lib.fmoe_route(None, None, None, 4, None, None, None, None) == -2
+
+
+def test_binding_fails_loudly_without_library(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libfmoe.so")
+    with pytest.raises(RuntimeError):
+        binding.load()
