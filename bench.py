@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=30)
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="also run a plain 256 MiB device copy (scale for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives are part of it); "
@@ -113,20 +115,17 @@ def main():
     n_vis = int(wl.is_visual.sum())
     work = {
         "route_kernel": dict(bytes=T * d * es + n_vis * E * 4 + T * Kmax * 8 + E * d * 4,
-                             flops=2.0 * T * d * E, peak_tflops=VALU_F32_PEAK_TFLOPS),
+                             flops=2.0 * T * d * E, peak_tflops=MFMA_F32_PEAK_TFLOPS),
+        # one launch covers the routed experts and the shared group
         "grouped_gemm_kernel<swiglu> routed": dict(
-            bytes=touched * 2 * F * d * es + M * d * es + M * F * es, flops=4.0 * M * d * F,
+            bytes=(touched * 2 * F * d + M * d + M * F + Ns * 2 * Fs * d + n_kept * d * (1 if Ns else 0)
+                   + n_kept * Ns * Fs) * es,
+            flops=4.0 * M * d * F + 4.0 * n_kept * d * Fs * Ns,
             peak_tflops=MFMA_BF16_PEAK_TFLOPS if is_bf16 else MFMA_F32_PEAK_TFLOPS),
         "grouped_gemm_kernel<down> routed": dict(
-            bytes=touched * d * F * es + M * F * es + M * d * es, flops=2.0 * M * d * F,
-            peak_tflops=MFMA_BF16_PEAK_TFLOPS if is_bf16 else MFMA_F32_PEAK_TFLOPS),
-        "grouped_gemm_kernel<swiglu> shared": dict(
-            bytes=Ns * 2 * Fs * d * es + n_kept * d * es + n_kept * Ns * Fs * es,
-            flops=4.0 * n_kept * d * Fs * Ns,
-            peak_tflops=MFMA_BF16_PEAK_TFLOPS if is_bf16 else MFMA_F32_PEAK_TFLOPS),
-        "grouped_gemm_kernel<down> shared": dict(
-            bytes=Ns * d * Fs * es + n_kept * Ns * Fs * es + n_kept * d * es,
-            flops=2.0 * n_kept * d * Fs * Ns,
+            bytes=(touched * d * F + M * F + M * d + Ns * d * Fs + n_kept * Ns * Fs
+                   + n_kept * d * (1 if Ns else 0)) * es,
+            flops=2.0 * M * d * F + 2.0 * n_kept * d * Fs * Ns,
             peak_tflops=MFMA_BF16_PEAK_TFLOPS if is_bf16 else MFMA_F32_PEAK_TFLOPS),
         "combine_kernel": dict(bytes=M * d * es + (n_kept * d * es if Ns else 0) + n_kept * d * es
                                + n_kept * Kmax * 8, flops=2.0 * M * d, peak_tflops=VALU_F32_PEAK_TFLOPS),
@@ -156,6 +155,13 @@ def main():
                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
                     "algo_bytes_per_launch": int(work[dom]["bytes"]), "us_per_launch": round(dom_ms * 1e3, 2),
                     "mfma_frac": kernels[dom].get("compute_frac")}
+
+    if args.copy_calib:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     cpu = None
     if not args.no_cpu_baseline:

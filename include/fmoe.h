@@ -92,8 +92,9 @@ int fmoe_set_topk(fmoe_ctx* ctx, int32_t k_text, int32_t k_visual);
  * before the softmax); w_gate, w_up [E,S_m,H]; w_down [E,H,S_m]; ws_gate, ws_up
  * [N_s,S_s,H]; ws_down [N_s,H,S_s] (NULL iff N_s == 0).  An expert is the three-matrix gated
  * FFN  y = W_down (silu(W_gate x) * (W_up x))  without biases (flop model of App. E).
- * For bf16 contexts the router matrix is widened once into a private fp32 copy (the only
- * device allocation the library makes; freed by the next set_weights / destroy). */
+ * The router matrix is copied once into a private fp32 buffer laid out for the router kernel
+ * (E*H*4 bytes rounded up to 16x16 blocks; the only device allocation the library makes, on
+ * the first call, freed by fmoe_destroy); the other weights are used in place. */
 int fmoe_set_weights(fmoe_ctx* ctx, const void* router_w, const float* router_bias,
                      const void* w_gate, const void* w_up, const void* w_down,
                      const void* ws_gate, const void* ws_up, const void* ws_down, void* stream);

@@ -35,6 +35,8 @@ def lib():
         _lib.orc_sum_canon.argtypes = [_f32p, C.c_int]
         _lib.orc_dot_canon.restype = C.c_float
         _lib.orc_dot_canon.argtypes = [_f32p, _f32p, C.c_int]
+        _lib.orc_dot_seq.restype = C.c_float
+        _lib.orc_dot_seq.argtypes = [_f32p, _f32p, C.c_int]
         _lib.orc_round_store.restype = C.c_float
         _lib.orc_round_store.argtypes = [C.c_double, C.c_int]
     return _lib
@@ -75,6 +77,12 @@ def dot_canon(a, b) -> np.float32:
     a, b = _f32(a), _f32(b)
     assert a.size == b.size
     return np.float32(lib().orc_dot_canon(_p(a, _f32p), _p(b, _f32p), int(a.size)))
+
+
+def dot_seq(a, b) -> np.float32:
+    a, b = _f32(a), _f32(b)
+    assert a.size == b.size
+    return np.float32(lib().orc_dot_seq(_p(a, _f32p), _p(b, _f32p), int(a.size)))
 
 
 def round_store(v: float, is_bf16: bool) -> np.float32:

@@ -16,10 +16,13 @@
 //    activation h is rounded to the storage dtype, and the layer output is rounded once.
 //
 // Canonical arithmetic (fp32, round-to-nearest-even, no contraction except written fmaf):
+//  * dot_seq(a,b,n): the plain fp32 dot product in index order with fused multiply-add:
+//    acc = +0; for k = 0..n-1: acc = fmaf(a[k], b[k], acc).  Used for the router logits (Eq.1).
 //  * sum_canon(v[0..n)):  64 partials p[l] (l = 0..63); p[l] starts at +0 and adds v[l+64j] for
 //    j = 0,1,.. in ascending order; then for s in 32,16,8,4,2,1: p[l] <- p[l] + p[l xor s]
-//    for all l at once; the result is p[0].
-//  * dot_canon(a,b,n): same, with p[l] <- fmaf(a[l+64j], b[l+64j], p[l]).
+//    for all l at once; the result is p[0].  Used for the softmax denominator (Eq.2).
+//  * dot_canon(a,b,n): same shape as sum_canon, with p[l] <- fmaf(a[l+64j], b[l+64j], p[l]).
+//    Used for the dot products over the E routing probabilities (Eq.8-10).
 //  * exp_canon(x), x <= 0:  t = x*LOG2E; n = rint(t); r = fmaf(-n, LN2_HI, x);
 //    r = fmaf(-n, LN2_LO, r); p = degree-7 Taylor polynomial of e^r in Horner form with fmaf;
 //    result = p * 2^n, and exactly 0 when n < -125.
@@ -64,6 +67,12 @@ float dot_canon(const float* a, const float* b, int n) {
   for (int l = 0; l < 64; ++l) p[l] = 0.0f;
   for (int i = 0; i < n; ++i) p[i & 63] = std::fmaf(a[i], b[i], p[i & 63]);
   return butterfly64(p);
+}
+
+float dot_seq(const float* a, const float* b, int n) {
+  float acc = 0.0f;
+  for (int i = 0; i < n; ++i) acc = std::fmaf(a[i], b[i], acc);
+  return acc;
 }
 
 float exp_canon(float x) {
@@ -117,12 +126,12 @@ inline float round_store(double v, int is_bf16) {
 }
 
 // ---------------------------------------------------------------- Eq.1-2: logits, softmax
-// Z[e] = dot_canon(x_t, W_E[e]) (+ bias[e], one rounded add); P = exp(Z - max) / sum.
+// Z[e] = dot_seq(x_t, W_E[e]) (+ bias[e], one rounded add); P = exp(Z - max) / sum.
 void route_probs_row(const float* xt, int d, int E, const float* Wr, const float* bias,
                      float* P /*[E]*/) {
   std::vector<float> z(E), q(E);
   for (int e = 0; e < E; ++e) {
-    float v = dot_canon(xt, Wr + (size_t)e * d, d);
+    float v = dot_seq(xt, Wr + (size_t)e * d, d);
     if (bias) v = v + bias[e];
     z[e] = v;
   }
@@ -241,6 +250,7 @@ extern "C" {
 float orc_exp_canon(float x) { return exp_canon(x); }
 float orc_sum_canon(const float* v, int n) { return sum_canon(v, n); }
 float orc_dot_canon(const float* a, const float* b, int n) { return dot_canon(a, b, n); }
+float orc_dot_seq(const float* a, const float* b, int n) { return dot_seq(a, b, n); }
 float orc_round_store(double v, int is_bf16) { return round_store(v, is_bf16); }
 
 // -------- Eq.1-3, Eq.5: route every token.

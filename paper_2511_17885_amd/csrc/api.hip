@@ -1,5 +1,5 @@
 // C-ABI entry points: argument validation, workspace carve-up, kernel sequencing.
-// No entry point other than fmoe_set_weights (bf16 router copy) allocates device memory, and
+// No entry point other than fmoe_set_weights (private router copy) allocates device memory, and
 // none synchronises with the host.
 
 #include <cstdarg>
@@ -156,7 +156,7 @@ void fmoe_destroy(fmoe_ctx* ctx) {
     }
     delete ctx->prof;
   }
-  if (ctx->router_w32_owned) (void)hipFree(ctx->router_w32_owned);
+  if (ctx->router_wp) (void)hipFree(ctx->router_wp);
   delete ctx;
 }
 
@@ -190,21 +190,13 @@ int fmoe_set_weights(fmoe_ctx* ctx, const void* router_w, const float* router_bi
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_set_weights: pointer %p not 16-byte aligned", p);
   ctx->weights_set = false;
-  if (ctx->router_w32_owned) {
-    FMOE_HIP_CHECK(hipFree(ctx->router_w32_owned));
-    ctx->router_w32_owned = nullptr;
-  }
   ctx->router_w = router_w;
-  if (ctx->cfg.dtype == FMOE_BF16) {
-    const size_t n = (size_t)ctx->cfg.n_experts * ctx->cfg.d_model;
+  if (!ctx->router_wp) {
     FMOE_HIP_CHECK(hipSetDevice(ctx->device));
-    FMOE_HIP_CHECK(hipMalloc(reinterpret_cast<void**>(&ctx->router_w32_owned), n * sizeof(float)));
-    rc = launch_widen_bf16(router_w, ctx->router_w32_owned, n, static_cast<hipStream_t>(stream));
-    if (rc != FMOE_OK) return rc;
-    ctx->router_w32 = ctx->router_w32_owned;
-  } else {
-    ctx->router_w32 = static_cast<const float*>(router_w);
+    FMOE_HIP_CHECK(hipMalloc(reinterpret_cast<void**>(&ctx->router_wp), router_pack_floats(ctx) * sizeof(float)));
   }
+  rc = launch_pack_router(ctx, router_w, ctx->router_wp, static_cast<hipStream_t>(stream));
+  if (rc != FMOE_OK) return rc;
   ctx->router_bias = router_bias;
   ctx->w_gate = w_gate; ctx->w_up = w_up; ctx->w_down = w_down;
   ctx->ws_gate = ws_gate; ctx->ws_up = ws_up; ctx->ws_down = ws_down;
@@ -264,7 +256,7 @@ int fmoe_permute(fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* kept_idx
   if ((rc = check_ws(ctx, ws, ws_bytes, n_kept, 1)) != FMOE_OK) return rc;
   const fmoe_ws_layout L = fmoe_layout(ctx, n_kept, 1);
   return launch_permute(ctx, topk_idx, kept_idx, n_kept, n_kept_dev, expert_offsets, perm_src,
-                        inv_perm, ws, L, static_cast<hipStream_t>(stream));
+                        inv_perm, ws, L, false, static_cast<hipStream_t>(stream));
 }
 
 int fmoe_expert_ffn(fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int32_t n_kept,
@@ -285,7 +277,7 @@ int fmoe_expert_ffn(fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int32
   if ((rc = check_ws(ctx, ws, ws_bytes, n_kept, 1)) != FMOE_OK) return rc;
   const fmoe_ws_layout L = fmoe_layout(ctx, n_kept, 1);
   return launch_expert_ffn(ctx, x, kept_idx, n_kept, n_kept_dev, expert_offsets, perm_src, y,
-                           ctx->cfg.n_shared > 0 ? y_shared : nullptr, ws, L,
+                           ctx->cfg.n_shared > 0 ? y_shared : nullptr, ws, L, false,
                            static_cast<hipStream_t>(stream));
 }
 
@@ -351,9 +343,9 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
   }
   if (rc != FMOE_OK) return rc;
   if (T == 0) return FMOE_OK;
-  if ((rc = launch_permute(ctx, topk_idx, kept, T, n_dev, expert_offsets, perm_src, inv_perm, ws, L, s)) != FMOE_OK)
+  if ((rc = launch_permute(ctx, topk_idx, kept, T, n_dev, expert_offsets, perm_src, inv_perm, ws, L, true, s)) != FMOE_OK)
     return rc;
-  if ((rc = launch_expert_ffn(ctx, x, kept, T, n_dev, expert_offsets, perm_src, y, y_shared, ws, L, s)) != FMOE_OK)
+  if ((rc = launch_expert_ffn(ctx, x, kept, T, n_dev, expert_offsets, perm_src, y, y_shared, ws, L, true, s)) != FMOE_OK)
     return rc;
   return launch_combine(ctx, y, y_shared, inv_perm, topk_gate, kept, T, n_dev, add_residual ? x : nullptr,
                         out, s);

@@ -30,8 +30,7 @@ struct fmoe_ctx {
   int device;
   int kmax;
   const void* router_w;      // caller's [E,H] in dtype
-  const float* router_w32;   // fp32 view used by the router (== router_w for fp32 contexts)
-  float* router_w32_owned;   // private widened copy for bf16 contexts (or nullptr)
+  float* router_wp;          // private fp32 copy of router_w in the router kernel's operand order
   const float* router_bias;
   const void *w_gate, *w_up, *w_down;
   const void *ws_gate, *ws_up, *ws_down;
@@ -80,7 +79,8 @@ struct fmoe_tile {  // one M-tile of the grouped GEMM
 };
 
 // ---- kernel launchers (each returns a fmoe_status; all work goes to `stream`)
-int launch_widen_bf16(const void* src, float* dst, size_t n, hipStream_t stream);
+size_t router_pack_floats(const fmoe_ctx* ctx);
+int launch_pack_router(const fmoe_ctx* ctx, const void* router_w, float* wp, hipStream_t stream);
 
 int launch_route(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int T, float* probs,
                  int32_t* topk_idx, float* topk_gate, hipStream_t stream);
@@ -94,13 +94,18 @@ int launch_identity_kept(const uint8_t* is_visual, const int32_t* cu_seqlens, in
                          int32_t* kept_idx, int32_t* new_cu_seqlens, uint8_t* is_visual_out,
                          hipStream_t stream);
 
+// build_tiles: also write the grouped-GEMM tile list for fmoe_tile_rows(ctx, n_cap)-row tiles
 int launch_permute(const fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* kept_idx, int n_cap,
                    const int32_t* n_dev, int32_t* expert_offsets, int32_t* perm_src,
-                   int32_t* inv_perm, void* ws, const fmoe_ws_layout& L, hipStream_t stream);
+                   int32_t* inv_perm, void* ws, const fmoe_ws_layout& L, bool build_tiles,
+                   hipStream_t stream);
+
+int fmoe_tile_rows(const fmoe_ctx* ctx, int n_cap);
+int fmoe_tile_cap(const fmoe_ctx* ctx, int n_cap);
 
 int launch_expert_ffn(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int n_cap,
                       const int32_t* n_dev, const int32_t* expert_offsets, const int32_t* perm_src,
-                      void* y, void* y_shared, void* ws, const fmoe_ws_layout& L,
+                      void* y, void* y_shared, void* ws, const fmoe_ws_layout& L, bool tiles_ready,
                       hipStream_t stream);
 
 int launch_combine(const fmoe_ctx* ctx, const void* y, const void* y_shared, const int32_t* inv_perm,

@@ -9,6 +9,7 @@
 // is expert_offset + block_base + rank.
 
 #include "common.h"
+#include "tiles.h"
 
 namespace {
 
@@ -70,8 +71,12 @@ __global__ __launch_bounds__(PB) void permute_count_kernel(
 // bases in place), then the per-expert totals are scanned into expert_offsets.
 __global__ __launch_bounds__(256) void permute_scan_kernel(int n_cap, const int32_t* __restrict__ n_dev,
                                                            int E, int32_t* __restrict__ blk_count,
-                                                           int32_t* __restrict__ expert_offsets) {
+                                                           int32_t* __restrict__ expert_offsets,
+                                                           int tile_rows, int has_shared, int row_cap,
+                                                           int tile_cap, fmoe_tile* __restrict__ tiles,
+                                                           int32_t* __restrict__ tile_count) {
   __shared__ int total[FMOE_MAX_EXPERTS];
+  __shared__ int scratch[FMOE_MAX_EXPERTS + 1];
   const int n = resolve_count(n_cap, n_dev);
   const int nblk = (n + PB - 1) / PB;
   const int e = threadIdx.x;
@@ -92,6 +97,12 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(int n_cap, const int3
       acc += total[i];
     }
     expert_offsets[E] = acc;
+  }
+  if (tile_rows > 0) {   // fused layer path: the grouped-GEMM work list comes out of the same scan
+    __threadfence_block();
+    __syncthreads();
+    fmoe_build_tiles(expert_offsets, E, row_cap, n, has_shared != 0, tile_rows, tile_cap, tiles,
+                     tile_count, scratch);
   }
 }
 
@@ -121,7 +132,8 @@ __global__ __launch_bounds__(PB) void permute_scatter_kernel(
 
 int launch_permute(const fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* kept_idx, int n_cap,
                    const int32_t* n_dev, int32_t* expert_offsets, int32_t* perm_src,
-                   int32_t* inv_perm, void* ws, const fmoe_ws_layout& L, hipStream_t stream) {
+                   int32_t* inv_perm, void* ws, const fmoe_ws_layout& L, bool build_tiles,
+                   hipStream_t stream) {
   char* base = static_cast<char*>(ws);
   int32_t* slot_rank = reinterpret_cast<int32_t*>(base + L.slot_rank);
   int32_t* blk_count = reinterpret_cast<int32_t*>(base + L.blk_count);
@@ -135,7 +147,11 @@ int launch_permute(const fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* 
   {
     fmoe_prof_scope prof(ctx, SLOT_PERM_SCAN, stream);
     hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(256), 0, stream, (Kmax > 0) ? n_cap : 0,
-                       (Kmax > 0) ? n_dev : nullptr, E, blk_count, expert_offsets);
+                       (Kmax > 0) ? n_dev : nullptr, E, blk_count, expert_offsets,
+                       build_tiles ? fmoe_tile_rows(ctx, n_cap) : 0, ctx->cfg.n_shared > 0 ? 1 : 0,
+                       n_cap * Kmax, fmoe_tile_cap(ctx, n_cap),
+                       reinterpret_cast<fmoe_tile*>(base + L.tiles),
+                       reinterpret_cast<int32_t*>(base + L.tile_count));
   }
   if (nblk > 0 && Kmax > 0) {
     fmoe_prof_scope prof(ctx, SLOT_PERM_SCATTER, stream);

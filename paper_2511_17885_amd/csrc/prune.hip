@@ -82,10 +82,12 @@ __global__ __launch_bounds__(256) void seq_ordinals_kernel(
 __global__ __launch_bounds__(256) void window_score_kernel(
     const float* __restrict__ probs, const int32_t* __restrict__ cu, int B, int T, int E, int W,
     int sim_mode, const int32_t* __restrict__ vis_tok, const int32_t* __restrict__ seq_nv,
-    const float* __restrict__ attn, float* __restrict__ win_s, float* __restrict__ win_a) {
+    const float* __restrict__ attn, float* __restrict__ win_s, float* __restrict__ win_a,
+    int32_t* __restrict__ precede) {
   const int lane = threadIdx.x & 63;
   const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (g >= T) return;
+  if (lane == 0) precede[g] = 0;   // accumulated by select_kernel
   const int b = find_seq(cu, B, g);
   int s, e;
   seq_range(cu, b, T, s, e);
@@ -178,76 +180,145 @@ __global__ __launch_bounds__(256) void window_score_kernel(
   if (lane == 0) win_s[g] = S;
 }
 
-// ---- C: drop selection.  One thread per slot; it walks every window of its sequence and adds up
-// the sizes of the windows that precede its own in the drop order
-// (normalised attention asc, score desc, index asc).  drop_from[g] = number of leading tokens
-// of the window that survive (w = untouched, 0 = dropped whole).
+// ---- C: drop order.  The drop order (normalised attention asc, score desc, index asc) is total, so
+// "how many windows precede window i" fixes everything.  The count is an all-pairs comparison on
+// integer sort keys, split two ways over the grid: blockIdx.x owns 256 window slots (i), blockIdx.y
+// a run of 64 candidate windows (j) of the same sequence, staged through LDS; partial counts are
+// added with integer atomics (order-free).  Bit 30 of the sum records that the sequence's last
+// (possibly shorter) window precedes i.
+constexpr int SEL_JC = 64;
+
+__device__ __forceinline__ uint32_t float_order_key(float v) {   // monotone: a < b <=> key(a) < key(b)
+  v = v + 0.0f;                                                   // -0 -> +0, so equal floats get equal keys
+  const uint32_t u = __float_as_uint(v);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
 __global__ __launch_bounds__(256) void select_kernel(
-    const int32_t* __restrict__ cu, int B, int T, int W, float retention, float alpha,
+    const int32_t* __restrict__ cu, int B, int T, int W, float alpha,
     const int32_t* __restrict__ seq_nv, const float* __restrict__ win_s,
-    const float* __restrict__ win_a, int32_t* __restrict__ drop_from, float* __restrict__ scores_out) {
-  const int g = blockIdx.x * blockDim.x + threadIdx.x;
-  if (g >= T) return;
-  const int b = find_seq(cu, B, g);
-  int s, e;
-  seq_range(cu, b, T, s, e);
-  const int i = g - s;
-  const int nv = seq_nv[b];
-  if (i < 0 || (long long)i * W >= nv) return;
+    const float* __restrict__ win_a, int32_t* __restrict__ precede, float* __restrict__ scores_out) {
+  __shared__ __align__(16) unsigned long long tileK[SEL_JC];   // (~key(C) << 32) | index: ascending = drop order
+  __shared__ __align__(16) uint32_t tileA[SEL_JC];             // key(A)
+  __shared__ float red[4];
+  const int g0 = blockIdx.x * 256;
+  const int g = g0 + threadIdx.x;
+  const int g_last = (g0 + 255 < T - 1) ? g0 + 255 : T - 1;
+  const int jbase = blockIdx.y * SEL_JC;
+  const int b_first = find_seq(cu, B, g0), b_last = find_seq(cu, B, g_last);
+  const bool has_attn = (win_a != nullptr);
+  const float one_minus_alpha = 1.0f - alpha;
+  for (int b = b_first; b <= b_last; ++b) {   // uniform over the block
+    int s, e;
+    seq_range(cu, b, T, s, e);
+    const int nv = seq_nv[b];
+    const int n = (nv + W - 1) / W;
+    if (jbase >= n || s + n <= g0 || s > g_last) continue;
+    // per-sequence attention maximum (Eq.12)
+    float amax = 0.0f;
+    if (has_attn) {
+      float m = 0.0f;
+      for (int j = threadIdx.x; j < n; j += 256) {
+        const float a = win_a[s + j];
+        m = (a > m) ? a : m;
+      }
+#pragma unroll
+      for (int sh = 32; sh >= 1; sh >>= 1) {
+        const float o = __shfl_xor(m, sh, 64);
+        m = (o > m) ? o : m;
+      }
+      __syncthreads();
+      if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+      __syncthreads();
+      amax = red[0];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) amax = (red[w] > amax) ? red[w] : amax;
+    }
+    auto score = [&](int j, float& Aj) -> float {   // Eq.13 (C = S exactly without attention)
+      const float Sj = win_s[s + j];
+      if (!has_attn) {
+        Aj = 0.0f;
+        return Sj;
+      }
+      float a = win_a[s + j];
+      if (amax > 0.0f) a = a / amax;
+      Aj = a;
+      const float t1 = alpha * Sj;
+      const float t2 = one_minus_alpha * a;
+      return t1 - t2;
+    };
+    const int i = g - s;
+    const bool mine = (g < T) && i >= 0 && i < n;
+    unsigned long long Ki = 0ull;
+    uint32_t Ai = 0u;
+    if (mine) {
+      float a;
+      const float c = score(i, a);
+      if (scores_out != nullptr && blockIdx.y == 0) scores_out[g] = c;
+      Ki = ((unsigned long long)(~float_order_key(c)) << 32) | (uint32_t)i;
+      Ai = float_order_key(a);
+    }
+    int count = 0, last_first = 0;
+    for (int j0 = jbase; j0 < n; j0 += (int)gridDim.y * SEL_JC) {   // uniform
+      __syncthreads();
+      if (threadIdx.x < SEL_JC) {
+        const int jl = j0 + threadIdx.x;
+        unsigned long long kj = ~0ull;   // sentinel: precedes nothing
+        uint32_t aj = ~0u;
+        if (jl < n) {
+          float a;
+          const float c = score(jl, a);
+          kj = ((unsigned long long)(~float_order_key(c)) << 32) | (uint32_t)jl;
+          aj = float_order_key(a);
+        }
+        tileK[threadIdx.x] = kj;
+        tileA[threadIdx.x] = aj;
+      }
+      __syncthreads();
+      if (mine) {
+#pragma unroll
+        for (int jj = 0; jj < SEL_JC; ++jj) {
+          const unsigned long long K = tileK[jj];
+          const uint32_t A = tileA[jj];
+          const int first = (int)(A < Ai) | ((int)(A == Ai) & (int)(K < Ki));
+          count += first;
+          last_first |= first & (int)(j0 + jj == n - 1);
+        }
+      }
+    }
+    if (mine && (count | last_first)) atomicAdd(&precede[g], count + (last_first << 30));
+  }
+}
+
+// number of leading tokens of visual ordinal `ord`'s window that survive (Sec. 3.2.3 budget and the
+// drop rule): windows are dropped whole in drop order while they fit in eps = N_v - eta and the
+// next one loses its last tokens.
+__device__ __forceinline__ int window_keep_lead(int ord, int nv, int W, float retention,
+                                                const int32_t* precede_seq) {
   const int n = (nv + W - 1) / W;
-  // budget: eta = floor(r*N_v + 1/2) in fp64, at least one token
-  int eta = (int)floor((double)retention * (double)nv + 0.5);
+  const int i = ord / W;
+  int eta = (int)floor((double)retention * (double)nv + 0.5);   // eta = floor(r*N_v + 1/2), fp64
   eta = eta > nv ? nv : eta;
   eta = eta < 1 ? 1 : eta;
   const int eps = nv - eta;
-
-  const bool has_attn = (win_a != nullptr);
-  float amax = 0.0f;
-  if (has_attn)
-    for (int j = 0; j < n; ++j) {
-      const float a = win_a[s + j];
-      amax = (a > amax) ? a : amax;
-    }
-  const float one_minus_alpha = 1.0f - alpha;
-  auto score = [&](int j, float& Aj) -> float {
-    const float Sj = win_s[s + j];
-    if (!has_attn) {
-      Aj = 0.0f;
-      return Sj;
-    }
-    float a = win_a[s + j];
-    if (amax > 0.0f) a = a / amax;
-    Aj = a;
-    const float t1 = alpha * Sj;
-    const float t2 = one_minus_alpha * a;
-    return t1 - t2;
-  };
-  float Ai;
-  const float Ci = score(i, Ai);
-  if (scores_out != nullptr) scores_out[g] = Ci;
-  int before = 0;
-  for (int j = 0; j < n; ++j) {
-    float Aj;
-    const float Cj = score(j, Aj);
-    const bool first = (Aj < Ai) || (Aj == Ai && (Cj > Ci || (Cj == Ci && j < i)));
-    if (first) {
-      const int wj = (nv - j * W < W) ? (nv - j * W) : W;
-      before += wj;
-    }
-  }
-  const int wi = (nv - i * W < W) ? (nv - i * W) : W;
-  int keep_lead = wi;
-  if (before + wi <= eps) keep_lead = 0;
-  else if (before < eps) keep_lead = wi - (eps - before);
-  drop_from[g] = keep_lead;
+  const int pc = precede_seq[i];
+  const int count = pc & 0x3fffffff, last_first = pc >> 30;
+  const int w_last = nv - (n - 1) * W;
+  const int before = count * W - (last_first ? (W - w_last) : 0);
+  const int wi = (i == n - 1) ? w_last : W;
+  if (before + wi <= eps) return 0;
+  if (before < eps) return wi - (eps - before);
+  return wi;
 }
 
-// ---- D: compaction.  A single block walks the tokens in order, keeps text tokens and the leading
-// tokens of each window, and writes ascending kept indices; keep_prefix[t] = kept tokens before t.
+// ---- D: budget + compaction.  A single block walks the tokens in order, keeps text tokens and the
+// leading tokens of each window, and writes ascending kept indices; keep_prefix[t] = kept tokens
+// before t.
 __global__ __launch_bounds__(1024) void compact_kernel(
     const uint8_t* __restrict__ is_visual, const int32_t* __restrict__ cu, int B, int T, int W,
-    const int32_t* __restrict__ vis_ord, const int32_t* __restrict__ drop_from,
-    int32_t* __restrict__ keep_prefix, int32_t* __restrict__ kept_idx,
+    float retention, const int32_t* __restrict__ vis_ord, const int32_t* __restrict__ seq_nv,
+    const int32_t* __restrict__ precede, int32_t* __restrict__ keep_prefix,
+    int32_t* __restrict__ kept_idx,
     int32_t* __restrict__ new_cu, uint8_t* __restrict__ is_visual_out) {
   __shared__ int wave_tot[16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -262,7 +333,7 @@ __global__ __launch_bounds__(1024) void compact_kernel(
       } else {
         const int b = find_seq(cu, B, t);
         const int s = clampi(cu[b], 0, T);
-        keep = (ord % W) < drop_from[s + ord / W];
+        keep = (ord % W) < window_keep_lead(ord, seq_nv[b], W, retention, precede + s);
       }
     }
     const unsigned long long mask = __ballot(keep);
@@ -329,19 +400,21 @@ int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* 
   {
     fmoe_prof_scope prof(ctx, SLOT_SCORES, stream);
     hipLaunchKernelGGL(window_score_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, probs, cu_seqlens,
-                       B, T, E, pp->window, pp->sim_mode, vis_tok, seq_nv, attn, win_s, win_a);
+                       B, T, E, pp->window, pp->sim_mode, vis_tok, seq_nv, attn, win_s, win_a, drop_from);
   }
   {
     fmoe_prof_scope prof(ctx, SLOT_SELECT, stream);
-    hipLaunchKernelGGL(select_kernel, dim3((T + 255) / 256), dim3(256), 0, stream, cu_seqlens, B, T,
-                       pp->window, pp->retention, pp->alpha, seq_nv, win_s, win_a, drop_from,
+    const int n_max = (T + pp->window - 1) / pp->window;   // no sequence has more windows
+    const int gy = (n_max + SEL_JC - 1) / SEL_JC;
+    hipLaunchKernelGGL(select_kernel, dim3((T + 255) / 256, gy < 4096 ? gy : 4096), dim3(256), 0,
+                       stream, cu_seqlens, B, T, pp->window, pp->alpha, seq_nv, win_s, win_a, drop_from,
                        scores_out);
   }
   {
     fmoe_prof_scope prof(ctx, SLOT_COMPACT, stream);
     hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, stream, is_visual, cu_seqlens, B, T,
-                       pp->window, vis_ord, drop_from, keep_prefix, kept_idx, new_cu_seqlens,
-                       is_visual_out);
+                       pp->window, pp->retention, vis_ord, seq_nv, drop_from, keep_prefix, kept_idx,
+                       new_cu_seqlens, is_visual_out);
   }
   FMOE_HIP_CHECK(hipGetLastError());
   return FMOE_OK;

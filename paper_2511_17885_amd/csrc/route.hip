@@ -4,24 +4,44 @@
 // fixed order that any IEEE-754 machine reproduces bit for bit.  This file is compiled with
 // floating-point contraction off; fused multiply-adds appear only where fmaf is written.
 //
-//  logit:  the d products of a (token, expert) pair are accumulated by 64 partial sums; element k
-//          belongs to partial k mod 64, partials take their elements in ascending k starting
-//          from +0 with fmaf, and are then combined by a 6-level butterfly
-//          (p[l] += p[l xor s], s = 32,16,..,1).  One wavefront lane owns one partial, so a
-//          lane reads a strided set of elements and the butterfly is a cross-lane exchange.
+//  logit:  the plain fp32 dot product in index order, acc = fmaf(x[k], w[k], acc) for k = 0..d-1
+//          from +0.  The fp32 matrix-core instruction v_mfma_f32_16x16x4_f32 performs exactly this
+//          chain (its four k per instruction are applied in ascending order, one rounding each;
+//          verified bit for bit on gfx950), so a 16-token x 16-expert tile of logits costs one
+//          instruction per four k and the chain is reproduced by a scalar fmaf loop anywhere else.
 //  exp:    range reduction by rint(x*log2 e) with a two-constant ln 2, degree-7 Taylor polynomial
 //          in Horner form, exact scaling by 2^n; flushed to 0 once 2^n leaves the normal range.
-//  sum:    lane l adds q[l], q[l+64], ... in that order from +0, then the same butterfly.
+//  sum:    lane l adds q[l], q[l+64], ... in that order from +0, then a 6-level xor butterfly
+//          (p[l] += p[l xor s], s = 32,16,..,1).
 //
-// Work split: a 256-thread block holds 4 wavefronts; each wavefront owns TOK tokens whose rows
-// sit in LDS, sweeps the experts EB at a time keeping TOK*EB partial sums per lane in
-// registers, then does softmax / top-k for its tokens with lanes mapped to experts.
+// Work split: a 256-thread block owns 16 tokens; its 4 wavefronts split the experts (NB blocks of
+// 16 experts each).  Token rows are staged through LDS in 128-wide k chunks, widened to fp32 and
+// de-interleaved so that a lane fetches the operands of four consecutive MFMAs with one 16-byte
+// LDS read; router weights come from a private fp32 copy that fmoe_set_weights lays out in
+// exactly the per-lane order the MFMA consumes (one coalesced 16-byte global load per four
+// MFMAs); several chunks of both are kept in flight in registers.  Logits meet in LDS, then each wavefront does softmax /
+// top-k for four tokens with lanes mapped to experts.
 
 #include "common.h"
 
 namespace {
 
-constexpr int kWaves = 4;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef float fx4_t __attribute__((ext_vector_type(4)));
+
+constexpr int TOKB = 16;           // tokens per block
+constexpr int KC = 128;            // k per LDS chunk
+constexpr int NG = KC / 16;        // groups of four MFMAs per chunk
+constexpr int RS = KC / 4 + 4;     // LDS row stride in floats (rows = kq*16 + token)
+
+// k groups (of 16) in the packed router weights: d rounded up to whole chunks, then to a multiple of
+// 5 chunks or 4 chunks (the prefetch depths the kernel is instantiated with), whichever is larger
+__host__ __device__ inline int router_groups(int d) {
+  const int chunks = (d + KC - 1) / KC;
+  const int p4 = (chunks + 3) / 4 * 4, p5 = (chunks + 4) / 5 * 5;
+  return (p4 > p5 ? p4 : p5) * NG;
+}
 
 __device__ __forceinline__ float wave_sum_butterfly(float p) {
 #pragma unroll
@@ -58,157 +78,284 @@ __device__ __forceinline__ float exp_fixed(float x) {
   return p * scale;
 }
 
-template <typename XT, int TOK, int EB>
+// Private router-weight layout: for expert block eb (16 experts) and k group g (16 k), lane l
+// holds the float4 { w[eb*16 + l%16][16g + 4j + l/16] : j = 0..3 } at ((eb*G + g)*64 + l).
+// Experts >= E and k >= d are zero (a zero product leaves the chain's value unchanged); G covers
+// d rounded up to whole 128-wide chunks, so the kernel's loads need no bounds predicate.
+template <typename WT>
+__global__ void pack_router_kernel(const WT* __restrict__ w, float* __restrict__ wp, int E, int d,
+                                   int Eb, int G) {
+  const size_t n = (size_t)Eb * G * 256;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const int j = (int)(i & 3), l = (int)((i >> 2) & 63);
+    const size_t eg = i >> 8;
+    const int g = (int)(eg % G), eb = (int)(eg / G);
+    const int e = eb * 16 + (l & 15), k = 16 * g + 4 * j + (l >> 4);
+    wp[i] = (e < E && k < d) ? to_f32(w[(size_t)e * d + k]) : 0.0f;
+  }
+}
+
+template <typename XT> struct XStage;
+template <> struct XStage<bf16_t> {
+  static constexpr int UNITS = 1;  // 16 tokens x 128 k / 8 per 16-byte load / 256 threads
+  u32x4_t v[UNITS];
+  // Unpredicated: a token past T re-reads the last token (its logits are never used) and k past d
+  // re-reads the row's last chunk (the packed weights are zero there).
+  __device__ __forceinline__ void load(const bf16_t* x, int t0, int T, int d, int c0, int tid) {
+    const int tok = tid >> 4, cu = tid & 15;
+    int k = c0 + 8 * cu, t = t0 + tok;
+    k = k < d ? k : d - 8;
+    t = t < T ? t : T - 1;
+    v[0] = *reinterpret_cast<const u32x4_t*>(x + (size_t)t * d + k);
+  }
+  __device__ __forceinline__ void store(float* xs, int tid) const {
+    const int tok = tid >> 4, cu = tid & 15;
+    const uint32_t w[4] = {v[0][0], v[0][1], v[0][2], v[0][3]};
+    float f[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+    // element i of the unit has k = 8cu + i: kq = i%4, step = 2cu + i/4
+#pragma unroll
+    for (int kq = 0; kq < 4; ++kq)
+      *reinterpret_cast<float2*>(&xs[(kq * 16 + tok) * RS + 2 * cu]) = make_float2(f[kq], f[kq + 4]);
+  }
+};
+template <> struct XStage<float> {
+  static constexpr int UNITS = 2;  // 16 x 128 / 4 / 256
+  fx4_t v[UNITS];
+  __device__ __forceinline__ void load(const float* x, int t0, int T, int d, int c0, int tid) {
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) {
+      const int unit = tid + u * 256;
+      const int tok = unit >> 5, cu = unit & 31;
+      int k = c0 + 4 * cu, t = t0 + tok;
+      k = k < d ? k : d - 4;
+      t = t < T ? t : T - 1;
+      v[u] = *reinterpret_cast<const fx4_t*>(x + (size_t)t * d + k);
+    }
+  }
+  __device__ __forceinline__ void store(float* xs, int tid) const {
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) {
+      const int unit = tid + u * 256;
+      const int tok = unit >> 5, cu = unit & 31;
+      xs[(0 * 16 + tok) * RS + cu] = v[u][0];
+      xs[(1 * 16 + tok) * RS + cu] = v[u][1];
+      xs[(2 * 16 + tok) * RS + cu] = v[u][2];
+      xs[(3 * 16 + tok) * RS + cu] = v[u][3];
+    }
+  }
+};
+
+template <typename XT, int NB, int PF>
 __global__ __launch_bounds__(256) void route_kernel(
-    const XT* __restrict__ x, const float* __restrict__ wr, const float* __restrict__ bias,
-    const uint8_t* __restrict__ is_visual, int T, int d, int E, int k_text, int k_visual, int Kmax,
-    int renorm, float* __restrict__ probs, int32_t* __restrict__ topk_idx,
+    const XT* __restrict__ x, const fx4_t* __restrict__ wp, const float* __restrict__ bias,
+    const uint8_t* __restrict__ is_visual, int T, int d, int E, int Eb, int G, int nch, int k_text,
+    int k_visual, int Kmax, int renorm, float* __restrict__ probs, int32_t* __restrict__ topk_idx,
     float* __restrict__ topk_gate) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  XT* xs = reinterpret_cast<XT*>(smem) + (size_t)wave * TOK * d;                   // [TOK][d]
-  float* zs = reinterpret_cast<float*>(smem + (size_t)kWaves * TOK * d * sizeof(XT)) +
-              (size_t)wave * TOK * E;                                               // [TOK][E]
-  const int t0 = (blockIdx.x * kWaves + wave) * TOK;
+  __shared__ __align__(16) float xs[64 * RS];
+  __shared__ float zs[TOKB][4 * NB * 16 + 1];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int t0 = blockIdx.x * TOKB;
 
-  // stage this wavefront's token rows into LDS (rows past T are zero and never written back)
-  for (int tok = 0; tok < TOK; ++tok) {
-    const int t = t0 + tok;
-    for (int k = lane; k < d; k += 64) xs[tok * d + k] = (t < T) ? x[(size_t)t * d + k] : XT(0);
+  f32x4_t acc[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  // PF chunks of operands are kept in flight in registers (the block's wavefronts are often alone
+  // on their SIMDs, so memory latency has to be covered inside the wavefront)
+  fx4_t wbuf[PF][NG][NB];
+  XStage<XT> xbuf[PF];
+  const fx4_t* wsrc[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    int eb = wave * NB + nb;
+    eb = eb < Eb ? eb : Eb - 1;   // expert blocks past E recompute the last one; never read back
+    wsrc[nb] = wp + (size_t)eb * G * 64 + lane;
   }
-  __builtin_amdgcn_wave_barrier();
-  __syncthreads();
-
-  // logits
-  for (int e0 = 0; e0 < E; e0 += EB) {
-    float acc[TOK][EB];
+  auto load_chunk = [&](int slot, int c0) {
+    xbuf[slot].load(x, t0, T, d, c0, tid);
 #pragma unroll
-    for (int a = 0; a < TOK; ++a)
+    for (int gl = 0; gl < NG; ++gl)
 #pragma unroll
-      for (int i = 0; i < EB; ++i) acc[a][i] = 0.0f;
-    for (int k = lane; k < d; k += 64) {
-      float xv[TOK];
+      for (int nb = 0; nb < NB; ++nb) wbuf[slot][gl][nb] = wsrc[nb][(size_t)(c0 / 16 + gl) * 64];
+  };
+  // nch chunks (a multiple of PF; d is zero-padded up to it in the packed weights).  The loop body
+  // is straight-line code with a fixed number of loads per step so that the waits on them can be
+  // counted exactly: chunk c is multiplied while chunks c+1 .. c+PF are in flight.
+  const int xrow = ((lane >> 4) * 16 + (lane & 15)) * RS;
+  auto step = [&](int p) {
+    xbuf[p].store(xs, tid);
+    __syncthreads();
 #pragma unroll
-      for (int a = 0; a < TOK; ++a) xv[a] = to_f32(xs[a * d + k]);
+    for (int gl = 0; gl < NG; ++gl) {
+      const fx4_t xa = *reinterpret_cast<const fx4_t*>(&xs[xrow + gl * 4]);
 #pragma unroll
-      for (int i = 0; i < EB; ++i) {
-        if (e0 + i < E) {
-          const float w = wr[(size_t)(e0 + i) * d + k];
-#pragma unroll
-          for (int a = 0; a < TOK; ++a) acc[a][i] = fmaf(xv[a], w, acc[a][i]);
-        }
+      for (int nb = 0; nb < NB; ++nb) {
+        const fx4_t wv = wbuf[p][gl][nb];
+        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], wv[0], acc[nb], 0, 0, 0);
+        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[1], wv[1], acc[nb], 0, 0, 0);
+        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[2], wv[2], acc[nb], 0, 0, 0);
+        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[3], wv[3], acc[nb], 0, 0, 0);
       }
     }
+  };
 #pragma unroll
-    for (int a = 0; a < TOK; ++a)
+  for (int p = 0; p < PF; ++p) load_chunk(p, p * KC);
+  int c = 0;
+  for (; c + PF < nch; c += PF) {
 #pragma unroll
-      for (int i = 0; i < EB; ++i) {
-        float z = wave_sum_butterfly(acc[a][i]);
-        if (lane == 0 && e0 + i < E) zs[a * E + e0 + i] = z;
-      }
+    for (int p = 0; p < PF; ++p) {
+      step(p);
+      load_chunk(p, (c + p + PF) * KC);
+      __syncthreads();
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < PF; ++p) {
+    step(p);
+    __syncthreads();
+  }
+
+  // accumulator register v of lane l: token 4*(l/16) + v, expert (block)*16 + l%16
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int e = (wave * NB + nb) * 16 + (lane & 15);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) zs[4 * (lane >> 4) + v][e] = acc[nb][v];
   }
   __syncthreads();
 
-  // softmax, top-k and gates: lanes <-> experts (expert e lives in lane e%64, register e/64)
-  for (int tok = 0; tok < TOK; ++tok) {
-    const int t = t0 + tok;
-    if (t >= T) break;  // uniform per wavefront
-    float z[4], q[4];
-    float m = -INFINITY;
+  // softmax, top-k and gates: lanes <-> experts (expert e lives in lane e%64, register e/64).
+  // The wavefront's four tokens are processed side by side so that the cross-lane reduction
+  // chains of different tokens overlap.
+  constexpr int TQ = 4;
+  float P[TQ][NB], part[TQ], mx[TQ];
+  int tt[TQ];
+  bool tv[TQ];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+  for (int tq = 0; tq < TQ; ++tq) {
+    const int tok = wave * TQ + tq;
+    tv[tq] = (t0 + tok) < T;
+    tt[tq] = tv[tq] ? t0 + tok : T - 1;
+    mx[tq] = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
       const int e = lane + 64 * i;
-      z[i] = -INFINITY;
+      float v = -INFINITY;
       if (e < E) {
-        float v = zs[tok * E + e];
+        v = zs[tok][e];
         if (bias != nullptr) v = v + bias[e];
-        z[i] = v;
-        m = (v > m) ? v : m;
       }
+      P[tq][i] = v;
+      mx[tq] = (v > mx[tq]) ? v : mx[tq];
     }
-    m = wave_max(m);
-    float part = 0.0f;
+  }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+  for (int s = 32; s >= 1; s >>= 1)
+#pragma unroll
+    for (int tq = 0; tq < TQ; ++tq) {
+      const float o = __shfl_xor(mx[tq], s, 64);
+      mx[tq] = (o > mx[tq]) ? o : mx[tq];
+    }
+#pragma unroll
+  for (int tq = 0; tq < TQ; ++tq) {
+    part[tq] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
       const int e = lane + 64 * i;
-      q[i] = 0.0f;
+      float q = 0.0f;
       if (e < E) {
-        q[i] = exp_fixed(z[i] - m);
-        part = part + q[i];
+        q = exp_fixed(P[tq][i] - mx[tq]);
+        part[tq] = part[tq] + q;
       }
+      P[tq][i] = q;
     }
-    const float denom = wave_sum_butterfly(part);
-    float P[4];
+  }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+  for (int s = 32; s >= 1; s >>= 1)
+#pragma unroll
+    for (int tq = 0; tq < TQ; ++tq) part[tq] = part[tq] + __shfl_xor(part[tq], s, 64);
+#pragma unroll
+  for (int tq = 0; tq < TQ; ++tq)
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
       const int e = lane + 64 * i;
-      P[i] = q[i] / denom;
-      if (probs != nullptr && e < E) probs[(size_t)t * E + e] = P[i];
+      P[tq][i] = (e < E) ? P[tq][i] / part[tq] : -1.0f;   // -1 ranks below every probability
+      if (probs != nullptr && tv[tq] && e < E) probs[(size_t)tt[tq] * E + e] = P[tq][i];
     }
 
-    const int k = is_visual[t] ? k_visual : k_text;
-    unsigned taken = 0;
-    int my_e = -1;
-    float my_p = 0.0f;
-    for (int r = 0; r < k; ++r) {
-      float bv = -1.0f;
-      int be = 0x7fffffff;
+  // rank of every expert in the order (probability desc, index asc): one pass over all experts,
+  // each broadcast from its lane, instead of k dependent arg-max reductions
+  int rank[TQ][NB];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int e = lane + 64 * i;
-        if (e < E && !(taken & (1u << i)) && P[i] > bv) {
-          bv = P[i];
-          be = e;
-        }
-      }
+  for (int tq = 0; tq < TQ; ++tq)
 #pragma unroll
-      for (int s = 32; s >= 1; s >>= 1) {
-        const float ov = __shfl_xor(bv, s, 64);
-        const int oe = __shfl_xor(be, s, 64);
-        if (ov > bv || (ov == bv && oe < be)) {
-          bv = ov;
-          be = oe;
+    for (int i = 0; i < NB; ++i) rank[tq][i] = 0;
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+#pragma unroll 16
+    for (int sl = 0; sl < 64; ++sl) {
+#pragma unroll
+      for (int tq = 0; tq < TQ; ++tq) {
+        const float v = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, P[tq][j]), sl));
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+          bool ahead;
+          if (j < i) ahead = v >= P[tq][i];
+          else if (j > i) ahead = v > P[tq][i];
+          else ahead = (v > P[tq][i]) | ((v == P[tq][i]) & (sl < lane));
+          rank[tq][i] += ahead ? 1 : 0;
         }
-      }
-      if ((be & 63) == lane) taken |= 1u << (be >> 6);
-      if (lane == r) {
-        my_e = be;
-        my_p = bv;
       }
     }
+  }
+  __syncthreads();   // every wavefront is done reading its logits: rows of zs are reused below
+#pragma unroll
+  for (int tq = 0; tq < TQ; ++tq) {
+    const int tok = wave * TQ + tq;
+    const int k = is_visual[tt[tq]] ? k_visual : k_text;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int e = lane + 64 * i;
+      if (e < E && rank[tq][i] < k) {
+        zs[tok][rank[tq][i]] = P[tq][i];
+        zs[tok][FMOE_MAX_TOPK + rank[tq][i]] = __int_as_float(e);
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int tq = 0; tq < TQ; ++tq) {
+    const int tok = wave * TQ + tq;
+    const int k = is_visual[tt[tq]] ? k_visual : k_text;
     float den = 0.0f;
-    for (int r = 0; r < k; ++r) den = den + __shfl(my_p, r, 64);
-    if (lane < Kmax) {
+    for (int r = 0; r < k; ++r) den = den + zs[tok][r];   // list order, sequential (Eq.5)
+    if (tv[tq] && lane < Kmax) {
       const bool live = lane < k;
-      const float g = live ? (renorm ? my_p / den : my_p) : 0.0f;
-      topk_idx[(size_t)t * Kmax + lane] = live ? my_e : -1;
-      topk_gate[(size_t)t * Kmax + lane] = g;
+      const float pr = live ? zs[tok][lane] : 0.0f;
+      topk_idx[(size_t)tt[tq] * Kmax + lane] = live ? __float_as_int(zs[tok][FMOE_MAX_TOPK + lane]) : -1;
+      topk_gate[(size_t)tt[tq] * Kmax + lane] = live ? (renorm ? pr / den : pr) : 0.0f;
     }
   }
 }
 
-__global__ void widen_bf16_kernel(const bf16_t* __restrict__ src, float* __restrict__ dst, size_t n) {
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (; i < n; i += stride) dst[i] = bf16_to_f32(src[i]);
-}
-
-template <typename XT, int TOK, int EB>
+template <typename XT, int NB, int PF>
 int launch_route_t(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int T, float* probs,
                    int32_t* topk_idx, float* topk_gate, hipStream_t stream) {
   const int d = ctx->cfg.d_model, E = ctx->cfg.n_experts;
-  const size_t lds = (size_t)kWaves * TOK * d * sizeof(XT) + (size_t)kWaves * TOK * E * sizeof(float);
-  auto kern = route_kernel<XT, TOK, EB>;
-  if (lds > 48 * 1024)
-    FMOE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  const int per_block = kWaves * TOK;
-  const int grid = (T + per_block - 1) / per_block;
+  const int Eb = (E + 15) / 16, G = router_groups(d);
+  const int nch = (((d + KC - 1) / KC + PF - 1) / PF) * PF;   // <= G / NG by construction
+  const int grid = (T + TOKB - 1) / TOKB;
   fmoe_prof_scope prof(ctx, SLOT_ROUTE, stream);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, static_cast<const XT*>(x),
-                     ctx->router_w32, ctx->router_bias, is_visual, T, d, E, ctx->cfg.k_text,
-                     ctx->cfg.k_visual, ctx->kmax, ctx->cfg.renormalize, probs, topk_idx, topk_gate);
+  hipLaunchKernelGGL((route_kernel<XT, NB, PF>), dim3(grid), dim3(256), 0, stream,
+                     static_cast<const XT*>(x), reinterpret_cast<const fx4_t*>(ctx->router_wp),
+                     ctx->router_bias, is_visual, T, d, E, Eb, G, nch, ctx->cfg.k_text, ctx->cfg.k_visual,
+                     ctx->kmax, ctx->cfg.renormalize, probs, topk_idx, topk_gate);
   FMOE_HIP_CHECK(hipGetLastError());
   return FMOE_OK;
 }
@@ -216,28 +363,38 @@ int launch_route_t(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual,
 template <typename XT>
 int launch_route_x(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int T, float* probs,
                    int32_t* topk_idx, float* topk_gate, hipStream_t stream) {
-  const int d = ctx->cfg.d_model, E = ctx->cfg.n_experts;
-  const size_t budget = 144 * 1024;
-  auto lds = [&](int tok) {
-    return (size_t)kWaves * tok * d * sizeof(XT) + (size_t)kWaves * tok * E * sizeof(float);
-  };
-  // more tokens per wavefront = more reuse of each router-weight load; fewer = more blocks
-  int tok = 4;
-  while (tok > 1 && (lds(tok) > budget || (T + kWaves * tok - 1) / (kWaves * tok) < 512)) tok >>= 1;
-  if (lds(tok) > budget)
-    return fmoe_fail(FMOE_ERR_UNSUPPORTED, "route: d_model %d too large for the LDS row stage", d);
-  if (tok == 4) return launch_route_t<XT, 4, 8>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, stream);
-  if (tok == 2) return launch_route_t<XT, 2, 8>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, stream);
-  return launch_route_t<XT, 1, 8>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, stream);
+  const int E = ctx->cfg.n_experts;
+  const int chunks = (ctx->cfg.d_model + KC - 1) / KC;
+  if (E <= 64) {
+    if (chunks < 4) return launch_route_t<XT, 1, 1>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, stream);
+    if (chunks % 5 == 0) return launch_route_t<XT, 1, 5>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, stream);
+    return launch_route_t<XT, 1, 4>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, stream);
+  }
+  if (E <= 128) {
+    if (chunks < 2) return launch_route_t<XT, 2, 1>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, stream);
+    return launch_route_t<XT, 2, 2>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, stream);
+  }
+  return launch_route_t<XT, 4, 1>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, stream);
 }
 
 }  // namespace
 
-int launch_widen_bf16(const void* src, float* dst, size_t n, hipStream_t stream) {
-  if (n == 0) return FMOE_OK;
+size_t router_pack_floats(const fmoe_ctx* ctx) {
+  const int Eb = (ctx->cfg.n_experts + 15) / 16, G = router_groups(ctx->cfg.d_model);
+  return (size_t)Eb * G * 256;
+}
+
+int launch_pack_router(const fmoe_ctx* ctx, const void* router_w, float* wp, hipStream_t stream) {
+  const int E = ctx->cfg.n_experts, d = ctx->cfg.d_model;
+  const int Eb = (E + 15) / 16, G = router_groups(d);
+  const size_t n = router_pack_floats(ctx);
   const int grid = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-  hipLaunchKernelGGL(widen_bf16_kernel, dim3(grid), dim3(256), 0, stream,
-                     static_cast<const bf16_t*>(src), dst, n);
+  if (ctx->cfg.dtype == FMOE_BF16)
+    hipLaunchKernelGGL(pack_router_kernel<bf16_t>, dim3(grid), dim3(256), 0, stream,
+                       static_cast<const bf16_t*>(router_w), wp, E, d, Eb, G);
+  else
+    hipLaunchKernelGGL(pack_router_kernel<float>, dim3(grid), dim3(256), 0, stream,
+                       static_cast<const float*>(router_w), wp, E, d, Eb, G);
   FMOE_HIP_CHECK(hipGetLastError());
   return FMOE_OK;
 }

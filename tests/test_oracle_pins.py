@@ -65,6 +65,28 @@ def test_sum_canon_order_is_lane_strided_then_tree():
     assert oracle.sum_canon(v) == np.float32(1.0 + 2.0 ** -23)
 
 
+def test_dot_seq_is_index_order_fma_chain():
+    rng = np.random.default_rng(21)
+    a = rng.integers(-30, 30, size=300).astype(np.float32)
+    b = rng.integers(-30, 30, size=300).astype(np.float32)
+    assert float(oracle.dot_seq(a, b)) == float((a.astype(np.int64) * b.astype(np.int64)).sum())
+    one, tiny = np.float32(1.0), np.float32(2.0 ** -24)
+    ones = np.ones(3, np.float32)
+    # ascending order: (tiny + tiny) + 1 keeps 2^-23; descending: (1 + tiny) + tiny loses both
+    assert oracle.dot_seq(np.array([tiny, tiny, one], np.float32), ones) == np.float32(1.0 + 2.0 ** -23)
+    assert oracle.dot_seq(np.array([one, tiny, tiny], np.float32), ones) == one
+    # fused: the product is not rounded before the add.  (1+2^-12)^2 = 1 + 2^-11 + 2^-24; a rounded
+    # product (1 + 2^-11) minus (1 + 2^-11) is 0, the fused chain keeps the 2^-24.
+    x = np.float32(1.0 + 2.0 ** -12)
+    got = oracle.dot_seq(np.array([1.0, x], np.float32), np.array([-(1.0 + 2.0 ** -11), x], np.float32))
+    assert got == np.float32(2.0 ** -24)
+    # against the exactly rounded value on random data
+    a = rng.standard_normal(2048).astype(np.float32)
+    b = (rng.standard_normal(2048) * 0.02).astype(np.float32)
+    exact = math.fsum(float(p) * float(q) for p, q in zip(a, b))
+    assert abs(float(oracle.dot_seq(a, b)) - exact) < 2e-6
+
+
 def test_round_store_bf16_matches_bit_trick_and_ties():
     rng = np.random.default_rng(2)
     v = (rng.standard_normal(4000) * np.exp(rng.uniform(-20, 20, 4000))).astype(np.float32)
