@@ -146,15 +146,16 @@ int fmoe_permute(fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* kept_idx
 
 /* The expert FFNs of Eq.4 as a grouped GEMM: for every row r of expert e,
  * y[r] = FFN_e(x[token(perm_src[r])]); the activation silu(.)*(.) is rounded to dtype between
- * the two products.  y [n_kept*Kmax capacity, H] dtype.  y_shared [n_kept,H] dtype or NULL iff
- * N_s == 0: the SUM of the shared experts for every kept token. */
+ * the two products.  y [n_kept*Kmax capacity, H] dtype.  y_shared [N_s, n_kept, H] dtype or NULL
+ * iff N_s == 0: the output of shared expert i for kept position p at (i*n_kept + p)*H. */
 int fmoe_expert_ffn(fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int32_t n_kept,
                     const int32_t* n_kept_dev, const int32_t* expert_offsets,
                     const int32_t* perm_src, void* y, void* y_shared, void* ws, size_t ws_bytes,
                     void* stream);
 
-/* Eq.4: out[p] = (residual[t]) + y_shared[p] + sum_s topk_gate[t,s] * y[inv_perm[p,s]] with
- * t = kept_idx[p]; fp32 accumulation in that order, one rounding to dtype.
+/* Eq.4: out[p] = (residual[t]) + sum_i y_shared[i][p] + sum_s topk_gate[t,s] * y[inv_perm[p,s]]
+ * with t = kept_idx[p]; fp32 accumulation in that order, one rounding to dtype.  y, y_shared,
+ * n_kept as given to fmoe_expert_ffn.
  * residual [T,H] dtype or NULL; out [n_kept,H] dtype. */
 int fmoe_combine(fmoe_ctx* ctx, const void* y, const void* y_shared, const int32_t* inv_perm,
                  const float* topk_gate, const int32_t* kept_idx, int32_t n_kept,

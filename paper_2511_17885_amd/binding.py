@@ -210,7 +210,8 @@ class FMoE:
         y = torch.empty((max(n_kept * K, 1), self.d), dtype=self.torch_dtype, device=self.device)
         ysh = None
         if self.cfg.n_shared > 0:
-            ysh = torch.empty((max(n_kept, 1), self.d), dtype=self.torch_dtype, device=self.device)
+            ysh = torch.empty((self.cfg.n_shared, max(n_kept, 1), self.d), dtype=self.torch_dtype,
+                              device=self.device)
         ws = self.workspace(n_kept, 1)
         _check(self.lib.fmoe_expert_ffn(self._ctx, _ptr(x), _ptr(kept_idx), n_kept, _ptr(n_kept_dev),
                                         _ptr(expert_offsets), _ptr(perm_src), _ptr(y), _ptr(ysh),

@@ -114,13 +114,14 @@ fmoe_ws_layout fmoe_layout(const fmoe_ctx* ctx, int32_t max_tokens, int32_t max_
   L.expert_offsets = take((E + 1) * 4);
   L.perm_src = take(rows * 4);
   L.inv_perm = take(rows * 4);
-  const size_t tile_cap = rows / FMOE_TILE_M + E + (T + FMOE_TILE_M - 1) / FMOE_TILE_M;
+  const size_t tile_cap = (size_t)fmoe_geom(ctx, (int)T).tile_cap;
   L.tiles = take(tile_cap * sizeof(fmoe_tile));
+  L.tiles2 = take(tile_cap * sizeof(fmoe_tile));
   L.tile_count = take(16);
   L.h = take(rows * (size_t)c.d_ffn * es);
   L.h_shared = take(c.n_shared > 0 ? T * (size_t)c.n_shared * c.d_ffn_shared * es : 0);
   L.y = take(rows * (size_t)c.d_model * es);
-  L.y_shared = take(c.n_shared > 0 ? T * (size_t)c.d_model * es : 0);
+  L.y_shared = take(c.n_shared > 0 ? (size_t)c.n_shared * T * (size_t)c.d_model * es : 0);
   L.total = off;
   return L;
 }
@@ -157,6 +158,9 @@ void fmoe_destroy(fmoe_ctx* ctx) {
     delete ctx->prof;
   }
   if (ctx->router_wp) (void)hipFree(ctx->router_wp);
+  void* packed[4] = {ctx->pk_gate_up, ctx->pk_down, ctx->pk_sgate_up, ctx->pk_sdown};
+  for (void* p : packed)
+    if (p) (void)hipFree(p);
   delete ctx;
 }
 
@@ -200,6 +204,14 @@ int fmoe_set_weights(fmoe_ctx* ctx, const void* router_w, const float* router_bi
   ctx->router_bias = router_bias;
   ctx->w_gate = w_gate; ctx->w_up = w_up; ctx->w_down = w_down;
   ctx->ws_gate = ws_gate; ctx->ws_up = ws_up; ctx->ws_down = ws_down;
+  if (ctx->cfg.dtype == FMOE_BF16) {
+    void** slots[4] = {&ctx->pk_gate_up, &ctx->pk_down, &ctx->pk_sgate_up, &ctx->pk_sdown};
+    for (int i = 0; i < 4; ++i) {
+      const size_t bytes = fmoe_packed_bytes(ctx, i);
+      if (bytes && !*slots[i]) FMOE_HIP_CHECK(hipMalloc(slots[i], bytes));
+    }
+    if ((rc = launch_pack_experts(ctx, static_cast<hipStream_t>(stream))) != FMOE_OK) return rc;
+  }
   ctx->weights_set = true;
   return FMOE_OK;
 }

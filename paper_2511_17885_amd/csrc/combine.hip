@@ -1,5 +1,5 @@
 // Gate-weighted un-permute / combine (Eq.4):
-//   out[p] = (residual[t]) + y_shared[p] + sum_s gate[t,s] * y[inv_perm[p,s]],   t = kept_idx[p]
+//   out[p] = (residual[t]) + sum_i y_shared[i][p] + sum_s gate[t,s] * y[inv_perm[p,s]],   t = kept_idx[p]
 // A pure bandwidth kernel: one block per kept token, 16-byte loads of every contributing row,
 // fp32 accumulation in the fixed order residual, shared, slot 0, 1, ... and a single rounding to
 // the storage type, so the result does not depend on scheduling.
@@ -43,8 +43,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(
     const T* __restrict__ y, const T* __restrict__ y_shared, const int32_t* __restrict__ inv_perm,
     const float* __restrict__ topk_gate, const int32_t* __restrict__ kept_idx, int n_cap,
-    const int32_t* __restrict__ n_dev, int row_cap, int Kmax, int d, const T* __restrict__ residual,
-    T* __restrict__ out) {
+    const int32_t* __restrict__ n_dev, int row_cap, int Kmax, int d, int n_shared,
+    const T* __restrict__ residual, T* __restrict__ out) {
   constexpr int N = Vec<T>::N;
   const int n = resolve_count(n_cap, n_dev);
   const int p = blockIdx.x;
@@ -69,9 +69,11 @@ __global__ __launch_bounds__(256) void combine_kernel(
       for (int i = 0; i < N; ++i) acc[i] = v[i];
     }
     if (y_shared) {
-      Vec<T>::load(y_shared + (size_t)p * d + c, v);
+      for (int s = 0; s < n_shared; ++s) {   // first sum of Eq.4, in expert order
+        Vec<T>::load(y_shared + ((size_t)s * n_cap + p) * d + c, v);
 #pragma unroll
-      for (int i = 0; i < N; ++i) acc[i] += v[i];
+        for (int i = 0; i < N; ++i) acc[i] += v[i];
+      }
     }
     for (int s = 0; s < Kmax; ++s) {
       const int r = rows[s];
@@ -97,12 +99,12 @@ int launch_combine(const fmoe_ctx* ctx, const void* y, const void* y_shared, con
   if (ctx->cfg.dtype == FMOE_BF16) {
     hipLaunchKernelGGL(combine_kernel<bf16_t>, dim3(n_cap), dim3(256), 0, stream,
                        static_cast<const bf16_t*>(y), static_cast<const bf16_t*>(y_shared), inv_perm,
-                       topk_gate, kept_idx, n_cap, n_dev, row_cap, Kmax, d,
+                       topk_gate, kept_idx, n_cap, n_dev, row_cap, Kmax, d, ctx->cfg.n_shared,
                        static_cast<const bf16_t*>(residual), static_cast<bf16_t*>(out));
   } else {
     hipLaunchKernelGGL(combine_kernel<float>, dim3(n_cap), dim3(256), 0, stream,
                        static_cast<const float*>(y), static_cast<const float*>(y_shared), inv_perm,
-                       topk_gate, kept_idx, n_cap, n_dev, row_cap, Kmax, d,
+                       topk_gate, kept_idx, n_cap, n_dev, row_cap, Kmax, d, ctx->cfg.n_shared,
                        static_cast<const float*>(residual), static_cast<float*>(out));
   }
   FMOE_HIP_CHECK(hipGetLastError());

@@ -34,6 +34,8 @@ struct fmoe_ctx {
   const float* router_bias;
   const void *w_gate, *w_up, *w_down;
   const void *ws_gate, *ws_up, *ws_down;
+  // bf16 contexts: private copies of the expert weights in matrix-core operand order (ffn.hip)
+  void *pk_gate_up, *pk_down, *pk_sgate_up, *pk_sdown;
   bool weights_set;
   fmoe_prof* prof;           // nullptr unless fmoe_profile_enable was called
 };
@@ -65,7 +67,7 @@ struct fmoe_ws_layout {
   size_t win_s, win_a, drop_from, keep_prefix;  // prune
   size_t slot_rank, blk_count;                  // permute
   size_t expert_offsets, perm_src, inv_perm;    // layer_forward intermediates
-  size_t tiles, tile_count;                     // grouped GEMM tile list
+  size_t tiles, tiles2, tile_count;             // grouped GEMM tile lists (gate/up, down)
   size_t h, h_shared, y, y_shared;              // FFN intermediates
   size_t total;
 };
@@ -74,9 +76,22 @@ fmoe_ws_layout fmoe_layout(const fmoe_ctx* ctx, int32_t max_tokens, int32_t max_
 struct fmoe_tile {  // one M-tile of the grouped GEMM
   int32_t group;    // expert id
   int32_t row0;     // first row (in the permuted row space)
-  int32_t rows;     // valid rows in the tile (1..FMOE_TILE_M)
-  int32_t pad;
+  int32_t rows;     // valid rows in the tile
+  int32_t col0;     // first column tile this entry covers (shared group split over entries)
+  int32_t rt;       // index of this row tile within its group's run of consecutive entries
+  int32_t nrt;      // number of row tiles in that run
 };
+
+// launch geometry of the two grouped GEMMs for a call with capacity n_cap
+struct fmoe_ffn_geom {
+  int bm;              // rows per tile
+  int cols1, scols1;   // column tiles per launch entry / of the shared group, gate-up GEMM
+  int cols2, scols2;   // same, down GEMM
+  int tile_cap;        // capacity of each tile list
+};
+fmoe_ffn_geom fmoe_geom(const fmoe_ctx* ctx, int n_cap);
+size_t fmoe_packed_bytes(const fmoe_ctx* ctx, int which);   // 0 gate/up, 1 down, 2 shared gate/up, 3 shared down
+int launch_pack_experts(fmoe_ctx* ctx, hipStream_t stream);
 
 // ---- kernel launchers (each returns a fmoe_status; all work goes to `stream`)
 size_t router_pack_floats(const fmoe_ctx* ctx);
@@ -94,14 +109,13 @@ int launch_identity_kept(const uint8_t* is_visual, const int32_t* cu_seqlens, in
                          int32_t* kept_idx, int32_t* new_cu_seqlens, uint8_t* is_visual_out,
                          hipStream_t stream);
 
-// build_tiles: also write the grouped-GEMM tile list for fmoe_tile_rows(ctx, n_cap)-row tiles
+// build_tiles: also write the grouped-GEMM tile lists (geometry from fmoe_geom(ctx, n_cap))
 int launch_permute(const fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* kept_idx, int n_cap,
                    const int32_t* n_dev, int32_t* expert_offsets, int32_t* perm_src,
                    int32_t* inv_perm, void* ws, const fmoe_ws_layout& L, bool build_tiles,
                    hipStream_t stream);
 
-int fmoe_tile_rows(const fmoe_ctx* ctx, int n_cap);
-int fmoe_tile_cap(const fmoe_ctx* ctx, int n_cap);
+
 
 int launch_expert_ffn(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int n_cap,
                       const int32_t* n_dev, const int32_t* expert_offsets, const int32_t* perm_src,

@@ -4,24 +4,30 @@
 //       h = silu(X_e W_gate[e]^T) * (X_e W_up[e]^T)      fused SwiGLU epilogue, h stored in dtype
 //   GEMM-2:  y = h W_down[e]^T
 //
-// Both are "NT" products: activations [rows, K] and weights [N, K] are K-contiguous, which is
-// exactly the operand layout the 32x32 MFMA instructions want (a lane supplies consecutive k of
-// one row / one output column), so tiles go global -> registers -> LDS -> MFMA without any
-// transposition.  With FastMMoE switched on an expert sees a few dozen to a few hundred rows, far
-// below the ~315 rows at which a bf16 expert becomes compute bound on this chip, so the kernel
-// is built to stream every expert's weights from HBM exactly once at full rate: a block owns a
-// (row tile, 128 weight rows) pair, keeps the next k-tile in flight in registers while the
-// matrix cores work on the current one, and several blocks share a CU.
-//
-// The ragged per-expert row counts become a device-built list of row tiles (tiles.h); the
-// always-on shared experts are one more dense group in the same list and the same launch.  The
-// N_s shared experts are treated as one FFN whose hidden dimension is the concatenation of
-// theirs, so their sum is accumulated in fp32 inside the down projection.
-//
-// Block -> work mapping: workgroups are spread round-robin over the 8 XCDs (each with its own
-// L2), so the linear block id is decoded as (batch of 8 row tiles, column tile, tile within the
-// batch = XCD); all column tiles of one row tile then run on one XCD and the gathered
-// activation rows are fetched from HBM once and re-read from that XCD's L2.
+// With FastMMoE switched on an expert sees a few dozen to a few hundred rows, far below the ~315
+// rows at which a bf16 expert becomes compute bound on this chip, so the bf16 kernel is built
+// around the weight stream:
+//  * fmoe_set_weights re-lays the (static) expert weights once into matrix-core operand order:
+//    for a column block and a 32-wide k step, the 64 lanes' 16-byte B fragments of
+//    v_mfma_f32_16x16x32_bf16 are contiguous (1 KB), gate and up fragments interleaved, k steps
+//    consecutive.  A wavefront's whole weight stream for its columns is then one linear run of
+//    memory that it loads straight into registers -- no LDS hop, no address arithmetic, perfect
+//    coalescing and DRAM page locality -- and every weight byte is fetched by exactly one wavefront
+//    per row tile.
+//  * a block owns a 128-row tile of one expert and 4 column blocks (one per wavefront); the
+//    gathered activation rows go through a double-buffered LDS tile; both streams are kept PF
+//    k-tiles ahead in registers, in a loop whose steady state has no predicated loads so the
+//    hardware wait counters can be set exactly.
+//  * the ragged per-expert row counts become device-built lists of row tiles (tiles.h); the
+//    always-on shared experts are one more dense group in the same lists and the same launch,
+//    treated as ONE FFN whose hidden dimension is the concatenation of the N_s experts, so their
+//    sum is accumulated in fp32 inside the down projection.
+//  * block -> work: workgroups are spread round-robin over the 8 XCDs (each with its own L2), so
+//    the linear block id is decoded as (batch of 8 row tiles, column tile, tile within the batch
+//    = XCD); all column tiles of one row tile run on one XCD and its activation rows are fetched
+//    from HBM once.
+// The fp32 storage type (a correctness configuration) uses a plain LDS-tiled kernel on the fp32
+// MFMA with the caller's weight layout.
 
 #include "common.h"
 #include "tiles.h"
@@ -30,16 +36,264 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // one 16-byte chunk
 
+__device__ __forceinline__ float silu_mul(float g, float u) {
+  return g * __frcp_rn(1.0f + __expf(-g)) * u;
+}
+
+// ======================================================================== bf16: weight-stream kernel
+constexpr int SBM = 128;        // rows per tile: 8 MFMA row blocks of 16
+constexpr int SBK = 64;         // k per tile: two 32-wide MFMA steps
+constexpr int SLDK = SBK + 8;   // LDS row stride in elements (144 bytes)
+
+struct StreamProblem {
+  const bf16_t* A;            // [*, lda]
+  int lda;
+  const int32_t* map1;        // row -> index (perm_src) or null
+  const int32_t* map2;        // index -> token (kept_idx) or null
+  int map1_limit;             // clamp for map1 values (exclusive), <= 0: none
+  const u32x4_t* Bp;          // packed weights
+  long long group_stride;     // 16-byte units between groups
+  int nbw;                    // column blocks per group in the packing
+  int ks;                     // 32-wide k steps per column block in the packing (K padded to 64)
+  bf16_t* C;                  // [*, ldc]
+  int ldc;
+  int N, K;
+  int n_col_tiles;
+  int a_group_off;            // shared group g reads A columns from g*a_group_off (elements)
+  long long c_group_off;      // and writes C at g*c_group_off (elements)
+};
+
+struct StreamArgs {
+  StreamProblem p0;           // routed experts
+  StreamProblem p1;           // shared group (tile.group == E)
+  int E;
+  const fmoe_tile* tiles;
+  const int32_t* n_tiles;     // device
+  int cols;                   // column tiles per tile entry in this launch
+};
+
+// One (row tile, column tile) work item.  NAB = number of live 32-row bands of the tile (1..4):
+// a compile-time constant, so the k loop below is straight-line code with a fixed number of loads,
+// LDS reads and matrix instructions per step, and rows past the last live band cost nothing.
+//   weights:     register ring of 4 k-tiles per wavefront (3 in flight while 1 is multiplied)
+//   activations: register ring of 2 k-tiles per thread feeding a double-buffered LDS tile
+template <bool SWIGLU, int NAB>
+__device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_tile& tile, int group, int nt,
+                                            bf16_t (*As)[SBM * SLDK]) {
+  constexpr int NRB = 2 * NAB;   // 16-row MFMA blocks computed
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int N = P.N, K = P.K;
+  const int NT = (K + SBK - 1) / SBK;
+
+  // this wavefront's weight stream: column block (nt*4 + wave) of the packing
+  int nbw = nt * 4 + wave;
+  nbw = nbw < P.nbw ? nbw : P.nbw - 1;     // past N: recompute the last block, never stored
+  const u32x4_t* bsrc = P.Bp + (size_t)group * P.group_stride + (size_t)nbw * P.ks * 128 + lane;
+
+  // activation chunks of this thread (NAB x 16 bytes per k-tile); rows past the tile reuse its last row
+  const bf16_t* a_src[NAB];
+  const int a_kc = (tid & 7) * 8;
+  const int a_lo = (tid >> 3) * SLDK + a_kc;
+#pragma unroll
+  for (int it = 0; it < NAB; ++it) {
+    const int r = (tid >> 3) + 32 * it;
+    int src = tile.row0 + (r < tile.rows ? r : tile.rows - 1);
+    if (P.map1) {
+      src = P.map1[src];
+      if (P.map1_limit > 0) src = src < 0 ? 0 : (src >= P.map1_limit ? P.map1_limit - 1 : src);
+    }
+    if (P.map2) src = P.map2[src];
+    a_src[it] = P.A + (size_t)src * P.lda;
+  }
+
+  f32x4_t acc[NRB][2];
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+    for (int f = 0; f < 2; ++f) acc[rb][f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  u32x4_t breg[4][2][2];   // [ring slot][k step][fragment]
+  u32x4_t areg[2][NAB];
+  auto loadB = [&](int slot, int t) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int f = 0; f < 2; ++f) breg[slot][s][f] = bsrc[(size_t)((t * 2 + s) * 2 + f) * 64];
+  };
+  // k past K (ragged last tile): the address is clamped into the row; the packed weights are zero
+  // there, so the product vanishes without predicating the load
+  auto loadA = [&](int slot, int t) {
+    const int k = t * SBK + a_kc;
+    const int kk = k < K ? k : K - 8;
+#pragma unroll
+    for (int it = 0; it < NAB; ++it) areg[slot][it] = *reinterpret_cast<const u32x4_t*>(a_src[it] + kk);
+  };
+  auto storeA = [&](int slot, int buf) {
+#pragma unroll
+    for (int it = 0; it < NAB; ++it)
+      *reinterpret_cast<u32x4_t*>(&As[buf][a_lo + it * 32 * SLDK]) = areg[slot][it];
+  };
+  const int frag_off = (lane & 15) * SLDK + 8 * (lane >> 4);
+  auto compute = [&](int slot, int buf) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const bf16x8_t fb0 = __builtin_bit_cast(bf16x8_t, breg[slot][s][0]);
+      const bf16x8_t fb1 = __builtin_bit_cast(bf16x8_t, breg[slot][s][1]);
+      bf16x8_t fa[NRB];
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb)
+        fa[rb] = *reinterpret_cast<const bf16x8_t*>(&As[buf][rb * 16 * SLDK + frag_off + s * 32]);
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb) {
+        acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[rb], fb0, acc[rb][0], 0, 0, 0);
+        acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[rb], fb1, acc[rb][1], 0, 0, 0);
+      }
+    }
+  };
+
+  // prologue: weights of tiles 0..2, activations of tiles 0..2 (tile 0 already in LDS buffer 0)
+#pragma unroll
+  for (int q = 0; q < 3; ++q)
+    if (q < NT) loadB(q, q);
+  loadA(0, 0);
+  if (1 < NT) loadA(1, 1);
+  storeA(0, 0);
+  if (2 < NT) loadA(0, 2);
+  __syncthreads();
+
+  // step t (u = t mod 4): publish tile t+1 to the other LDS buffer, start the loads of tile t+3,
+  // multiply tile t, barrier
+  int t = 0;
+  for (; t + 7 <= NT; t += 4) {   // steady state: every load is unconditional
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      storeA((u + 1) & 1, (u + 1) & 1);
+      loadA((u + 1) & 1, t + u + 3);
+      loadB((u + 3) & 3, t + u + 3);
+      compute(u, u & 1);
+      __syncthreads();
+    }
+  }
+  for (; t < NT; t += 4) {        // drain
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (t + u < NT) {
+        if (t + u + 1 < NT) storeA((u + 1) & 1, (u + 1) & 1);
+        if (t + u + 3 < NT) {
+          loadA((u + 1) & 1, t + u + 3);
+          loadB((u + 3) & 3, t + u + 3);
+        }
+        compute(u, u & 1);
+        __syncthreads();
+      }
+    }
+  }
+
+  // epilogue: accumulator register v of lane l holds row 4*(l/16) + v, column l%16 of a 16x16 block
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int row = rb * 16 + 4 * (lane >> 4) + v;
+      if (row >= tile.rows) continue;
+      bf16_t* crow = P.C + (size_t)(tile.row0 + row) * P.ldc;
+      if (SWIGLU) {
+        const int col = nt * 64 + wave * 16 + (lane & 15);
+        if (col < N) crow[col] = f32_to_bf16(silu_mul(acc[rb][0][v], acc[rb][1][v]));
+      } else {
+        const int col = nt * 128 + wave * 32 + (lane & 15);
+        if (col < N) crow[col] = f32_to_bf16(acc[rb][0][v]);
+        if (col + 16 < N) crow[col + 16] = f32_to_bf16(acc[rb][1][v]);
+      }
+    }
+  }
+}
+
+template <bool SWIGLU>
+__global__ __launch_bounds__(256) void ffn_stream_kernel(StreamArgs a) {
+  __shared__ __align__(16) bf16_t As[2][SBM * SLDK];
+
+  // One work item per block: item -> (batch of 8 row tiles, column tile, tile within the batch =
+  // XCD).  Blocks past the device-side tile count leave at once.
+  const int n_tiles = *a.n_tiles;
+  const int item = blockIdx.x;
+  const int xcd = item & 7;
+  const int rr = item >> 3;
+  const int batch = rr / a.cols;
+  int nt_launch = rr - batch * a.cols;
+  int ti = batch * 8 + xcd;
+  if (ti >= n_tiles) return;
+  fmoe_tile tile = a.tiles[ti];
+  const bool shared = tile.group >= a.E;
+  // field-by-field select keeps the descriptors in scalar registers (indexing the kernel argument
+  // dynamically would spill it to scratch memory)
+  StreamProblem P;
+#define FMOE_SEL(f) P.f = shared ? a.p1.f : a.p0.f
+  FMOE_SEL(A); FMOE_SEL(lda); FMOE_SEL(map1); FMOE_SEL(map2); FMOE_SEL(map1_limit); FMOE_SEL(Bp);
+  FMOE_SEL(group_stride); FMOE_SEL(nbw); FMOE_SEL(ks); FMOE_SEL(C); FMOE_SEL(ldc); FMOE_SEL(N);
+  FMOE_SEL(K); FMOE_SEL(n_col_tiles); FMOE_SEL(a_group_off); FMOE_SEL(c_group_off);
+#undef FMOE_SEL
+  // column tiles this entry really has
+  const int c_eff = (P.n_col_tiles - tile.col0 < a.cols) ? (P.n_col_tiles - tile.col0) : a.cols;
+  if (nt_launch >= c_eff) return;
+  // A group with 2..8 row tiles sits on that many XCDs (consecutive tile indices).  Its blocks are
+  // re-dealt column-major: XCD r takes the contiguous run [r*C, (r+1)*C) of items ordered by
+  // (column tile, row tile), i.e. ALL row tiles of ~C/R column tiles, so each weight column block is
+  // fetched by one XCD only (weights outweigh the activation rows, which every XCD then reads).
+  if (tile.nrt > 1 && tile.nrt <= 8) {
+    const int w = tile.rt * c_eff + nt_launch;
+    const int r2 = w % tile.nrt;
+    nt_launch = w / tile.nrt;
+    ti = ti - tile.rt + r2;
+    tile = a.tiles[ti];
+  }
+  const int nt = tile.col0 + nt_launch;
+  const int group = shared ? tile.group - a.E : tile.group;
+  if (shared) {   // per-shared-expert slices of the hidden buffer / output (down GEMM)
+    P.A += (size_t)group * P.a_group_off;
+    P.C += (size_t)group * P.c_group_off;
+  }
+  switch ((tile.rows + 31) >> 5) {   // uniform per block
+    case 1: stream_tile<SWIGLU, 1>(P, tile, group, nt, As); break;
+    case 2: stream_tile<SWIGLU, 2>(P, tile, group, nt, As); break;
+    case 3: stream_tile<SWIGLU, 3>(P, tile, group, nt, As); break;
+    default: stream_tile<SWIGLU, 4>(P, tile, group, nt, As); break;
+  }
+}
+
+// Packing: unit u (16 bytes = 8 consecutive k) -> (group, column block, k step, fragment, lane).
+//   gate/up (PAIR): column block = 16 output features, fragment 0 = gate rows, 1 = up rows
+//   down (!PAIR):   column block = 32 output features, fragment f = features 16f..16f+15
+// src rows are [group][n][k].
+template <bool PAIR>
+__global__ void pack_weights_kernel(const bf16_t* __restrict__ src0, const bf16_t* __restrict__ src1,
+                                    u32x4_t* __restrict__ dst, int G, int N, int K, int nbw, int ks) {
+  const size_t total = (size_t)G * nbw * ks * 128;
+  for (size_t u = (size_t)blockIdx.x * blockDim.x + threadIdx.x; u < total;
+       u += (size_t)gridDim.x * blockDim.x) {
+    const int lane = (int)(u & 63), f = (int)((u >> 6) & 1);
+    size_t q = u >> 7;
+    const int s = (int)(q % ks);
+    q /= ks;
+    const int b = (int)(q % nbw), g = (int)(q / nbw);
+    const int n = PAIR ? (b * 16 + (lane & 15)) : (b * 32 + f * 16 + (lane & 15));
+    const int k = s * 32 + 8 * (lane >> 4);
+    u32x4_t v = {0u, 0u, 0u, 0u};
+    if (n < N && k < K) {
+      const bf16_t* base = (PAIR && f) ? src1 : src0;
+      v = *reinterpret_cast<const u32x4_t*>(base + ((size_t)g * N + n) * K + k);
+    }
+    dst[u] = v;
+  }
+}
+
+// ======================================================================== fp32: LDS-tiled kernel
 constexpr int BNW = 128;  // weight rows per block: 64 gate + 64 up columns, or 128 down columns
 
 template <typename T> struct Traits;
-template <> struct Traits<bf16_t> {
-  static constexpr int VEC = 8;        // elements per 16-byte chunk
-  static constexpr int BK = 64;        // k per LDS stage
-  static constexpr int LDK = BK + 8;   // padded LDS row: 144 bytes, conflict-free 16-byte reads
-};
 template <> struct Traits<float> {
   static constexpr int VEC = 4;
   static constexpr int BK = 32;
@@ -56,12 +310,12 @@ struct GemmProblem {
   const void* B1;           // [G, N, K] up (SwiGLU only)
   long long group_stride;   // elements between groups (0 for the shared group)
   int ldb;                  // elements between consecutive weight rows
-  int seg_len;              // K is cut in segments of seg_len ...
-  long long seg_stride;     // ... seg_stride elements apart (shared down projection)
   void* C;                  // [*, ldc]
   int ldc;
   int N, K;
   int n_col_tiles;
+  int a_group_off;          // shared group g reads A columns from g*a_group_off (elements)
+  long long c_group_off;    // and writes C at g*c_group_off (elements)
 };
 
 struct GemmArgs {
@@ -72,10 +326,6 @@ struct GemmArgs {
   const int32_t* n_tiles;   // device
   int n_col_tiles_max;
 };
-
-__device__ __forceinline__ float silu_mul(float g, float u) {
-  return g * __frcp_rn(1.0f + __expf(-g)) * u;
-}
 
 template <typename T, bool SWIGLU, int MT>
 __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
@@ -92,7 +342,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
   const int xcd = blockIdx.x & 7;
   const int rr = blockIdx.x >> 3;
   const int batch = rr / a.n_col_tiles_max;
-  const int nt = rr - batch * a.n_col_tiles_max;
+  const int nt_launch = rr - batch * a.n_col_tiles_max;
   const int ti = batch * 8 + xcd;
   if (ti >= *a.n_tiles) return;
   const fmoe_tile tile = a.tiles[ti];
@@ -102,16 +352,18 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
   GemmProblem P;
 #define FMOE_SEL(f) P.f = shared ? a.p1.f : a.p0.f
   FMOE_SEL(A); FMOE_SEL(lda); FMOE_SEL(map1); FMOE_SEL(map2); FMOE_SEL(map1_limit);
-  FMOE_SEL(B0); FMOE_SEL(B1); FMOE_SEL(group_stride); FMOE_SEL(ldb); FMOE_SEL(seg_len);
-  FMOE_SEL(seg_stride); FMOE_SEL(C); FMOE_SEL(ldc); FMOE_SEL(N); FMOE_SEL(K); FMOE_SEL(n_col_tiles);
+  FMOE_SEL(B0); FMOE_SEL(B1); FMOE_SEL(group_stride); FMOE_SEL(ldb);
+  FMOE_SEL(C); FMOE_SEL(ldc); FMOE_SEL(N); FMOE_SEL(K); FMOE_SEL(n_col_tiles);
+  FMOE_SEL(a_group_off); FMOE_SEL(c_group_off);
 #undef FMOE_SEL
+  const int nt = tile.col0 + nt_launch;
   if (nt >= P.n_col_tiles) return;
-  const int group = shared ? 0 : tile.group;
+  const int group = shared ? tile.group - a.E : tile.group;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int N = P.N, K = P.K;
 
-  const T* Ag = static_cast<const T*>(P.A);
+  const T* Ag = static_cast<const T*>(P.A) + (shared ? (size_t)group * P.a_group_off : 0);
   const T* B0g = static_cast<const T*>(P.B0) + (size_t)group * P.group_stride;
   const T* B1g = SWIGLU ? static_cast<const T*>(P.B1) + (size_t)group * P.group_stride : nullptr;
 
@@ -152,8 +404,6 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
     }
     b_src[it] = base + (size_t)(n < N ? n : N - 1) * P.ldb;   // same trick for columns past N
   }
-  const bool segmented = P.seg_len < K;
-
   f32x16_t acc[MT][2];
 #pragma unroll
   for (int r = 0; r < MT; ++r)
@@ -183,12 +433,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
     for (int it = 0; it < B_IT; ++it) {
       const int k = k0 + b_k[it];
       const int kk = k < K ? k : K - VEC;
-      size_t off = (size_t)kk;
-      if (segmented) {   // uniform: only the shared experts' down projection
-        const int seg = kk / P.seg_len;
-        off = (size_t)seg * P.seg_stride + (size_t)(kk - seg * P.seg_len);
-      }
-      const u32x4_t v = *reinterpret_cast<const u32x4_t*>(b_src[it] + off);
+      const u32x4_t v = *reinterpret_cast<const u32x4_t*>(b_src[it] + kk);
       rb[it] = k < K ? v : zero4;
     }
   };
@@ -241,7 +486,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
   }
 
   // epilogue: accumulator register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
-  T* Cg = static_cast<T*>(P.C);
+  T* Cg = static_cast<T*>(P.C) + (shared ? (size_t)group * P.c_group_off : 0);
 #pragma unroll
   for (int r = 0; r < MT; ++r) {
     if (!live[r]) continue;
@@ -265,110 +510,209 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
 __global__ __launch_bounds__(256) void build_tiles_kernel(const int32_t* __restrict__ expert_offsets,
                                                           int E, int row_cap, int n_cap,
                                                           const int32_t* __restrict__ n_dev,
-                                                          int has_shared, int bm, int tile_cap,
-                                                          fmoe_tile* __restrict__ tiles,
+                                                          int n_shared, fmoe_ffn_geom geom,
+                                                          fmoe_tile* __restrict__ tiles1,
+                                                          fmoe_tile* __restrict__ tiles2,
                                                           int32_t* __restrict__ counts) {
-  __shared__ int scratch[FMOE_MAX_EXPERTS + 1];
-  fmoe_build_tiles(expert_offsets, E, row_cap, resolve_count(n_cap, n_dev), has_shared != 0, bm,
-                   tile_cap, tiles, counts, scratch);
+  __shared__ int scratch[256];
+  fmoe_build_tiles(expert_offsets, E, row_cap, resolve_count(n_cap, n_dev), n_shared, geom.bm,
+                   geom.tile_cap, geom.cols1, geom.scols1, tiles1, tiles2, counts, scratch);
 }
 
-template <typename T, int MT>
-int run_ffn(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int n_cap,
-            const int32_t* n_dev, const int32_t* expert_offsets, const int32_t* perm_src, void* y,
-            void* y_shared, void* ws, const fmoe_ws_layout& L, bool tiles_ready, hipStream_t stream) {
-  const fmoe_config& c = ctx->cfg;
-  const int d = c.d_model, E = c.n_experts, F = c.d_ffn, Kmax = ctx->kmax;
-  const bool has_shared = c.n_shared > 0;
-  char* base = static_cast<char*>(ws);
-  fmoe_tile* tiles = reinterpret_cast<fmoe_tile*>(base + L.tiles);
-  int32_t* tile_count = reinterpret_cast<int32_t*>(base + L.tile_count);
-  const int row_cap = n_cap * Kmax;
-  const int bm = 64 * MT;
-  const int tile_cap = fmoe_tile_cap(ctx, n_cap);
-  if (n_cap == 0 || (row_cap == 0 && !has_shared)) return FMOE_OK;
+inline int ks_steps(int K) { return ((K + SBK - 1) / SBK) * 2; }
 
-  if (!tiles_ready) {
-    fmoe_prof_scope prof(ctx, SLOT_TILES, stream);
-    hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(256), 0, stream, expert_offsets, E, row_cap,
-                       n_cap, n_dev, has_shared ? 1 : 0, bm, tile_cap, tiles, tile_count);
+}  // namespace
+
+fmoe_ffn_geom fmoe_geom(const fmoe_ctx* ctx, int n_cap) {
+  const fmoe_config& c = ctx->cfg;
+  fmoe_ffn_geom g;
+  g.bm = (c.dtype == FMOE_BF16) ? SBM : 64;
+  const int Ft = c.n_shared * c.d_ffn_shared;
+  g.cols1 = (c.d_ffn + 63) / 64;           // 64 hidden columns per block
+  g.scols1 = (Ft + 63) / 64;
+  g.cols2 = (c.d_model + 127) / 128;       // 128 output columns per block
+  g.scols2 = c.n_shared > 0 ? g.cols2 : 0;
+  const int rep1 = (g.scols1 + g.cols1 - 1) / g.cols1;
+  const int rep = rep1 > c.n_shared ? rep1 : (c.n_shared > 1 ? c.n_shared : 1);
+  const long long rows = (long long)n_cap * (ctx->kmax > 0 ? ctx->kmax : 1);
+  g.tile_cap = (int)(rows / g.bm) + c.n_experts + ((n_cap + g.bm - 1) / g.bm) * rep + 8;
+  return g;
+}
+
+size_t fmoe_packed_bytes(const fmoe_ctx* ctx, int which) {
+  const fmoe_config& c = ctx->cfg;
+  if (c.dtype != FMOE_BF16) return 0;
+  const size_t Ft = (size_t)c.n_shared * c.d_ffn_shared;
+  switch (which) {
+    case 0: return (size_t)c.n_experts * ((c.d_ffn + 15) / 16) * ks_steps(c.d_model) * 2048;
+    case 1: return (size_t)c.n_experts * ((c.d_model + 31) / 32) * ks_steps(c.d_ffn) * 2048;
+    case 2: return Ft ? ((Ft + 15) / 16) * ks_steps(c.d_model) * 2048 : 0;
+    case 3: return Ft ? (size_t)c.n_shared * ((c.d_model + 31) / 32) * ks_steps(c.d_ffn_shared) * 2048 : 0;
   }
-  const int Fs = c.d_ffn_shared, Ft = c.n_shared * Fs;
-  GemmArgs g1{}, g2{};
-  g1.E = g2.E = E;
-  g1.tiles = g2.tiles = tiles;
-  g1.n_tiles = g2.n_tiles = tile_count;
-  // GEMM-1: gate/up + SwiGLU
-  {
-    GemmProblem& p = g1.p0;
-    p.A = x; p.lda = d; p.map1 = perm_src; p.map2 = kept_idx; p.map1_limit = n_cap;
-    p.B0 = ctx->w_gate; p.B1 = ctx->w_up; p.group_stride = (long long)F * d; p.ldb = d;
-    p.seg_len = d; p.seg_stride = 0;
-    p.C = base + L.h; p.ldc = F; p.N = F; p.K = d; p.n_col_tiles = (F + 63) / 64;
-    GemmProblem& q = g1.p1;
-    q = p;
-    q.map1 = nullptr; q.map1_limit = 0;
-    q.B0 = ctx->ws_gate; q.B1 = ctx->ws_up; q.group_stride = 0;
-    q.C = base + L.h_shared; q.ldc = Ft; q.N = Ft; q.n_col_tiles = has_shared ? (Ft + 63) / 64 : 0;
-    g1.n_col_tiles_max = p.n_col_tiles > q.n_col_tiles ? p.n_col_tiles : q.n_col_tiles;
-  }
-  // GEMM-2: down projection
-  {
-    GemmProblem& p = g2.p0;
-    p.A = base + L.h; p.lda = F; p.map1 = nullptr; p.map2 = nullptr; p.map1_limit = 0;
-    p.B0 = ctx->w_down; p.B1 = nullptr; p.group_stride = (long long)d * F; p.ldb = F;
-    p.seg_len = F; p.seg_stride = 0;
-    p.C = y; p.ldc = d; p.N = d; p.K = F; p.n_col_tiles = (d + BNW - 1) / BNW;
-    GemmProblem& q = g2.p1;
-    q = p;
-    q.A = base + L.h_shared; q.lda = Ft;
-    q.B0 = ctx->ws_down; q.group_stride = 0; q.ldb = Fs; q.seg_len = has_shared ? Fs : 1;
-    q.seg_stride = (long long)d * Fs;
-    q.C = y_shared; q.K = Ft; q.n_col_tiles = has_shared ? p.n_col_tiles : 0;
-    g2.n_col_tiles_max = p.n_col_tiles;
-  }
-  const unsigned batches = (unsigned)((tile_cap + 7) / 8);
-  {
-    fmoe_prof_scope prof(ctx, SLOT_GEMM1, stream);
-    hipLaunchKernelGGL((grouped_gemm_kernel<T, true, MT>), dim3(batches * 8 * g1.n_col_tiles_max),
-                       dim3(256), 0, stream, g1);
-  }
-  {
-    fmoe_prof_scope prof(ctx, SLOT_GEMM2, stream);
-    hipLaunchKernelGGL((grouped_gemm_kernel<T, false, MT>), dim3(batches * 8 * g2.n_col_tiles_max),
-                       dim3(256), 0, stream, g2);
+  return 0;
+}
+
+int launch_pack_experts(fmoe_ctx* ctx, hipStream_t stream) {
+  const fmoe_config& c = ctx->cfg;
+  const int d = c.d_model, F = c.d_ffn, E = c.n_experts, Fs = c.d_ffn_shared;
+  const int Ft = c.n_shared * Fs;
+  auto grid = [](size_t bytes) { size_t b = bytes / 16 / 256 + 1; return (int)(b < 65536 ? b : 65536); };
+  hipLaunchKernelGGL(pack_weights_kernel<true>, dim3(grid(fmoe_packed_bytes(ctx, 0))), dim3(256), 0, stream,
+                     static_cast<const bf16_t*>(ctx->w_gate), static_cast<const bf16_t*>(ctx->w_up),
+                     static_cast<u32x4_t*>(ctx->pk_gate_up), E, F, d, (F + 15) / 16, ks_steps(d));
+  hipLaunchKernelGGL(pack_weights_kernel<false>, dim3(grid(fmoe_packed_bytes(ctx, 1))), dim3(256), 0, stream,
+                     static_cast<const bf16_t*>(ctx->w_down), static_cast<const bf16_t*>(nullptr),
+                     static_cast<u32x4_t*>(ctx->pk_down), E, d, F, (d + 31) / 32, ks_steps(F));
+  if (Ft > 0) {
+    hipLaunchKernelGGL(pack_weights_kernel<true>, dim3(grid(fmoe_packed_bytes(ctx, 2))), dim3(256), 0, stream,
+                       static_cast<const bf16_t*>(ctx->ws_gate), static_cast<const bf16_t*>(ctx->ws_up),
+                       static_cast<u32x4_t*>(ctx->pk_sgate_up), 1, Ft, d, (Ft + 15) / 16, ks_steps(d));
+    hipLaunchKernelGGL(pack_weights_kernel<false>, dim3(grid(fmoe_packed_bytes(ctx, 3))), dim3(256), 0, stream,
+                       static_cast<const bf16_t*>(ctx->ws_down), static_cast<const bf16_t*>(nullptr),
+                       static_cast<u32x4_t*>(ctx->pk_sdown), c.n_shared, d, Fs, (d + 31) / 32, ks_steps(Fs));
   }
   FMOE_HIP_CHECK(hipGetLastError());
   return FMOE_OK;
 }
 
+namespace {
+
+int run_ffn_f32(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int n_cap,
+                const int32_t* perm_src, void* y, void* y_shared, char* base, const fmoe_ws_layout& L,
+                const fmoe_ffn_geom& geo, hipStream_t stream) {
+  const fmoe_config& c = ctx->cfg;
+  const int d = c.d_model, E = c.n_experts, F = c.d_ffn;
+  const bool has_shared = c.n_shared > 0;
+  const int Fs = c.d_ffn_shared, Ft = c.n_shared * Fs;
+  int32_t* tile_count = reinterpret_cast<int32_t*>(base + L.tile_count);
+  GemmArgs g1{}, g2{};
+  g1.E = g2.E = E;
+  g1.tiles = reinterpret_cast<fmoe_tile*>(base + L.tiles);
+  g2.tiles = reinterpret_cast<fmoe_tile*>(base + L.tiles2);
+  g1.n_tiles = tile_count;
+  g2.n_tiles = tile_count + 1;
+  {
+    GemmProblem& p = g1.p0;
+    p.A = x; p.lda = d; p.map1 = perm_src; p.map2 = kept_idx; p.map1_limit = n_cap;
+    p.B0 = ctx->w_gate; p.B1 = ctx->w_up; p.group_stride = (long long)F * d; p.ldb = d;
+    p.C = base + L.h; p.ldc = F; p.N = F; p.K = d; p.n_col_tiles = geo.cols1;
+    GemmProblem& q = g1.p1;
+    q = p;
+    q.map1 = nullptr; q.map1_limit = 0;
+    q.B0 = ctx->ws_gate; q.B1 = ctx->ws_up; q.group_stride = 0;
+    q.C = base + L.h_shared; q.ldc = Ft; q.N = Ft; q.n_col_tiles = geo.scols1;
+    g1.n_col_tiles_max = geo.cols1;
+  }
+  {
+    GemmProblem& p = g2.p0;
+    p.A = base + L.h; p.lda = F; p.map1 = nullptr; p.map2 = nullptr; p.map1_limit = 0;
+    p.B0 = ctx->w_down; p.B1 = nullptr; p.group_stride = (long long)d * F; p.ldb = F;
+    p.C = y; p.ldc = d; p.N = d; p.K = F; p.n_col_tiles = geo.cols2;
+    GemmProblem& q = g2.p1;
+    q = p;
+    q.A = base + L.h_shared; q.lda = Ft; q.a_group_off = Fs;
+    q.B0 = ctx->ws_down; q.group_stride = (long long)d * Fs; q.ldb = Fs;
+    q.C = y_shared; q.c_group_off = (long long)n_cap * d; q.K = Fs; q.n_col_tiles = geo.scols2;
+    g2.n_col_tiles_max = geo.cols2;
+  }
+  const unsigned batches = (unsigned)((geo.tile_cap + 7) / 8);
+  {
+    fmoe_prof_scope prof(ctx, SLOT_GEMM1, stream);
+    hipLaunchKernelGGL((grouped_gemm_kernel<float, true, 1>), dim3(batches * 8 * g1.n_col_tiles_max),
+                       dim3(256), 0, stream, g1);
+  }
+  {
+    fmoe_prof_scope prof(ctx, SLOT_GEMM2, stream);
+    hipLaunchKernelGGL((grouped_gemm_kernel<float, false, 1>), dim3(batches * 8 * g2.n_col_tiles_max),
+                       dim3(256), 0, stream, g2);
+  }
+  return FMOE_OK;
+}
+
+int run_ffn_bf16(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int n_cap,
+                 const int32_t* perm_src, void* y, void* y_shared, char* base, const fmoe_ws_layout& L,
+                 const fmoe_ffn_geom& geo, hipStream_t stream) {
+  const fmoe_config& c = ctx->cfg;
+  const int d = c.d_model, E = c.n_experts, F = c.d_ffn;
+  const int Ft = c.n_shared * c.d_ffn_shared;
+  int32_t* tile_count = reinterpret_cast<int32_t*>(base + L.tile_count);
+  StreamArgs g1{}, g2{};
+  g1.E = g2.E = E;
+  g1.tiles = reinterpret_cast<fmoe_tile*>(base + L.tiles);
+  g2.tiles = reinterpret_cast<fmoe_tile*>(base + L.tiles2);
+  g1.n_tiles = tile_count;
+  g2.n_tiles = tile_count + 1;
+  g1.cols = geo.cols1;
+  g2.cols = geo.cols2;
+  {
+    StreamProblem& p = g1.p0;
+    p.A = static_cast<const bf16_t*>(x); p.lda = d; p.map1 = perm_src; p.map2 = kept_idx; p.map1_limit = n_cap;
+    p.Bp = static_cast<const u32x4_t*>(ctx->pk_gate_up);
+    p.nbw = (F + 15) / 16; p.ks = ks_steps(d); p.group_stride = (long long)p.nbw * p.ks * 128;
+    p.C = reinterpret_cast<bf16_t*>(base + L.h); p.ldc = F; p.N = F; p.K = d; p.n_col_tiles = geo.cols1;
+    StreamProblem& q = g1.p1;
+    q = p;
+    q.map1 = nullptr; q.map1_limit = 0;
+    q.Bp = static_cast<const u32x4_t*>(ctx->pk_sgate_up);
+    q.nbw = (Ft + 15) / 16; q.group_stride = 0;
+    q.C = reinterpret_cast<bf16_t*>(base + L.h_shared); q.ldc = Ft; q.N = Ft; q.n_col_tiles = geo.scols1;
+  }
+  {
+    StreamProblem& p = g2.p0;
+    p.A = reinterpret_cast<const bf16_t*>(base + L.h); p.lda = F; p.map1 = nullptr; p.map2 = nullptr; p.map1_limit = 0;
+    p.Bp = static_cast<const u32x4_t*>(ctx->pk_down);
+    p.nbw = (d + 31) / 32; p.ks = ks_steps(F); p.group_stride = (long long)p.nbw * p.ks * 128;
+    p.C = static_cast<bf16_t*>(y); p.ldc = d; p.N = d; p.K = F; p.n_col_tiles = geo.cols2;
+    StreamProblem& q = g2.p1;
+    q = p;
+    q.A = reinterpret_cast<const bf16_t*>(base + L.h_shared); q.lda = Ft; q.a_group_off = c.d_ffn_shared;
+    q.Bp = static_cast<const u32x4_t*>(ctx->pk_sdown);
+    q.ks = ks_steps(c.d_ffn_shared > 0 ? c.d_ffn_shared : 1); q.group_stride = (long long)q.nbw * q.ks * 128;
+    q.C = static_cast<bf16_t*>(y_shared); q.c_group_off = (long long)n_cap * d; q.K = c.d_ffn_shared;
+    q.n_col_tiles = geo.scols2;
+  }
+  const unsigned batches = (unsigned)((geo.tile_cap + 7) / 8);
+  {
+    fmoe_prof_scope prof(ctx, SLOT_GEMM1, stream);
+    const unsigned items = batches * 8 * g1.cols;
+    hipLaunchKernelGGL((ffn_stream_kernel<true>), dim3(items),
+                       dim3(256), 0, stream, g1);
+  }
+  {
+    fmoe_prof_scope prof(ctx, SLOT_GEMM2, stream);
+    const unsigned items = batches * 8 * g2.cols;
+    hipLaunchKernelGGL((ffn_stream_kernel<false>), dim3(items),
+                       dim3(256), 0, stream, g2);
+  }
+  return FMOE_OK;
+}
+
 }  // namespace
-
-// Rows per grouped-GEMM tile for a call with capacity n_cap: larger tiles when experts can be
-// expected to hold many rows (fewer re-reads of their weights), smaller ones otherwise.
-int fmoe_tile_rows(const fmoe_ctx* ctx, int n_cap) {
-  if (ctx->cfg.dtype != FMOE_BF16) return 64;
-  const long long avg = (long long)n_cap * ctx->kmax / ctx->cfg.n_experts;
-  return avg >= 1024 ? 256 : 128;
-}
-
-int fmoe_tile_cap(const fmoe_ctx* ctx, int n_cap) {
-  const int bm = fmoe_tile_rows(ctx, n_cap);
-  return (int)(((long long)n_cap * ctx->kmax) / bm) + ctx->cfg.n_experts + (n_cap + bm - 1) / bm;
-}
 
 int launch_expert_ffn(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int n_cap,
                       const int32_t* n_dev, const int32_t* expert_offsets, const int32_t* perm_src,
                       void* y, void* y_shared, void* ws, const fmoe_ws_layout& L, bool tiles_ready,
                       hipStream_t stream) {
-  const int bm = fmoe_tile_rows(ctx, n_cap);
-  if (ctx->cfg.dtype == FMOE_BF16) {
-    if (bm == 256)
-      return run_ffn<bf16_t, 4>(ctx, x, kept_idx, n_cap, n_dev, expert_offsets, perm_src, y, y_shared,
-                                ws, L, tiles_ready, stream);
-    return run_ffn<bf16_t, 2>(ctx, x, kept_idx, n_cap, n_dev, expert_offsets, perm_src, y, y_shared,
-                              ws, L, tiles_ready, stream);
+  const fmoe_config& c = ctx->cfg;
+  const bool has_shared = c.n_shared > 0;
+  const int row_cap = n_cap * ctx->kmax;
+  if (n_cap == 0 || (row_cap == 0 && !has_shared)) return FMOE_OK;
+  char* base = static_cast<char*>(ws);
+  const fmoe_ffn_geom geo = fmoe_geom(ctx, n_cap);
+  if (!tiles_ready) {
+    fmoe_prof_scope prof(ctx, SLOT_TILES, stream);
+    hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(256), 0, stream, expert_offsets, c.n_experts,
+                       row_cap, n_cap, n_dev, c.n_shared, geo,
+                       reinterpret_cast<fmoe_tile*>(base + L.tiles),
+                       reinterpret_cast<fmoe_tile*>(base + L.tiles2),
+                       reinterpret_cast<int32_t*>(base + L.tile_count));
   }
-  return run_ffn<float, 1>(ctx, x, kept_idx, n_cap, n_dev, expert_offsets, perm_src, y, y_shared, ws,
-                           L, tiles_ready, stream);
+  int rc;
+  if (c.dtype == FMOE_BF16)
+    rc = run_ffn_bf16(ctx, x, kept_idx, n_cap, perm_src, y, y_shared, base, L, geo, stream);
+  else
+    rc = run_ffn_f32(ctx, x, kept_idx, n_cap, perm_src, y, y_shared, base, L, geo, stream);
+  if (rc != FMOE_OK) return rc;
+  FMOE_HIP_CHECK(hipGetLastError());
+  return FMOE_OK;
 }

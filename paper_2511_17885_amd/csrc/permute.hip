@@ -72,11 +72,12 @@ __global__ __launch_bounds__(PB) void permute_count_kernel(
 __global__ __launch_bounds__(256) void permute_scan_kernel(int n_cap, const int32_t* __restrict__ n_dev,
                                                            int E, int32_t* __restrict__ blk_count,
                                                            int32_t* __restrict__ expert_offsets,
-                                                           int tile_rows, int has_shared, int row_cap,
-                                                           int tile_cap, fmoe_tile* __restrict__ tiles,
+                                                           fmoe_ffn_geom geom, int build, int n_shared,
+                                                           int row_cap, fmoe_tile* __restrict__ tiles1,
+                                                           fmoe_tile* __restrict__ tiles2,
                                                            int32_t* __restrict__ tile_count) {
   __shared__ int total[FMOE_MAX_EXPERTS];
-  __shared__ int scratch[FMOE_MAX_EXPERTS + 1];
+  __shared__ int scratch[256];
   const int n = resolve_count(n_cap, n_dev);
   const int nblk = (n + PB - 1) / PB;
   const int e = threadIdx.x;
@@ -98,11 +99,11 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(int n_cap, const int3
     }
     expert_offsets[E] = acc;
   }
-  if (tile_rows > 0) {   // fused layer path: the grouped-GEMM work list comes out of the same scan
+  if (build) {   // fused layer path: the grouped-GEMM work lists come out of the same scan
     __threadfence_block();
     __syncthreads();
-    fmoe_build_tiles(expert_offsets, E, row_cap, n, has_shared != 0, tile_rows, tile_cap, tiles,
-                     tile_count, scratch);
+    fmoe_build_tiles(expert_offsets, E, row_cap, n, n_shared, geom.bm, geom.tile_cap, geom.cols1,
+                     geom.scols1, tiles1, tiles2, tile_count, scratch);
   }
 }
 
@@ -148,9 +149,9 @@ int launch_permute(const fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* 
     fmoe_prof_scope prof(ctx, SLOT_PERM_SCAN, stream);
     hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(256), 0, stream, (Kmax > 0) ? n_cap : 0,
                        (Kmax > 0) ? n_dev : nullptr, E, blk_count, expert_offsets,
-                       build_tiles ? fmoe_tile_rows(ctx, n_cap) : 0, ctx->cfg.n_shared > 0 ? 1 : 0,
-                       n_cap * Kmax, fmoe_tile_cap(ctx, n_cap),
-                       reinterpret_cast<fmoe_tile*>(base + L.tiles),
+                       fmoe_geom(ctx, n_cap), build_tiles ? 1 : 0, ctx->cfg.n_shared,
+                       n_cap * Kmax, reinterpret_cast<fmoe_tile*>(base + L.tiles),
+                       reinterpret_cast<fmoe_tile*>(base + L.tiles2),
                        reinterpret_cast<int32_t*>(base + L.tile_count));
   }
   if (nblk > 0 && Kmax > 0) {

@@ -1,19 +1,30 @@
-// Device-side construction of the grouped-GEMM work list, shared by the permutation scan (fused
+// Device-side construction of the grouped-GEMM work lists, shared by the permutation scan (fused
 // layer path) and the stand-alone expert-FFN entry point.
 #pragma once
 
 #include "common.h"
 
 #if defined(__HIPCC__)
-// Builds the tile list with one 256-thread block: routed experts first (ascending expert, then
-// ascending rows, `bm` rows per tile), then the dense shared-expert group (group id E) over the
-// n kept tokens if has_shared.  counts[0] = number of tiles.  Experts whose offsets are malformed
+// Builds, with one 256-thread block, the two row-tile lists of the expert FFN (`bm` rows per tile):
+//   list 1 (gate/up GEMM): the dense shared-expert group (group id E, all n kept tokens, hidden
+//     dimension = the N_s experts concatenated) first, then the routed experts;
+//   list 2 (down GEMM): one dense group per shared expert (group id E+s) first, then the routed
+//     experts.
+// Long items go first: the shared groups (every kept token), then the routed experts by
+// descending row count (ties: ascending expert id), so that the short tiles are the ones left to
+// fill the tail of the launch.  A launch gives every entry `cols1` column tiles; the shared group
+// of list 1 may have more (`scols1`): its row tiles are then repeated with a column-tile offset in
+// `col0`.  The row tiles of one group (one replica) are consecutive entries.
+// counts[0], counts[1] = number of entries in list 1 / list 2.  Experts whose offsets are malformed
 // (negative, decreasing or past row_cap) are skipped so that no tile can index outside the row
-// buffers.  `scratch` is 257 ints of LDS.
+// buffers.  `scratch` is 256 ints of LDS; bm is a power of two.
 __device__ __forceinline__ void fmoe_build_tiles(const int32_t* expert_offsets, int E, int row_cap,
-                                                 int n, bool has_shared, int bm, int tile_cap,
-                                                 fmoe_tile* tiles, int32_t* counts, int* scratch) {
+                                                 int n, int n_shared, int bm, int tile_cap, int cols1,
+                                                 int scols1, fmoe_tile* tiles1, fmoe_tile* tiles2,
+                                                 int32_t* counts, int* scratch) {
+  int* s_cnt = scratch;   // rows per expert
   const int e = threadIdx.x;
+  const int sh = 31 - __clz(bm);   // bm is a power of two
   int r0 = 0, cnt = 0;
   if (e < E) {
     r0 = expert_offsets[e];
@@ -21,41 +32,61 @@ __device__ __forceinline__ void fmoe_build_tiles(const int32_t* expert_offsets, 
     cnt = r1 - r0;
     if (r0 < 0 || cnt < 0 || r1 > row_cap) cnt = 0;
   }
-  const int nt = (cnt + bm - 1) / bm;
   __syncthreads();
-  if (e < E) scratch[e + 1] = nt;
-  if (e == 0) scratch[0] = 0;
+  if (e < 256) s_cnt[e] = (e < E) ? cnt : 0;
   __syncthreads();
-  if (threadIdx.x == 0)
-    for (int i = 1; i <= E; ++i) scratch[i] += scratch[i - 1];
-  __syncthreads();
-  const int routed = scratch[E];
-  if (e < E) {
-    for (int j = 0; j < nt; ++j) {
-      const int slot = scratch[e] + j;
+  // first tile slot of expert e = tiles of all experts ahead of it in the (rows desc, id asc) order
+  int start = 0, routed = 0;
+#pragma unroll 8
+  for (int o = 0; o < E; ++o) {
+    const int co = s_cnt[o];
+    const int nto = (co + bm - 1) >> sh;
+    routed += nto;
+    start += ((co > cnt) || (co == cnt && o < e)) ? nto : 0;
+  }
+
+  const int ns = (n_shared > 0) ? (n + bm - 1) / bm : 0;
+  const int rep1 = (ns > 0 && cols1 > 0) ? (scols1 + cols1 - 1) / cols1 : 0;
+  const int sh1 = ns * rep1, sh2 = ns * n_shared;
+  for (int j = threadIdx.x; j < ns; j += blockDim.x) {
+    fmoe_tile t;
+    t.row0 = j * bm;
+    t.rows = (n - j * bm < bm) ? (n - j * bm) : bm;
+    t.rt = j;
+    t.nrt = ns;
+    t.group = E;
+    for (int c = 0; c < rep1; ++c) {   // replica-major: the row tiles of one replica are consecutive
+      const int slot = c * ns + j;
       if (slot >= tile_cap) break;
+      t.col0 = c * cols1;
+      tiles1[slot] = t;
+    }
+    t.col0 = 0;
+    for (int s = 0; s < n_shared; ++s) {
+      const int slot = s * ns + j;
+      if (slot >= tile_cap) break;
+      t.group = E + s;
+      tiles2[slot] = t;
+    }
+  }
+  if (e < E) {
+    const int nt = (cnt + bm - 1) >> sh;
+    for (int j = 0; j < nt; ++j) {
       fmoe_tile t;
       t.group = e;
       t.row0 = r0 + j * bm;
       t.rows = (cnt - j * bm < bm) ? (cnt - j * bm) : bm;
-      t.pad = 0;
-      tiles[slot] = t;
+      t.col0 = 0;
+      t.rt = j;
+      t.nrt = nt;
+      if (sh1 + start + j < tile_cap) tiles1[sh1 + start + j] = t;
+      if (sh2 + start + j < tile_cap) tiles2[sh2 + start + j] = t;
     }
   }
-  const int ns = has_shared ? (n + bm - 1) / bm : 0;
-  for (int j = threadIdx.x; j < ns; j += blockDim.x) {
-    const int slot = routed + j;
-    if (slot >= tile_cap) break;
-    fmoe_tile t;
-    t.group = E;
-    t.row0 = j * bm;
-    t.rows = (n - j * bm < bm) ? (n - j * bm) : bm;
-    t.pad = 0;
-    tiles[slot] = t;
-  }
   if (threadIdx.x == 0) {
-    const int total = routed + ns;
-    counts[0] = total < tile_cap ? total : tile_cap;
+    const int t1 = routed + sh1, t2 = routed + sh2;
+    counts[0] = t1 < tile_cap ? t1 : tile_cap;
+    counts[1] = t2 < tile_cap ? t2 : tile_cap;
   }
 }
 #endif
