@@ -231,7 +231,8 @@ int fmoe_route(fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int32_t T
   if (ctx->kmax > 0 && (!topk_idx || !topk_gate))
     return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_route: topk_idx / topk_gate is NULL");
   if (!aligned16(x)) return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_route: x not 16-byte aligned");
-  return launch_route(ctx, x, is_visual, T, probs, topk_idx, topk_gate, static_cast<hipStream_t>(stream));
+  return launch_route(ctx, x, is_visual, T, probs, topk_idx, topk_gate, fmoe_ordinals_job{},
+                      static_cast<hipStream_t>(stream));
 }
 
 int fmoe_prune(fmoe_ctx* ctx, const fmoe_prune_params* params, const float* probs,
@@ -341,10 +342,31 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
   void* y = base + L.y;
   void* y_shared = ctx->cfg.n_shared > 0 ? base + L.y_shared : nullptr;
 
-  if ((rc = launch_route(ctx, x, is_visual, T, do_prune ? probs : nullptr, topk_idx, topk_gate, s)) != FMOE_OK)
+  const bool small = T > 0 && dispatch_small_fits(T, do_prune ? params->window : 1, do_prune);
+  fmoe_ordinals_job ord{};
+  if (small && do_prune)
+    ord = fmoe_ordinals_job{cu_seqlens, B, reinterpret_cast<int32_t*>(base + L.vis_ord),
+                            reinterpret_cast<int32_t*>(base + L.vis_tok),
+                            reinterpret_cast<int32_t*>(base + L.seq_nv)};
+  if ((rc = launch_route(ctx, x, is_visual, T, do_prune ? probs : nullptr, topk_idx, topk_gate, ord, s)) != FMOE_OK)
     return rc;
   const int32_t* kept = nullptr;
   const int32_t* n_dev = nullptr;
+  if (small) {
+    // a few thousand tokens: scores, then one block for the whole prune/permute chain
+    if ((rc = launch_prune_dispatch_small(ctx, params, do_prune, probs, is_visual, cu_seqlens, B, T,
+                                          attn_importance, topk_idx, kept_idx, new_cu_seqlens,
+                                          is_visual_out, expert_offsets, perm_src, inv_perm, ws, L, s)) != FMOE_OK)
+      return rc;
+    if (do_prune) {
+      kept = kept_idx;
+      n_dev = new_cu_seqlens + B;
+    }
+    if ((rc = launch_expert_ffn(ctx, x, kept, T, n_dev, expert_offsets, perm_src, y, y_shared, ws, L, true, s)) != FMOE_OK)
+      return rc;
+    return launch_combine(ctx, y, y_shared, inv_perm, topk_gate, kept, T, n_dev, add_residual ? x : nullptr,
+                          out, s);
+  }
   if (do_prune) {
     rc = launch_prune(ctx, params, probs, is_visual, cu_seqlens, B, T, attn_importance, kept_idx,
                       new_cu_seqlens, nullptr, is_visual_out, ws, L, s);
@@ -371,7 +393,7 @@ const char* fmoe_profile_name(int slot) {
       "permute_count_kernel", "permute_scan_kernel", "permute_scatter_kernel", "build_tiles_kernel",
       "grouped_gemm_kernel<swiglu> routed", "grouped_gemm_kernel<down> routed",
       "build_dense_tiles_kernel", "grouped_gemm_kernel<swiglu> shared",
-      "grouped_gemm_kernel<down> shared", "combine_kernel"};
+      "grouped_gemm_kernel<down> shared", "combine_kernel", "prune_dispatch_small_kernel"};
   return (slot >= 0 && slot < SLOT_COUNT) ? names[slot] : "";
 }
 

@@ -17,7 +17,7 @@
 enum fmoe_kernel_slot {
   SLOT_ROUTE = 0, SLOT_ORDINALS, SLOT_SCORES, SLOT_SELECT, SLOT_COMPACT, SLOT_PERM_COUNT,
   SLOT_PERM_SCAN, SLOT_PERM_SCATTER, SLOT_TILES, SLOT_GEMM1, SLOT_GEMM2, SLOT_SH_TILES,
-  SLOT_SH_GEMM1, SLOT_SH_GEMM2, SLOT_COMBINE, SLOT_COUNT
+  SLOT_SH_GEMM1, SLOT_SH_GEMM2, SLOT_COMBINE, SLOT_DISPATCH, SLOT_COUNT
 };
 struct fmoe_prof {
   bool on;
@@ -97,13 +97,31 @@ int launch_pack_experts(fmoe_ctx* ctx, hipStream_t stream);
 size_t router_pack_floats(const fmoe_ctx* ctx);
 int launch_pack_router(const fmoe_ctx* ctx, const void* router_w, float* wp, hipStream_t stream);
 
+// Visual ordinals to be produced by extra blocks of the router's launch (Sec. 3.2 needs them before
+// the window scores; they do not depend on the routing).  cu == nullptr: none.
+struct fmoe_ordinals_job {
+  const int32_t* cu;
+  int B;
+  int32_t *vis_ord, *vis_tok, *seq_nv;
+};
 int launch_route(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int T, float* probs,
-                 int32_t* topk_idx, float* topk_gate, hipStream_t stream);
+                 int32_t* topk_idx, float* topk_gate, const fmoe_ordinals_job& ord, hipStream_t stream);
 
 int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* probs,
                  const uint8_t* is_visual, const int32_t* cu_seqlens, int B, int T,
                  const float* attn, int32_t* kept_idx, int32_t* new_cu_seqlens, float* scores_out,
                  uint8_t* is_visual_out, void* ws, const fmoe_ws_layout& L, hipStream_t stream);
+
+// Small batches: window scores, then ONE block for drop order, compaction, permutation by expert and
+// the grouped-GEMM tile lists (prune == false: every token is kept).  Expects the visual ordinals in
+// the workspace (fmoe_ordinals_job) when pruning.
+bool dispatch_small_fits(int T, int window, bool prune);
+int launch_prune_dispatch_small(const fmoe_ctx* ctx, const fmoe_prune_params* pp, bool prune,
+                                const float* probs, const uint8_t* is_visual, const int32_t* cu_seqlens,
+                                int B, int T, const float* attn, const int32_t* topk_idx,
+                                int32_t* kept_idx, int32_t* new_cu_seqlens, uint8_t* is_visual_out,
+                                int32_t* expert_offsets, int32_t* perm_src, int32_t* inv_perm, void* ws,
+                                const fmoe_ws_layout& L, hipStream_t stream);
 
 int launch_identity_kept(const uint8_t* is_visual, const int32_t* cu_seqlens, int B, int T,
                          int32_t* kept_idx, int32_t* new_cu_seqlens, uint8_t* is_visual_out,

@@ -514,7 +514,7 @@ __global__ __launch_bounds__(256) void build_tiles_kernel(const int32_t* __restr
                                                           fmoe_tile* __restrict__ tiles1,
                                                           fmoe_tile* __restrict__ tiles2,
                                                           int32_t* __restrict__ counts) {
-  __shared__ int scratch[256];
+  __shared__ __align__(8) int scratch[513];
   fmoe_build_tiles(expert_offsets, E, row_cap, resolve_count(n_cap, n_dev), n_shared, geom.bm,
                    geom.tile_cap, geom.cols1, geom.scols1, tiles1, tiles2, counts, scratch);
 }

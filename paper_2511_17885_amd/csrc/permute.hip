@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(int n_cap, const int3
                                                            fmoe_tile* __restrict__ tiles2,
                                                            int32_t* __restrict__ tile_count) {
   __shared__ int total[FMOE_MAX_EXPERTS];
-  __shared__ int scratch[256];
+  __shared__ __align__(8) int scratch[513];
   const int n = resolve_count(n_cap, n_dev);
   const int nblk = (n + PB - 1) / PB;
   const int e = threadIdx.x;

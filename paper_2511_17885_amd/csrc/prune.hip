@@ -13,6 +13,8 @@
 // sequence by binary search over cu_seqlens.
 
 #include "common.h"
+#include "prune_dev.h"
+#include "tiles.h"
 
 namespace {
 
@@ -22,25 +24,6 @@ __device__ __forceinline__ float wave_sum_butterfly(float p) {
   return p;
 }
 
-__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
-
-// sequence b covers [seq_begin, seq_end) after clamping to [0,T] and to non-decreasing order, so
-// that a malformed cu_seqlens can never index outside the token arrays.
-__device__ __forceinline__ void seq_range(const int32_t* cu, int b, int T, int& s, int& e) {
-  s = clampi(cu[b], 0, T);
-  e = clampi(cu[b + 1], s, T);
-}
-
-// largest b in [0,B) with cu[b] <= g (cu is non-decreasing, cu[0] = 0)
-__device__ __forceinline__ int find_seq(const int32_t* cu, int B, int g) {
-  int lo = 0, hi = B - 1;
-  while (lo < hi) {
-    const int mid = (lo + hi + 1) >> 1;
-    if (cu[mid] <= g) lo = mid; else hi = mid - 1;
-  }
-  return lo;
-}
-
 // ---- A: visual ordinals.  One block per sequence.
 // vis_ord[t] = number of visual tokens before t in its sequence (for visual t), -1 for text;
 // vis_tok[cu[b] + j] = global index of the j-th visual token of sequence b; seq_nv[b] = N_v.
@@ -48,33 +31,7 @@ __global__ __launch_bounds__(256) void seq_ordinals_kernel(
     const uint8_t* __restrict__ is_visual, const int32_t* __restrict__ cu, int T,
     int32_t* __restrict__ vis_ord, int32_t* __restrict__ vis_tok, int32_t* __restrict__ seq_nv) {
   __shared__ int wave_tot[4];
-  const int b = blockIdx.x;
-  int s, e;
-  seq_range(cu, b, T, s, e);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int running = 0;
-  for (int base = s; base < e; base += 256) {
-    const int t = base + threadIdx.x;
-    const bool vis = (t < e) && (is_visual[t] != 0);
-    const unsigned long long mask = __ballot(vis);
-    const int before = __popcll(mask & ((1ull << lane) - 1ull));
-    if (lane == 0) wave_tot[wave] = __popcll(mask);
-    __syncthreads();
-    int wave_base = 0, total = 0;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      if (w < wave) wave_base += wave_tot[w];
-      total += wave_tot[w];
-    }
-    if (t < e) {
-      const int ord = running + wave_base + before;
-      vis_ord[t] = vis ? ord : -1;
-      if (vis) vis_tok[s + ord] = t;
-    }
-    running += total;
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) seq_nv[b] = running;
+  seq_ordinals_block(is_visual, cu, blockIdx.x, T, vis_ord, vis_tok, seq_nv, wave_tot);
 }
 
 // ---- B: window scores.  One wavefront per slot g in [0,T); lanes <-> experts.
@@ -188,12 +145,6 @@ __global__ __launch_bounds__(256) void window_score_kernel(
 // (possibly shorter) window precedes i.
 constexpr int SEL_JC = 64;
 
-__device__ __forceinline__ uint32_t float_order_key(float v) {   // monotone: a < b <=> key(a) < key(b)
-  v = v + 0.0f;                                                   // -0 -> +0, so equal floats get equal keys
-  const uint32_t u = __float_as_uint(v);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
 __global__ __launch_bounds__(256) void select_kernel(
     const int32_t* __restrict__ cu, int B, int T, int W, float alpha,
     const int32_t* __restrict__ seq_nv, const float* __restrict__ win_s,
@@ -235,17 +186,8 @@ __global__ __launch_bounds__(256) void select_kernel(
       for (int w = 1; w < 4; ++w) amax = (red[w] > amax) ? red[w] : amax;
     }
     auto score = [&](int j, float& Aj) -> float {   // Eq.13 (C = S exactly without attention)
-      const float Sj = win_s[s + j];
-      if (!has_attn) {
-        Aj = 0.0f;
-        return Sj;
-      }
-      float a = win_a[s + j];
-      if (amax > 0.0f) a = a / amax;
-      Aj = a;
-      const float t1 = alpha * Sj;
-      const float t2 = one_minus_alpha * a;
-      return t1 - t2;
+      return redundancy_score(win_s[s + j], has_attn, has_attn ? win_a[s + j] : 0.0f, amax, alpha,
+                              one_minus_alpha, Aj);
     };
     const int i = g - s;
     const bool mine = (g < T) && i >= 0 && i < n;
@@ -290,27 +232,6 @@ __global__ __launch_bounds__(256) void select_kernel(
   }
 }
 
-// number of leading tokens of visual ordinal `ord`'s window that survive (Sec. 3.2.3 budget and the
-// drop rule): windows are dropped whole in drop order while they fit in eps = N_v - eta and the
-// next one loses its last tokens.
-__device__ __forceinline__ int window_keep_lead(int ord, int nv, int W, float retention,
-                                                const int32_t* precede_seq) {
-  const int n = (nv + W - 1) / W;
-  const int i = ord / W;
-  int eta = (int)floor((double)retention * (double)nv + 0.5);   // eta = floor(r*N_v + 1/2), fp64
-  eta = eta > nv ? nv : eta;
-  eta = eta < 1 ? 1 : eta;
-  const int eps = nv - eta;
-  const int pc = precede_seq[i];
-  const int count = pc & 0x3fffffff, last_first = pc >> 30;
-  const int w_last = nv - (n - 1) * W;
-  const int before = count * W - (last_first ? (W - w_last) : 0);
-  const int wi = (i == n - 1) ? w_last : W;
-  if (before + wi <= eps) return 0;
-  if (before < eps) return wi - (eps - before);
-  return wi;
-}
-
 // ---- D: budget + compaction.  A single block walks the tokens in order, keeps text tokens and the
 // leading tokens of each window, and writes ascending kept indices; keep_prefix[t] = kept tokens
 // before t.
@@ -333,7 +254,7 @@ __global__ __launch_bounds__(1024) void compact_kernel(
       } else {
         const int b = find_seq(cu, B, t);
         const int s = clampi(cu[b], 0, T);
-        keep = (ord % W) < window_keep_lead(ord, seq_nv[b], W, retention, precede + s);
+        keep = (ord % W) < window_keep_lead(ord, seq_nv[b], W, retention, precede[s + ord / W]);
       }
     }
     const unsigned long long mask = __ballot(keep);
@@ -372,6 +293,327 @@ __global__ void identity_kept_kernel(const uint8_t* __restrict__ is_visual,
     if (is_visual_out != nullptr) is_visual_out[i] = is_visual[i];
   }
   if (i <= B && new_cu != nullptr) new_cu[i] = clampi(cu[i], 0, T);
+}
+
+// ---- E: small batches.  One 1024-thread block takes the whole chain after the window scores:
+// drop order, budget, compaction, permutation by expert and the grouped-GEMM tile lists, with the
+// intermediate arrays in LDS.  At a few thousand tokens each of those steps is a few microseconds
+// of work and the launches between them cost more than the steps themselves.
+//   * every global input is fetched up front (thread i owns tokens i, i+1024, ...), every global
+//     output is stored at the very end, so no barrier in between waits on memory;
+//   * drop order: the order (normalised attention asc, score desc, index asc) is total, so a
+//     bitonic sort of the integer keys (one window per thread; exchanges inside a wavefront by
+//     lane shuffles, across wavefronts through LDS) gives every window its number of predecessors;
+//   * permutation: as in the stand-alone kernels (per-expert position masks, popcount ranks), one
+//     pass per 1024 tokens, one 64-bit mask word per wavefront.
+constexpr int SB_THREADS = 1024;
+constexpr int SB_MAX_TP = 4;                       // tokens per thread, at most
+constexpr int SB_MAX_T = SB_THREADS * SB_MAX_TP;   // tokens
+constexpr int SB_MAX_NW = 1024;                // windows of one sequence: one sort element per thread
+constexpr int SB_MROW = 17;                    // 64-bit mask words per expert (16 + 1 against bank conflicts)
+constexpr int SB_MAX_B = 512;                  // sequences whose bounds are cached in LDS
+
+struct SmallArgs {
+  int prune;                       // 0: keep every token
+  const uint8_t* is_visual;
+  const int32_t* cu;
+  int B, T, W;
+  float retention, alpha;
+  const int32_t* vis_ord;
+  const int32_t* seq_nv;
+  const float* win_s;
+  const float* win_a;              // null without attention importance
+  int32_t* kept_idx;
+  int32_t* new_cu;
+  uint8_t* is_visual_out;          // may be null
+  const int32_t* topk_idx;
+  int E, Kmax;
+  int32_t* expert_offsets;
+  int32_t* perm_src;
+  int32_t* inv_perm;
+  fmoe_ffn_geom geom;
+  int n_shared, row_cap;
+  fmoe_tile* tiles1;
+  fmoe_tile* tiles2;
+  int32_t* tile_count;
+};
+
+// SB_TP tokens per thread, at most KM experts per token (both fix the size of register arrays).
+template <int SB_TP, int KM>
+__global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallArgs a) {
+  __shared__ uint16_t s_kept[SB_MAX_T];
+  // phase 1: precede u16[SB_MAX_T] | 2 x sort keys u64[SB_MAX_NW] | 2 x sort keys u32[SB_MAX_NW]
+  // phase 2: position masks u64[FMOE_MAX_EXPERTS][SB_MROW]
+  constexpr int U_BYTES = FMOE_MAX_EXPERTS * SB_MROW * 8;
+  static_assert(SB_MAX_T * 2 + SB_MAX_NW * 24 <= U_BYTES, "phase-1 arrays fit");
+  __shared__ __align__(16) unsigned char s_u[U_BYTES];
+  __shared__ int s_off[FMOE_MAX_EXPERTS + 1], s_base[FMOE_MAX_EXPERTS];
+  __shared__ int s_cu[SB_MAX_B + 1], s_nv[SB_MAX_B];
+  __shared__ __align__(8) int s_scr[513];
+  __shared__ uint16_t s_pfx[FMOE_MAX_EXPERTS * 16];   // rows of an expert ahead of each wavefront's tokens
+  __shared__ int wave_tot[16];
+  __shared__ float red[16];
+  __shared__ int s_last;
+  uint16_t* s_pre = reinterpret_cast<uint16_t*>(s_u);
+  unsigned long long* sK = reinterpret_cast<unsigned long long*>(s_u + SB_MAX_T * 2);
+  uint32_t* sA = reinterpret_cast<uint32_t*>(s_u + SB_MAX_T * 2 + SB_MAX_NW * 16);
+  unsigned long long* mask = reinterpret_cast<unsigned long long*>(s_u);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int T = a.T, W = a.W, E = a.E, Kmax = a.Kmax, B = a.B;
+
+  // ---- all global inputs of this thread's tokens
+  int ord_r[SB_TP];
+  uint8_t vis_r[SB_TP];
+  int ex[SB_TP][KM];   // expert per slot, later (expert << 16 | row within the expert)
+#pragma unroll
+  for (int k = 0; k < SB_TP; ++k) {
+    const int t = k * SB_THREADS + tid;
+    ord_r[k] = (a.prune && t < T) ? a.vis_ord[t] : -1;
+    vis_r[k] = (t < T && a.is_visual_out != nullptr) ? a.is_visual[t] : 0;
+#pragma unroll
+    for (int sl = 0; sl < KM; ++sl) {
+      int e = -1;
+      if (sl < Kmax && t < T) e = a.topk_idx[(size_t)t * Kmax + sl];
+      ex[k][sl] = (e >= 0 && e < E) ? e : -1;
+    }
+  }
+  const bool cached = B <= SB_MAX_B;
+  if (cached) {
+    for (int b = tid; b <= B; b += SB_THREADS) s_cu[b] = clampi(a.cu[b], 0, T);
+    if (a.prune)
+      for (int b = tid; b < B; b += SB_THREADS) s_nv[b] = a.seq_nv[b];
+  }
+  __syncthreads();
+  const int32_t* cu = cached ? s_cu : a.cu;   // clamping a clamped bound changes nothing
+  const int32_t* seq_nv = cached ? s_nv : a.seq_nv;
+
+  // ---- drop order per sequence
+  if (a.prune) {
+    const bool has_attn = (a.win_a != nullptr);
+    const float one_minus_alpha = 1.0f - a.alpha;
+    for (int b = 0; b < B; ++b) {   // uniform over the block
+      int s, e;
+      seq_range(cu, b, T, s, e);
+      const int nv = seq_nv[b];
+      int n = (nv + W - 1) / W;
+      n = n < SB_MAX_NW ? n : SB_MAX_NW;   // the launcher only takes batches where this holds
+      if (n <= 0) continue;
+      const float ws_r = (tid < n) ? a.win_s[s + tid] : 0.0f;
+      const float wa_r = (has_attn && tid < n) ? a.win_a[s + tid] : 0.0f;
+      float amax = 0.0f;
+      if (has_attn) {   // per-sequence attention maximum (Eq.12)
+        float m = (wa_r > 0.0f) ? wa_r : 0.0f;
+#pragma unroll
+        for (int sh = 32; sh >= 1; sh >>= 1) {
+          const float o = __shfl_xor(m, sh, 64);
+          m = (o > m) ? o : m;
+        }
+        __syncthreads();
+        if (lane == 0) red[wave] = m;
+        __syncthreads();
+        amax = red[0];
+#pragma unroll
+        for (int w = 1; w < 16; ++w) amax = (red[w] > amax) ? red[w] : amax;
+      }
+      uint32_t ka = ~0u;               // padding sorts behind every window
+      unsigned long long kk = ~0ull;
+      if (tid < n) {
+        float A;
+        const float c = redundancy_score(ws_r, has_attn, wa_r, amax, a.alpha, one_minus_alpha, A);
+        kk = ((unsigned long long)(~float_order_key(c)) << 32) | (uint32_t)tid;
+        ka = float_order_key(A);
+      }
+      int N = 64;
+      while (N < n) N <<= 1;
+      const bool active = tid < N;   // whole wavefronts; the others only keep the barriers company
+      int buf = 0;
+      for (int k = 2; k <= N; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+          uint32_t pa = ka;
+          unsigned long long pk = kk;
+          if (j >= 64) {   // partner in another wavefront: through LDS, buffers alternate
+            if (active) {
+              sK[buf * SB_MAX_NW + tid] = kk;
+              if (has_attn) sA[buf * SB_MAX_NW + tid] = ka;
+            }
+            __syncthreads();
+            if (active) {
+              pk = sK[buf * SB_MAX_NW + (tid ^ j)];
+              if (has_attn) pa = sA[buf * SB_MAX_NW + (tid ^ j)];
+            }
+            buf ^= 1;
+          } else if (active) {
+            const uint32_t lo = __shfl_xor((uint32_t)kk, j, 64);
+            const uint32_t hi = __shfl_xor((uint32_t)(kk >> 32), j, 64);
+            pk = ((unsigned long long)hi << 32) | lo;
+            if (has_attn) pa = __shfl_xor(ka, j, 64);
+          }
+          if (active) {
+            const bool partner_first = (pa < ka) || (pa == ka && pk < kk);
+            const bool want_min = (((tid & j) == 0) == ((tid & k) == 0));
+            if (want_min == partner_first) {
+              ka = pa;
+              kk = pk;
+            }
+          }
+        }
+      }
+      // thread r < n now holds the window at place r of the drop order
+      const int wi = (int)(kk & 0xffffffffu);
+      if (tid < n && wi == n - 1) s_last = tid;
+      __syncthreads();
+      if (tid < n) s_pre[s + wi] = (uint16_t)(tid | ((s_last < tid) ? 0x8000 : 0));
+      __syncthreads();
+    }
+  }
+
+  // ---- budget: text tokens and the leading tokens of each window stay
+  bool keep_r[SB_TP];
+#pragma unroll
+  for (int k = 0; k < SB_TP; ++k) {
+    const int t = k * SB_THREADS + tid;
+    bool keep = false;
+    if (t < T) {
+      const int ord = ord_r[k];
+      if (ord < 0) {
+        keep = true;
+      } else {
+        const int b = find_seq(cu, B, t);
+        const int s = clampi(cu[b], 0, T);
+        const int pc = s_pre[s + ord / W];
+        keep = (ord % W) < window_keep_lead(ord, seq_nv[b], W, a.retention,
+                                            (pc & 0x7fff) | ((pc >> 15) << 30));
+      }
+    }
+    keep_r[k] = keep;
+  }
+  __syncthreads();   // s_pre is dead from here on: the masks take its place
+
+  // ---- compaction + per-expert ranks, one pass per 1024 tokens
+  if (tid < FMOE_MAX_EXPERTS) s_base[tid] = 0;
+  int pos_r[SB_TP];
+  int running = 0;
+#pragma unroll
+  for (int k = 0; k < SB_TP; ++k) {
+    pos_r[k] = -1;
+    if (k * SB_THREADS < T) {   // uniform
+      const int t = k * SB_THREADS + tid;
+      const bool keep = keep_r[k];
+      const unsigned long long m = __ballot(keep);
+      const int before = __popcll(m & ((1ull << lane) - 1ull));
+      if (lane == 0) wave_tot[wave] = __popcll(m);
+      for (int i = tid; i < E * SB_MROW; i += SB_THREADS) mask[i] = 0ull;
+      __syncthreads();
+      int wave_base = 0, total = 0;
+#pragma unroll
+      for (int w = 0; w < 16; ++w) {
+        if (w < wave) wave_base += wave_tot[w];
+        total += wave_tot[w];
+      }
+      if (keep) {
+        pos_r[k] = running + wave_base + before;
+        s_kept[pos_r[k]] = (uint16_t)t;
+#pragma unroll
+        for (int sl = 0; sl < KM; ++sl)
+          if (sl < Kmax && ex[k][sl] >= 0) atomicOr(&mask[ex[k][sl] * SB_MROW + wave], 1ull << lane);
+      }
+      running += total;
+      __syncthreads();
+      // item (expert, wavefront w): rows of the expert so far = earlier passes + wavefronts below w
+      for (int it = tid; it < E * 16; it += SB_THREADS) {   // 16 consecutive lanes share an expert
+        const int e = it >> 4, w = it & 15;
+        const int c = __popcll(mask[e * SB_MROW + w]);
+        const int base = s_base[e];
+        int incl = c;
+#pragma unroll
+        for (int sh = 1; sh < 16; sh <<= 1) {
+          const int o = __shfl_up(incl, sh, 16);
+          if (w >= sh) incl += o;
+        }
+        s_pfx[it] = (uint16_t)(base + incl - c);
+        if (w == 15) s_base[e] = base + incl;   // same wavefront: every lane has read the old value
+      }
+      __syncthreads();
+      if (keep) {
+#pragma unroll
+        for (int sl = 0; sl < KM; ++sl) {
+          if (sl < Kmax && ex[k][sl] >= 0) {
+            const int e = ex[k][sl];
+            const int rank = (int)s_pfx[e * 16 + wave] +
+                             __popcll(mask[e * SB_MROW + wave] & ((1ull << lane) - 1ull));
+            ex[k][sl] = (e << 16) | rank;
+          }
+        }
+      } else {
+#pragma unroll
+        for (int sl = 0; sl < KM; ++sl) ex[k][sl] = -1;
+      }
+      __syncthreads();
+    }
+  }
+  const int n = running;
+
+  // ---- expert offsets: exclusive scan of the (at most 256) totals, four per lane
+  __syncthreads();
+  if (wave == 0) {
+    int c[4], sum = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int e = 4 * lane + q;
+      c[q] = (e < E) ? s_base[e] : 0;
+      sum += c[q];
+    }
+    int incl = sum;
+#pragma unroll
+    for (int sh = 1; sh < 64; sh <<= 1) {
+      const int o = __shfl_up(incl, sh, 64);
+      if (lane >= sh) incl += o;
+    }
+    int excl = incl - sum;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      s_off[4 * lane + q] = excl;
+      excl += c[q];
+    }
+    if (lane == 63) s_off[FMOE_MAX_EXPERTS] = incl;
+  }
+  __syncthreads();
+
+  // ---- grouped-GEMM tile lists
+  fmoe_build_tiles(s_off, E, a.row_cap, n, a.n_shared, a.geom.bm, a.geom.tile_cap, a.geom.cols1,
+                   a.geom.scols1, a.tiles1, a.tiles2, a.tile_count, s_scr);
+
+  // ---- outputs
+  if (tid <= E) a.expert_offsets[tid] = s_off[tid];
+  for (int b = tid; b <= B; b += SB_THREADS) {   // new_cu[b] = kept tokens before the sequence start
+    const int c = clampi(cu[b], 0, T);
+    int lo = 0, hi = n;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if ((int)s_kept[mid] < c) lo = mid + 1; else hi = mid;
+    }
+    a.new_cu[b] = lo;
+  }
+#pragma unroll
+  for (int k = 0; k < SB_TP; ++k) {
+    const int p = pos_r[k];
+    if (p >= 0) {
+      a.kept_idx[p] = k * SB_THREADS + tid;
+      if (a.is_visual_out != nullptr) a.is_visual_out[p] = vis_r[k];
+#pragma unroll
+      for (int sl = 0; sl < KM; ++sl) {
+        if (sl < Kmax) {
+          int row = -1;
+          if (ex[k][sl] >= 0) {
+            row = s_off[ex[k][sl] >> 16] + (ex[k][sl] & 0xffff);
+            if (row < a.row_cap) a.perm_src[row] = p;
+          }
+          a.inv_perm[(size_t)p * Kmax + sl] = row;
+        }
+      }
+    }
+  }
 }
 
 }  // namespace
@@ -429,3 +671,58 @@ int launch_identity_kept(const uint8_t* is_visual, const int32_t* cu_seqlens, in
   FMOE_HIP_CHECK(hipGetLastError());
   return FMOE_OK;
 }
+
+bool dispatch_small_fits(int T, int window, bool prune) {
+  if (T <= 0 || T > SB_MAX_T) return false;
+  return !prune || (T + window - 1) / window <= SB_MAX_NW;
+}
+
+int launch_prune_dispatch_small(const fmoe_ctx* ctx, const fmoe_prune_params* pp, bool prune,
+                                const float* probs, const uint8_t* is_visual, const int32_t* cu_seqlens,
+                                int B, int T, const float* attn, const int32_t* topk_idx,
+                                int32_t* kept_idx, int32_t* new_cu_seqlens, uint8_t* is_visual_out,
+                                int32_t* expert_offsets, int32_t* perm_src, int32_t* inv_perm, void* ws,
+                                const fmoe_ws_layout& L, hipStream_t stream) {
+  char* base = static_cast<char*>(ws);
+  int32_t* vis_tok = reinterpret_cast<int32_t*>(base + L.vis_tok);
+  int32_t* vis_ord = reinterpret_cast<int32_t*>(base + L.vis_ord);
+  int32_t* seq_nv = reinterpret_cast<int32_t*>(base + L.seq_nv);
+  float* win_s = reinterpret_cast<float*>(base + L.win_s);
+  float* win_a = attn ? reinterpret_cast<float*>(base + L.win_a) : nullptr;
+  int32_t* drop_from = reinterpret_cast<int32_t*>(base + L.drop_from);
+  const int E = ctx->cfg.n_experts;
+  if (prune) {   // the visual ordinals were produced in the router's launch
+    fmoe_prof_scope prof(ctx, SLOT_SCORES, stream);
+    hipLaunchKernelGGL(window_score_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, probs, cu_seqlens,
+                       B, T, E, pp->window, pp->sim_mode, vis_tok, seq_nv, attn, win_s, win_a, drop_from);
+  }
+  SmallArgs a;
+  a.prune = prune ? 1 : 0;
+  a.is_visual = is_visual;
+  a.cu = cu_seqlens;
+  a.B = B; a.T = T; a.W = prune ? pp->window : 1;
+  a.retention = prune ? pp->retention : 1.0f;
+  a.alpha = prune ? pp->alpha : 1.0f;
+  a.vis_ord = vis_ord; a.seq_nv = seq_nv; a.win_s = win_s; a.win_a = win_a;
+  a.kept_idx = kept_idx; a.new_cu = new_cu_seqlens; a.is_visual_out = is_visual_out;
+  a.topk_idx = topk_idx;
+  a.E = E; a.Kmax = ctx->kmax;
+  a.expert_offsets = expert_offsets; a.perm_src = perm_src; a.inv_perm = inv_perm;
+  a.geom = fmoe_geom(ctx, T);
+  a.n_shared = ctx->cfg.n_shared;
+  a.row_cap = T * ctx->kmax;
+  a.tiles1 = reinterpret_cast<fmoe_tile*>(base + L.tiles);
+  a.tiles2 = reinterpret_cast<fmoe_tile*>(base + L.tiles2);
+  a.tile_count = reinterpret_cast<int32_t*>(base + L.tile_count);
+  {
+    fmoe_prof_scope prof(ctx, SLOT_DISPATCH, stream);
+    if (T <= 2 * SB_THREADS && ctx->kmax <= 8)
+      hipLaunchKernelGGL((prune_dispatch_small_kernel<2, 8>), dim3(1), dim3(SB_THREADS), 0, stream, a);
+    else
+      hipLaunchKernelGGL((prune_dispatch_small_kernel<SB_MAX_TP, FMOE_MAX_TOPK>), dim3(1), dim3(SB_THREADS),
+                         0, stream, a);
+  }
+  FMOE_HIP_CHECK(hipGetLastError());
+  return FMOE_OK;
+}
+

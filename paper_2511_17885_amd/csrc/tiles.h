@@ -17,12 +17,11 @@
 // `col0`.  The row tiles of one group (one replica) are consecutive entries.
 // counts[0], counts[1] = number of entries in list 1 / list 2.  Experts whose offsets are malformed
 // (negative, decreasing or past row_cap) are skipped so that no tile can index outside the row
-// buffers.  `scratch` is 256 ints of LDS; bm is a power of two.
+// buffers.  `scratch` is 513 ints of LDS (8-byte aligned); bm is a power of two.
 __device__ __forceinline__ void fmoe_build_tiles(const int32_t* expert_offsets, int E, int row_cap,
                                                  int n, int n_shared, int bm, int tile_cap, int cols1,
                                                  int scols1, fmoe_tile* tiles1, fmoe_tile* tiles2,
                                                  int32_t* counts, int* scratch) {
-  int* s_cnt = scratch;   // rows per expert
   const int e = threadIdx.x;
   const int sh = 31 - __clz(bm);   // bm is a power of two
   int r0 = 0, cnt = 0;
@@ -33,17 +32,26 @@ __device__ __forceinline__ void fmoe_build_tiles(const int32_t* expert_offsets, 
     if (r0 < 0 || cnt < 0 || r1 > row_cap) cnt = 0;
   }
   __syncthreads();
-  if (e < 256) s_cnt[e] = (e < E) ? cnt : 0;
-  __syncthreads();
-  // first tile slot of expert e = tiles of all experts ahead of it in the (rows desc, id asc) order
-  int start = 0, routed = 0;
-#pragma unroll 8
-  for (int o = 0; o < E; ++o) {
-    const int co = s_cnt[o];
-    const int nto = (co + bm - 1) >> sh;
-    routed += nto;
-    start += ((co > cnt) || (co == cnt && o < e)) ? nto : 0;
+  // order key: more rows first, then the lower expert id (rows < 2^24, ids < 2^8)
+  const unsigned key = ((unsigned)cnt << 8) | (unsigned)(255 - (e & 255));
+  if (e < 256) {
+    scratch[2 * e] = (e < E) ? (int)key : 0;
+    scratch[2 * e + 1] = (e < E) ? ((cnt + bm - 1) >> sh) : 0;
   }
+  __syncthreads();
+  // first tile slot of expert e = tiles of all experts ahead of it in that order
+  int start = 0, routed = 0;
+  if (e < E) {
+#pragma unroll 8
+    for (int o = 0; o < E; ++o) {
+      const int2 kn = *reinterpret_cast<const int2*>(&scratch[2 * o]);
+      routed += kn.y;
+      start += ((unsigned)kn.x > key) ? kn.y : 0;
+    }
+    if (e == 0) scratch[512] = routed;
+  }
+  __syncthreads();
+  routed = scratch[512];
 
   const int ns = (n_shared > 0) ? (n + bm - 1) / bm : 0;
   const int rep1 = (ns > 0 && cols1 > 0) ? (scols1 + cols1 - 1) / cols1 : 0;
