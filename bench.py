@@ -27,9 +27,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 MFMA_F32_PEAK_TFLOPS = 157.3
 VALU_F32_PEAK_TFLOPS = 157.3
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), scaled
-# by a copy kernel of known size; None until measured (see profiles/).
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch of the dominant kernel on workload c2 from two rocprofv3 --pmc runs
+# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB; the factors are what a 256 MiB device copy reads on the
+# same counters) -- profiles/ffn_stream_c2_hbm_traffic.md.  Other workloads: not measured.
+MEASURED_TRAFFIC_BYTES = {"c2": int((85117.0 * 2.0 + 7617.4) * 1024)}
 
 
 def main():
@@ -117,12 +118,12 @@ def main():
         "route_kernel": dict(bytes=T * d * es + n_vis * E * 4 + T * Kmax * 8 + E * d * 4,
                              flops=2.0 * T * d * E, peak_tflops=MFMA_F32_PEAK_TFLOPS),
         # one launch covers the routed experts and the shared group
-        "grouped_gemm_kernel<swiglu> routed": dict(
+        "ffn_stream_kernel<true>": dict(
             bytes=(touched * 2 * F * d + M * d + M * F + Ns * 2 * Fs * d + n_kept * d * (1 if Ns else 0)
                    + n_kept * Ns * Fs) * es,
             flops=4.0 * M * d * F + 4.0 * n_kept * d * Fs * Ns,
             peak_tflops=MFMA_BF16_PEAK_TFLOPS if is_bf16 else MFMA_F32_PEAK_TFLOPS),
-        "grouped_gemm_kernel<down> routed": dict(
+        "ffn_stream_kernel<false>": dict(
             bytes=(touched * d * F + M * F + M * d + Ns * d * Fs + n_kept * Ns * Fs
                    + n_kept * d * (1 if Ns else 0)) * es,
             flops=2.0 * M * d * F + 2.0 * n_kept * d * Fs * Ns,
@@ -146,13 +147,13 @@ def main():
                        TFLOPs=round(tfl, 2), compute_frac=round(tfl / w["peak_tflops"], 4))
         kernels[name] = ent
 
-    dom = "grouped_gemm_kernel<swiglu> routed"
+    dom = "ffn_stream_kernel<true>"   # gate/up projections + SwiGLU of all experts, routed and shared
     dom_ms = kms.get(dom, 0.0)
     roofline = None
     if dom_ms > 0:
         ach = work[dom]["bytes"] / (dom_ms * 1e-3) / 1e9
         roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                     "algo_bytes_per_launch": int(work[dom]["bytes"]), "us_per_launch": round(dom_ms * 1e3, 2),
                     "mfma_frac": kernels[dom].get("compute_frac")}
 
@@ -167,13 +168,16 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         t0 = time.time()
-        oracle.layer_forward(wl.x, wl.is_visual, wl.cu_seqlens, lw, k_text=wl.k_text,
-                             k_visual=wl.k_visual, is_bf16=is_bf16, retention=wl.retention,
-                             window=wl.window)
+        passes = 0
+        while passes == 0 or (time.time() - t0 < 10.0 and passes < 1000):   # about 10 s of CPU work
+            oracle.layer_forward(wl.x, wl.is_visual, wl.cu_seqlens, lw, k_text=wl.k_text,
+                                 k_visual=wl.k_visual, is_bf16=is_bf16, retention=wl.retention,
+                                 window=wl.window)
+            passes += 1
         dt = time.time() - t0
-        cpu = {"value": round(T / dt, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+        cpu = {"value": round(passes * T / dt, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
                "kind": "oracle", "seconds": round(dt, 2),
-               "sample": f"the whole {wl.name} batch ({T} tokens), one pass of the full layer"}
+               "sample": f"{passes} passes of the full layer over the whole {wl.name} batch ({T} tokens each)"}
 
     line = {
         "metric": "MoE-layer prefill tokens/s (visual-reduced top-k + pruning)",

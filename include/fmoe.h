@@ -147,7 +147,10 @@ int fmoe_permute(fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* kept_idx
 /* The expert FFNs of Eq.4 as a grouped GEMM: for every row r of expert e,
  * y[r] = FFN_e(x[token(perm_src[r])]); the activation silu(.)*(.) is rounded to dtype between
  * the two products.  y [n_kept*Kmax capacity, H] dtype.  y_shared [N_s, n_kept, H] dtype or NULL
- * iff N_s == 0: the output of shared expert i for kept position p at (i*n_kept + p)*H. */
+ * iff N_s == 0: the output of shared expert i for kept position p at (i*n_kept + p)*H.
+ * bf16: rows of x are addressed with 32-bit byte offsets, so every token index in kept_idx must
+ * lie within the first 4 GiB of x (2^32 / (2*H) tokens); hidden buffers beyond 4 GiB are
+ * refused with FMOE_ERR_UNSUPPORTED. */
 int fmoe_expert_ffn(fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int32_t n_kept,
                     const int32_t* n_kept_dev, const int32_t* expert_offsets,
                     const int32_t* perm_src, void* y, void* y_shared, void* ws, size_t ws_bytes,

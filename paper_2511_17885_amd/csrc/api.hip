@@ -327,6 +327,8 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
     return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_layer_forward: x / is_visual / out / kept_idx is NULL");
   if (!aligned16(x) || !aligned16(out))
     return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_layer_forward: x / out not 16-byte aligned");
+  if (ctx->cfg.dtype == FMOE_BF16 && (size_t)T * ctx->cfg.d_model * 2 > 0xffffffffull)
+    return fmoe_fail(FMOE_ERR_UNSUPPORTED, "fmoe_layer_forward: x of %d tokens exceeds 4 GiB", T);
   const bool do_prune = params && params->prune_mode != 0 && params->retention < 1.0f;
   if (params && (rc = check_prune(params)) != FMOE_OK) return rc;
   if ((rc = check_ws(ctx, ws, ws_bytes, T, B)) != FMOE_OK) return rc;
@@ -388,12 +390,12 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
 int fmoe_profile_slots(void) { return SLOT_COUNT; }
 
 const char* fmoe_profile_name(int slot) {
+  // kernel symbols (the two expert GEMMs: bf16 symbol; fp32 contexts run grouped_gemm_kernel)
   static const char* names[SLOT_COUNT] = {
       "route_kernel", "seq_ordinals_kernel", "window_score_kernel", "select_kernel", "compact_kernel",
-      "permute_count_kernel", "permute_scan_kernel", "permute_scatter_kernel", "build_tiles_kernel",
-      "grouped_gemm_kernel<swiglu> routed", "grouped_gemm_kernel<down> routed",
-      "build_dense_tiles_kernel", "grouped_gemm_kernel<swiglu> shared",
-      "grouped_gemm_kernel<down> shared", "combine_kernel", "prune_dispatch_small_kernel"};
+      "prune_dispatch_small_kernel", "permute_count_kernel", "permute_scan_kernel",
+      "permute_scatter_kernel", "build_tiles_kernel", "ffn_stream_kernel<true>",
+      "ffn_stream_kernel<false>", "combine_kernel"};
   return (slot >= 0 && slot < SLOT_COUNT) ? names[slot] : "";
 }
 

@@ -15,9 +15,9 @@
 
 // ---- optional per-kernel timing (instrumentation; off by default)
 enum fmoe_kernel_slot {
-  SLOT_ROUTE = 0, SLOT_ORDINALS, SLOT_SCORES, SLOT_SELECT, SLOT_COMPACT, SLOT_PERM_COUNT,
-  SLOT_PERM_SCAN, SLOT_PERM_SCATTER, SLOT_TILES, SLOT_GEMM1, SLOT_GEMM2, SLOT_SH_TILES,
-  SLOT_SH_GEMM1, SLOT_SH_GEMM2, SLOT_COMBINE, SLOT_DISPATCH, SLOT_COUNT
+  SLOT_ROUTE = 0, SLOT_ORDINALS, SLOT_SCORES, SLOT_SELECT, SLOT_COMPACT, SLOT_DISPATCH,
+  SLOT_PERM_COUNT, SLOT_PERM_SCAN, SLOT_PERM_SCATTER, SLOT_TILES, SLOT_GEMM1, SLOT_GEMM2,
+  SLOT_COMBINE, SLOT_COUNT
 };
 struct fmoe_prof {
   bool on;

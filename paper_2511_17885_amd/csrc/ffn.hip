@@ -15,9 +15,10 @@
 //    coalescing and DRAM page locality -- and every weight byte is fetched by exactly one wavefront
 //    per row tile.
 //  * a block owns a 128-row tile of one expert and 4 column blocks (one per wavefront); the
-//    gathered activation rows go through a double-buffered LDS tile; both streams are kept PF
-//    k-tiles ahead in registers, in a loop whose steady state has no predicated loads so the
-//    hardware wait counters can be set exactly.
+//    gathered activation rows are loaded straight from global memory into a 4-stage LDS ring
+//    (buffer_load ... lds: no register hop, no LDS store instructions) in a bank-conflict-free
+//    swizzled layout; both streams run 3 k-tiles ahead, in a loop whose steady state has no
+//    predicated loads so the hardware wait counters can be set exactly.
 //  * the ragged per-expert row counts become device-built lists of row tiles (tiles.h); the
 //    always-on shared experts are one more dense group in the same lists and the same launch,
 //    treated as ONE FFN whose hidden dimension is the concatenation of the N_s experts, so their
@@ -45,8 +46,9 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
 
 // ======================================================================== bf16: weight-stream kernel
 constexpr int SBM = 128;        // rows per tile: 8 MFMA row blocks of 16
-constexpr int SBK = 64;         // k per tile: two 32-wide MFMA steps
-constexpr int SLDK = SBK + 8;   // LDS row stride in elements (144 bytes)
+constexpr int SBK = 64;         // k per tile: two 32-wide MFMA steps; one LDS row = 128 bytes
+constexpr int A_STAGES = 4;     // LDS ring of activation k-tiles
+constexpr int B_SLOTS = 4;      // register ring of weight k-tiles
 
 struct StreamProblem {
   const bf16_t* A;            // [*, lda]
@@ -75,15 +77,80 @@ struct StreamArgs {
   int cols;                   // column tiles per tile entry in this launch
 };
 
+// s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt = bits 15:14 | 3:0)
+#define FMOE_WAIT_VM(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
+__device__ __forceinline__ void wait_vm_upto(int n) {   // n not known at compile time (loop tails)
+  switch (n < 0 ? 0 : n) {
+    case 0: FMOE_WAIT_VM(0); break;
+    case 1: case 2: case 3: FMOE_WAIT_VM(1); break;
+    case 4: case 5: case 6: case 7: FMOE_WAIT_VM(4); break;
+    case 8: case 9: case 10: case 11: FMOE_WAIT_VM(8); break;
+    case 12: case 13: case 14: case 15: FMOE_WAIT_VM(12); break;
+    case 16: case 17: case 18: case 19: FMOE_WAIT_VM(16); break;
+    default: FMOE_WAIT_VM(20); break;
+  }
+}
+// NRB operand fragments (16 bytes per lane each, 2048 bytes apart) from LDS byte address `addr`,
+// valid on return.  Written as one block of machine instructions so that the compiler, which knows
+// nothing about the asynchronous global->LDS loads that filled the tile, neither adds waits for them
+// here nor touches the destination registers before the LDS counter has drained.
+template <int NRB>
+__device__ __forceinline__ void lds_read_frags(uint32_t addr, u32x4_t (&f)[NRB]) {
+  static_assert(NRB == 2 || NRB == 4 || NRB == 6 || NRB == 8, "one to four 32-row bands");
+  if constexpr (NRB == 2) {
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:2048\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(f[0]), "=&v"(f[1]) : "v"(addr) : "memory");
+  } else if constexpr (NRB == 4) {
+    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:2048\n\t"
+                 "ds_read_b128 %2, %4 offset:4096\n\tds_read_b128 %3, %4 offset:6144\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]), "=&v"(f[3]) : "v"(addr) : "memory");
+  } else if constexpr (NRB == 6) {
+    asm volatile("ds_read_b128 %0, %6\n\tds_read_b128 %1, %6 offset:2048\n\t"
+                 "ds_read_b128 %2, %6 offset:4096\n\tds_read_b128 %3, %6 offset:6144\n\t"
+                 "ds_read_b128 %4, %6 offset:8192\n\tds_read_b128 %5, %6 offset:10240\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]), "=&v"(f[3]), "=&v"(f[4]), "=&v"(f[5])
+                 : "v"(addr) : "memory");
+  } else {
+    asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %8 offset:2048\n\t"
+                 "ds_read_b128 %2, %8 offset:4096\n\tds_read_b128 %3, %8 offset:6144\n\t"
+                 "ds_read_b128 %4, %8 offset:8192\n\tds_read_b128 %5, %8 offset:10240\n\t"
+                 "ds_read_b128 %6, %8 offset:12288\n\tds_read_b128 %7, %8 offset:14336\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]), "=&v"(f[3]), "=&v"(f[4]), "=&v"(f[5]),
+                   "=&v"(f[6]), "=&v"(f[7])
+                 : "v"(addr) : "memory");
+  }
+}
+#define FMOE_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
 // One (row tile, column tile) work item.  NAB = number of live 32-row bands of the tile (1..4):
 // a compile-time constant, so the k loop below is straight-line code with a fixed number of loads,
 // LDS reads and matrix instructions per step, and rows past the last live band cost nothing.
-//   weights:     register ring of 4 k-tiles per wavefront (3 in flight while 1 is multiplied)
-//   activations: register ring of 2 k-tiles per thread feeding a double-buffered LDS tile
+//   weights:     register ring of B_SLOTS k-tiles per wavefront (B_SLOTS-1 in flight)
+//   activations: LDS ring of A_STAGES k-tiles filled by direct global->LDS loads (no register hop,
+//                no LDS store instructions; A_STAGES-1 in flight).  Such a load drops the 64 lanes'
+//                16-byte pieces at consecutive LDS addresses, so which (row, k chunk) a lane fetches
+//                decides the LDS layout: rows are 128 bytes, and row r keeps its 16-byte chunk c at
+//                position c ^ ((r >> 1) & 7), which makes the 16 rows x 16 bytes read for one matrix
+//                operand fall on 16 different bank groups without any padding.
+// Workgroup barrier without the memory fence of __syncthreads(): a fence would wait for EVERY
+// outstanding global->LDS load (they count as stores to LDS), i.e. drain the prefetch ring each
+// step.  What the barrier has to order here is covered explicitly: a wavefront waits for its own
+// loads of the tile about to be read (FMOE_WAIT_VM) before the barrier, and its LDS reads of the
+// previous tile have returned (lds_read_frags) before it.
+__device__ __forceinline__ void block_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 template <bool SWIGLU, int NAB>
 __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_tile& tile, int group, int nt,
-                                            bf16_t (*As)[SBM * SLDK]) {
+                                            bf16_t* As) {
   constexpr int NRB = 2 * NAB;   // 16-row MFMA blocks computed
+  constexpr int PER_STEP = NAB + 4;   // loads a wavefront issues per k step
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int N = P.N, K = P.K;
   const int NT = (K + SBK - 1) / SBK;
@@ -93,20 +160,27 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
   nbw = nbw < P.nbw ? nbw : P.nbw - 1;     // past N: recompute the last block, never stored
   const u32x4_t* bsrc = P.Bp + (size_t)group * P.group_stride + (size_t)nbw * P.ks * 128 + lane;
 
-  // activation chunks of this thread (NAB x 16 bytes per k-tile); rows past the tile reuse its last row
-  const bf16_t* a_src[NAB];
-  const int a_kc = (tid & 7) * 8;
-  const int a_lo = (tid >> 3) * SLDK + a_kc;
+  // activation pieces of this lane: rows 32*it + 8*wave + lane/8, LDS position lane%8 of the row,
+  // i.e. k chunk (lane%8) ^ ((row >> 1) & 7); rows past the tile reuse its last row
+  // (addressed as byte offsets into one buffer descriptor over A: the buffer form of the
+  // global->LDS load is an ordinary vector-memory instruction to the compiler, whereas the
+  // flat/global form makes it drain every outstanding load whenever it waits for one)
+  uint32_t a_src[NAB];
+  const __amdgpu_buffer_rsrc_t a_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(P.A), 0, 0xffffffff, 0x00020000);
+  const int a_kc = ((lane & 7) ^ ((4 * wave + (lane >> 4)) & 7)) * 8;
+  const uint32_t a_max_row = 0xffffffffu / ((uint32_t)P.lda * 2u) - 1u;
 #pragma unroll
   for (int it = 0; it < NAB; ++it) {
-    const int r = (tid >> 3) + 32 * it;
+    const int r = 32 * it + 8 * wave + (lane >> 3);
     int src = tile.row0 + (r < tile.rows ? r : tile.rows - 1);
     if (P.map1) {
       src = P.map1[src];
       if (P.map1_limit > 0) src = src < 0 ? 0 : (src >= P.map1_limit ? P.map1_limit - 1 : src);
     }
     if (P.map2) src = P.map2[src];
-    a_src[it] = P.A + (size_t)src * P.lda;
+    src = (uint32_t)src < a_max_row ? src : (int)a_max_row;   // offsets stay below 4 GiB whatever the input
+    a_src[it] = (uint32_t)src * (uint32_t)P.lda * 2u;
   }
 
   f32x4_t acc[NRB][2];
@@ -115,8 +189,7 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
 #pragma unroll
     for (int f = 0; f < 2; ++f) acc[rb][f] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  u32x4_t breg[4][2][2];   // [ring slot][k step][fragment]
-  u32x4_t areg[2][NAB];
+  u32x4_t breg[B_SLOTS][2][2];   // [ring slot][k step][fragment]
   auto loadB = [&](int slot, int t) {
 #pragma unroll
     for (int s = 0; s < 2; ++s)
@@ -125,96 +198,136 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
   };
   // k past K (ragged last tile): the address is clamped into the row; the packed weights are zero
   // there, so the product vanishes without predicating the load
-  auto loadA = [&](int slot, int t) {
+  auto loadA = [&](int stage, int t) {
     const int k = t * SBK + a_kc;
     const int kk = k < K ? k : K - 8;
 #pragma unroll
-    for (int it = 0; it < NAB; ++it) areg[slot][it] = *reinterpret_cast<const u32x4_t*>(a_src[it] + kk);
-  };
-  auto storeA = [&](int slot, int buf) {
-#pragma unroll
     for (int it = 0; it < NAB; ++it)
-      *reinterpret_cast<u32x4_t*>(&As[buf][a_lo + it * 32 * SLDK]) = areg[slot][it];
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          a_rsrc, FMOE_LPTR(As + stage * (SBM * SBK) + (32 * it + 8 * wave) * SBK), 16,
+          a_src[it] + (uint32_t)kk * 2u, 0, 0, 0);
   };
-  const int frag_off = (lane & 15) * SLDK + 8 * (lane >> 4);
-  auto compute = [&](int slot, int buf) {
+  // LDS byte address of this lane's operand piece in row block 0 of stage 0, for the two 32-wide k steps
+  const uint32_t lds0 = (uint32_t)(uintptr_t)FMOE_LPTR(As);
+  const uint32_t frag_row = lds0 + (uint32_t)(lane & 15) * (SBK * 2);
+  const uint32_t frag_a0 = frag_row + (uint32_t)(((lane >> 4)) ^ ((lane & 15) >> 1)) * 16;
+  const uint32_t frag_a1 = frag_row + (uint32_t)(((lane >> 4) + 4) ^ ((lane & 15) >> 1)) * 16;
+  auto compute = [&](int slot, int stage) {
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       const bf16x8_t fb0 = __builtin_bit_cast(bf16x8_t, breg[slot][s][0]);
       const bf16x8_t fb1 = __builtin_bit_cast(bf16x8_t, breg[slot][s][1]);
-      bf16x8_t fa[NRB];
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb)
-        fa[rb] = *reinterpret_cast<const bf16x8_t*>(&As[buf][rb * 16 * SLDK + frag_off + s * 32]);
+      u32x4_t fa[NRB];
+      lds_read_frags<NRB>((s ? frag_a1 : frag_a0) + (uint32_t)stage * (SBM * SBK * 2), fa);
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) {
-        acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[rb], fb0, acc[rb][0], 0, 0, 0);
-        acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[rb], fb1, acc[rb][1], 0, 0, 0);
+        const bf16x8_t a8 = __builtin_bit_cast(bf16x8_t, fa[rb]);
+        acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, fb0, acc[rb][0], 0, 0, 0);
+        acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, fb1, acc[rb][1], 0, 0, 0);
       }
     }
   };
 
-  // prologue: weights of tiles 0..2, activations of tiles 0..2 (tile 0 already in LDS buffer 0)
-#pragma unroll
-  for (int q = 0; q < 3; ++q)
-    if (q < NT) loadB(q, q);
-  loadA(0, 0);
-  if (1 < NT) loadA(1, 1);
-  storeA(0, 0);
-  if (2 < NT) loadA(0, 2);
-  __syncthreads();
-
-  // step t (u = t mod 4): publish tile t+1 to the other LDS buffer, start the loads of tile t+3,
-  // multiply tile t, barrier
+  // Step t issues the activations of tile t + A_AHEAD and the weights of tile t + B_AHEAD (in an
+  // order the compiler may choose, but never across the barrier that opens a step); the prologue
+  // replays the steps before 0 the same way.  Loads land in issue order, so "all but the newest
+  // (A_AHEAD-1)*PER_STEP loads have landed" implies "tile t's activations are in LDS".
+  constexpr int A_AHEAD = A_STAGES - 1, B_AHEAD = B_SLOTS - 1;
+  constexpr int NEWER = (A_AHEAD - 1) * PER_STEP;
+  constexpr int UNROLL = 4;    // a multiple of both ring sizes: slots and stages are compile-time
+  static_assert(UNROLL % A_STAGES == 0 && UNROLL % B_SLOTS == 0, "ring indices must be static");
+  static_assert(A_AHEAD <= B_AHEAD, "the prologue below starts with the weights");
   int t = 0;
-  for (; t + 7 <= NT; t += 4) {   // steady state: every load is unconditional
+  if (UNROLL + B_AHEAD <= NT) {
+    // the steady loop will run: an unconditional prologue, so that the compiler's own count of the
+    // loads in flight at the loop head is exact (a conditional one makes it wait for all of them)
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      storeA((u + 1) & 1, (u + 1) & 1);
-      loadA((u + 1) & 1, t + u + 3);
-      loadB((u + 3) & 3, t + u + 3);
-      compute(u, u & 1);
-      __syncthreads();
+    for (int q = -B_AHEAD; q < 0; ++q) {
+      if (q + A_AHEAD >= 0) loadA((q + A_AHEAD) % A_STAGES, q + A_AHEAD);
+      loadB(q + B_AHEAD, q + B_AHEAD);
+      asm volatile("" ::: "memory");   // keeps the steps' loads apart
+    }
+    for (; t + UNROLL + B_AHEAD <= NT; t += UNROLL) {   // steady state: every load is unconditional
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) {
+        FMOE_WAIT_VM(NEWER);
+        block_barrier();   // every wavefront's share of tile t+u is in LDS; all are done with tile t+u-1
+        loadA((u + A_AHEAD) % A_STAGES, t + u + A_AHEAD);
+        loadB((u + B_AHEAD) % B_SLOTS, t + u + B_AHEAD);
+        compute(u % B_SLOTS, u % A_STAGES);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int q = -B_AHEAD; q < 0; ++q) {
+      if (q + A_AHEAD >= 0 && q + A_AHEAD < NT) loadA((q + A_AHEAD) % A_STAGES, q + A_AHEAD);
+      if (q + B_AHEAD < NT) loadB(q + B_AHEAD, q + B_AHEAD);
+      asm volatile("" ::: "memory");
     }
   }
-  for (; t < NT; t += 4) {        // drain
+  for (; t < NT; t += UNROLL) {        // tail: the number of newer loads shrinks as issuing stops
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (t + u < NT) {
-        if (t + u + 1 < NT) storeA((u + 1) & 1, (u + 1) & 1);
-        if (t + u + 3 < NT) {
-          loadA((u + 1) & 1, t + u + 3);
-          loadB((u + 3) & 3, t + u + 3);
+    for (int u = 0; u < UNROLL; ++u) {
+      const int tt = t + u;
+      if (tt < NT) {
+        int newer = 0;   // loads issued in the steps after the one that fetched tile tt's activations
+#pragma unroll
+        for (int q = 1; q < A_AHEAD; ++q) {
+          const int st = tt - A_AHEAD + q;   // issuing step
+          newer += (st + A_AHEAD < NT ? NAB : 0) + (st + B_AHEAD < NT ? 4 : 0);
         }
-        compute(u, u & 1);
-        __syncthreads();
+        wait_vm_upto(newer);
+        block_barrier();
+        if (tt + A_AHEAD < NT) loadA((u + A_AHEAD) % A_STAGES, tt + A_AHEAD);
+        if (tt + B_AHEAD < NT) loadB((u + B_AHEAD) % B_SLOTS, tt + B_AHEAD);
+        compute(u % B_SLOTS, u % A_STAGES);
       }
     }
   }
 
-  // epilogue: accumulator register v of lane l holds row 4*(l/16) + v, column l%16 of a 16x16 block
+  // epilogue: accumulator register v of lane l holds row 4*(l/16) + v, column l%16 of a 16x16 block.
+  // The block's output tile is transposed through LDS (the activation ring is free by now) so that
+  // global memory sees whole 128/256-byte row segments instead of 32-byte pieces.
+  constexpr int BC = SWIGLU ? 64 : 128;    // output columns of the block
+  constexpr int CS = BC + 8;               // LDS row stride (elements): rows 4 apart land 16 banks apart
+  static_assert(SBM * CS <= A_STAGES * SBM * SBK, "output tile fits in the activation ring");
+  block_barrier();   // every wavefront has read its last operands
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) {
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int row = rb * 16 + 4 * (lane >> 4) + v;
-      if (row >= tile.rows) continue;
-      bf16_t* crow = P.C + (size_t)(tile.row0 + row) * P.ldc;
       if (SWIGLU) {
-        const int col = nt * 64 + wave * 16 + (lane & 15);
-        if (col < N) crow[col] = f32_to_bf16(silu_mul(acc[rb][0][v], acc[rb][1][v]));
+        As[row * CS + wave * 16 + (lane & 15)] = f32_to_bf16(silu_mul(acc[rb][0][v], acc[rb][1][v]));
       } else {
-        const int col = nt * 128 + wave * 32 + (lane & 15);
-        if (col < N) crow[col] = f32_to_bf16(acc[rb][0][v]);
-        if (col + 16 < N) crow[col + 16] = f32_to_bf16(acc[rb][1][v]);
+        As[row * CS + wave * 32 + (lane & 15)] = f32_to_bf16(acc[rb][0][v]);
+        As[row * CS + wave * 32 + 16 + (lane & 15)] = f32_to_bf16(acc[rb][1][v]);
       }
+    }
+  }
+  __syncthreads();
+  constexpr int CPR = BC / 8;              // 16-byte chunks per row
+  constexpr int RPP = 256 / CPR;           // rows per pass of the block
+  const int col = nt * BC + (tid % CPR) * 8;
+  const bool vec_ok = ((P.ldc & 7) == 0) && (col + 8 <= N) &&
+                      ((reinterpret_cast<uintptr_t>(P.C) & 15) == 0);
+#pragma unroll
+  for (int r0 = 0; r0 < 32 * NAB; r0 += RPP) {
+    const int row = r0 + tid / CPR;
+    if (row >= tile.rows || col >= N) continue;
+    const bf16_t* src = &As[row * CS + (tid % CPR) * 8];
+    bf16_t* dst = P.C + (size_t)(tile.row0 + row) * P.ldc + col;
+    if (vec_ok) {
+      *reinterpret_cast<u32x4_t*>(dst) = *reinterpret_cast<const u32x4_t*>(src);
+    } else {
+      for (int i = 0; i < 8 && col + i < N; ++i) dst[i] = src[i];
     }
   }
 }
 
 template <bool SWIGLU>
 __global__ __launch_bounds__(256) void ffn_stream_kernel(StreamArgs a) {
-  __shared__ __align__(16) bf16_t As[2][SBM * SLDK];
+  __shared__ __align__(16) bf16_t As[A_STAGES * SBM * SBK];
 
   // One work item per block: item -> (batch of 8 row tiles, column tile, tile within the batch =
   // XCD).  Blocks past the device-side tile count leave at once.
@@ -239,11 +352,12 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(StreamArgs a) {
   // column tiles this entry really has
   const int c_eff = (P.n_col_tiles - tile.col0 < a.cols) ? (P.n_col_tiles - tile.col0) : a.cols;
   if (nt_launch >= c_eff) return;
-  // A group with 2..8 row tiles sits on that many XCDs (consecutive tile indices).  Its blocks are
-  // re-dealt column-major: XCD r takes the contiguous run [r*C, (r+1)*C) of items ordered by
-  // (column tile, row tile), i.e. ALL row tiles of ~C/R column tiles, so each weight column block is
-  // fetched by one XCD only (weights outweigh the activation rows, which every XCD then reads).
-  if (tile.nrt > 1 && tile.nrt <= 8) {
+  // A group with several row tiles sits on as many XCDs (consecutive tile indices).  Its blocks are
+  // re-dealt column-major: the items, ordered by (column tile, row tile), are cut into runs of C, one
+  // run per original row tile, i.e. an XCD gets ALL row tiles of ~C/R column tiles, so each weight
+  // column block is fetched by one XCD (two at a run boundary) instead of by all of them (weights
+  // outweigh the activation rows, which every XCD then reads).
+  if (tile.nrt > 1) {
     const int w = tile.rt * c_eff + nt_launch;
     const int r2 = w % tile.nrt;
     nt_launch = w / tile.nrt;
@@ -635,6 +749,9 @@ int run_ffn_bf16(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, in
   const fmoe_config& c = ctx->cfg;
   const int d = c.d_model, E = c.n_experts, F = c.d_ffn;
   const int Ft = c.n_shared * c.d_ffn_shared;
+  // activation rows are addressed with 32-bit byte offsets
+  if ((size_t)n_cap * ctx->kmax * F * 2 > 0xffffffffull || (size_t)n_cap * Ft * 2 > 0xffffffffull)
+    return fmoe_fail(FMOE_ERR_UNSUPPORTED, "expert FFN: a hidden buffer of %d rows exceeds 4 GiB", n_cap);
   int32_t* tile_count = reinterpret_cast<int32_t*>(base + L.tile_count);
   StreamArgs g1{}, g2{};
   g1.E = g2.E = E;
