@@ -7,6 +7,7 @@ been built, loading raises.
 from __future__ import annotations
 
 import ctypes as C
+import math
 import os
 from typing import Optional
 
@@ -246,3 +247,47 @@ class FMoE:
                                            _ptr(new_cu), _ptr(is_visual_out), _ptr(ws), ws.numel(),
                                            _stream()))
         return out, kept_idx, new_cu, is_visual_out
+
+
+def kept_count(visual_lens, text_lens, retention):
+    """T' of a pruned batch, on the host: eta_b = floor(r*N_v + 1/2) clamped to [min(1,N_v), N_v] visual
+    tokens of every sequence survive (Sec. 3.2.3), all text tokens do.  Pure integer bookkeeping that
+    lets a caller size the next layer's call without reading the device."""
+    total = 0
+    for nv, nt in zip(visual_lens, text_lens):
+        eta = int(math.floor(float(retention) * nv + 0.5))
+        eta = min(max(eta, min(1, nv)), nv)
+        total += eta + nt
+    return total
+
+
+class FMoEStack:
+    """A stack of MoE layers with x <- x + MoE_l(x), per-layer (k_text, k_visual) and one pruning
+    point (Sec. 3.1: reduced activation from layer l_v on; Sec. 3.2: pruning once the routing has
+    settled).  Host-side sequencing only: every layer is one fmoe_layer_forward enqueue; the token
+    count handed to the layers after the pruning point comes from `kept_count`."""
+
+    def __init__(self, layers, k_schedule, prune_after_layer=None, params=None):
+        self.layers = list(layers)
+        self.k_schedule = [tuple(k) for k in k_schedule]
+        self.prune_after_layer = prune_after_layer
+        self.params = params
+        assert len(self.layers) == len(self.k_schedule)
+
+    def forward(self, x, is_visual, cu_seqlens, visual_lens, text_lens):
+        """visual_lens / text_lens: per-sequence token counts on the host.  Returns (x_out [T', d],
+        kept_idx [T'] indices into the input batch or None, new_cu_seqlens)."""
+        T = x.shape[0]
+        kept_total = None
+        for l, layer in enumerate(self.layers):
+            layer.set_topk(*self.k_schedule[l])
+            if l == self.prune_after_layer and self.params is not None:
+                out, kept, new_cu, vis_out = layer.layer_forward(x, is_visual, cu_seqlens, self.params,
+                                                                 add_residual=True, want_mask=True)
+                T = kept_count(visual_lens, text_lens, self.params.retention)
+                x, is_visual, cu_seqlens = out[:T], vis_out[:T], new_cu
+                kept_total = kept[:T]
+            else:
+                out, _, _, _ = layer.layer_forward(x, is_visual, cu_seqlens, None, add_residual=True)
+                x = out[:T]
+        return x, kept_total, cu_seqlens

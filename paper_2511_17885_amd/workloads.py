@@ -238,14 +238,14 @@ def config5_lengths(seed: int = 4, n_seqs: int = 8, lo: int = 1024, hi: int = 64
 
 
 def config5(n_layers: int = 12, d: int = 2048, E: int = 64, F: int = 1408, n_shared: int = 2,
-            len_div: int = 1, n_seqs: int = 8, text_len: int = 128) -> Workload:
+            len_div: int = 1, n_seqs: int = 8, text_len: int = 128, dtype: str = BF16) -> Workload:
     """Ragged batched prefill: 8 packed sequences (visual 1024..6400 step 256, +128 text),
     a 12-layer stack of config-3-shaped layers with x <- x + MoE(x); top-6/top-6 in layers
     0-1, top-6/top-3 from layer 2; pruning to 50 % once, after layer 2, per sequence.
     `len_div`, `d`, `F`, `n_layers` shrink it for tests the oracle must finish quickly."""
     lens = [max(1, v // len_div) for v in config5_lengths(n_seqs=n_seqs)]
     sched = [(6, 6) if l < 2 else (6, 3) for l in range(n_layers)]
-    return make_workload("c5_ragged_stack", seed=4, dtype=BF16, d=d, E=E, F=F, n_shared=n_shared,
+    return make_workload("c5_ragged_stack", seed=4, dtype=dtype, d=d, E=E, F=F, n_shared=n_shared,
                          k_text=6, k_visual=3, retention=0.5, window=3,
                          visual_lens=lens, text_lens=[max(1, text_len // len_div)] * n_seqs,
                          n_components=192, bias_std=1.0, n_layers=n_layers,

@@ -316,3 +316,74 @@ def test_config3_dsvl2_small_half_retention_sampled():
 
 def test_config4_internvl35_sampled():
     assert _check_config(W.config4(), sample=48) == 3968 + 256
+
+
+@pytest.mark.parametrize("retention,kept_visual", [(0.25, 960), (0.75, 2880)])
+def test_config3_retention_sweep_sampled(retention, kept_visual):
+    assert _check_config(W.config3(retention), sample=32) == kept_visual + 256
+
+
+def test_config3_full_activation_no_pruning_sampled():
+    # the standard MoE layer (k 6/6, r = 1): the compute-bound end of the expert GEMM
+    wl = W.config3(1.0, k_visual=6)
+    assert _check_config(wl, sample=32) == wl.T
+
+
+# ---------------------------------------------------------------- the ragged multi-layer stack
+def _oracle_stack(wl):
+    """x <- x + MoE_l(x) layer by layer on the CPU; pruning once, after `prune_after_layer`."""
+    is_bf16 = wl.dtype == W.BF16
+    x, vis, cu = wl.x, wl.is_visual, wl.cu_seqlens
+    kept_total = None
+    for l, lw in enumerate(wl.layers):
+        kt, kv = wl.k_schedule[l]
+        prune_here = l == wl.prune_after_layer
+        o = oracle.layer_forward(x, vis, cu, lw, k_text=kt, k_visual=kv, is_bf16=is_bf16,
+                                 retention=wl.retention if prune_here else 1.0, window=wl.window,
+                                 add_residual=True, do_prune=prune_here)
+        if prune_here:
+            kept_total = o["kept_idx"]
+            vis, cu = vis[kept_total], o["new_cu_seqlens"]
+        x = o["out"]
+    return x, kept_total, cu
+
+
+def _gpu_stack(wl):
+    layers = [make_layer(wl, layer=l) for l in range(len(wl.layers))]
+    stack = binding.FMoEStack(layers, wl.k_schedule, wl.prune_after_layer,
+                              binding.prune_params(retention=wl.retention, window=wl.window, prune_mode=2))
+    x, vis, cu = inputs(wl)
+    lens = np.diff(wl.cu_seqlens)
+    nv = [int(wl.is_visual[s:e].sum()) for s, e in zip(wl.cu_seqlens[:-1], wl.cu_seqlens[1:])]
+    nt = [int(n - v) for n, v in zip(lens, nv)]
+    out, kept, new_cu = stack.forward(x, vis, cu, nv, nt)
+    torch.cuda.synchronize()
+    return host(out), host(kept), host(new_cu), nv, nt
+
+
+def test_stack_ragged_12_layers_fp32():
+    # config 5 in structure (8 ragged sequences, 12 layers, k 6/6 then 6/3, pruning after layer 2)
+    # at sizes the oracle finishes in seconds; fp32 storage keeps the two sides' activations within
+    # 1e-6 of each other, so every routing and pruning decision down the stack must agree
+    wl = W.config5(n_layers=12, d=128, E=64, F=64, len_div=32, text_len=128, dtype=W.F32)
+    out, kept, new_cu, nv, nt = _gpu_stack(wl)
+    ref, ref_kept, ref_cu = _oracle_stack(wl)
+    assert np.array_equal(new_cu, ref_cu)
+    assert np.array_equal(kept, ref_kept)
+    assert out.shape[0] == binding.kept_count(nv, nt, wl.retention) == ref.shape[0]
+    assert max_rel_err(out, ref) <= 12 * TOL[W.F32]      # one layer's bound per layer
+
+
+def test_stack_ragged_bf16_prune_point():
+    # bf16 storage: layers 0-2 (the two full-activation layers and the pruning layer).  Rounding
+    # differences between the sides can flip later near-tied decisions, so the deep stack is
+    # checked in fp32 above and only the first three layers here.
+    wl = W.config5(n_layers=3, d=256, E=64, F=128, len_div=16, text_len=64)
+    out, kept, new_cu, nv, nt = _gpu_stack(wl)
+    ref, ref_kept, ref_cu = _oracle_stack(wl)
+    assert out.shape[0] == binding.kept_count(nv, nt, wl.retention) == ref.shape[0]
+    assert np.array_equal(new_cu, ref_cu)
+    same = np.intersect1d(kept, ref_kept).size / ref_kept.size
+    assert same >= 0.98                                   # kept sets agree but for flipped near-ties
+    if np.array_equal(kept, ref_kept):
+        assert max_rel_err(out, ref) <= 3 * TOL[W.BF16]
