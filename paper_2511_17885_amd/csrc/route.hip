@@ -22,6 +22,8 @@
 // MFMAs); several chunks of both are kept in flight in registers.  Logits meet in LDS, then each wavefront does softmax /
 // top-k for four tokens with lanes mapped to experts.
 
+#include <type_traits>
+
 #include "common.h"
 #include "prune_dev.h"
 
@@ -57,6 +59,27 @@ __device__ __forceinline__ float wave_max(float v) {
     v = (o > v) ? o : v;
   }
   return v;
+}
+
+// Maximum over the 64 lanes, returned in every lane.  Inside a row of 16 lanes: xor-1 and xor-2 quad
+// permutes, then the half-row and full-row mirrors (each step pairs lanes holding different partial
+// maxima); across the four rows: one lane read per row.
+__device__ __forceinline__ float wave_max_all(float v) {
+  auto step = [](float x, auto ctrl) {
+    const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value, 0xf, 0xf, false);
+    const float y = __int_as_float(o);
+    return (y > x) ? y : x;
+  };
+  v = step(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]
+  v = step(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]
+  v = step(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
+  v = step(v, std::integral_constant<int, 0x140>{});   // row_mirror
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  const float a = (r1 > r0) ? r1 : r0, b = (r3 > r2) ? r3 : r2;
+  return (b > a) ? b : a;
 }
 
 __device__ __forceinline__ float exp_fixed(float x) {
@@ -295,57 +318,62 @@ __global__ __launch_bounds__(256) void route_kernel(
       if (probs != nullptr && tv[tq] && e < E) probs[(size_t)tt[tq] * E + e] = P[tq][i];
     }
 
-  // rank of every expert in the order (probability desc, index asc): one pass over all experts,
-  // each broadcast from its lane, instead of k dependent arg-max reductions
-  int rank[TQ][NB];
-#pragma unroll
-  for (int tq = 0; tq < TQ; ++tq)
-#pragma unroll
-    for (int i = 0; i < NB; ++i) rank[tq][i] = 0;
-#pragma unroll
-  for (int j = 0; j < NB; ++j) {
-#pragma unroll 16
-    for (int sl = 0; sl < 64; ++sl) {
-#pragma unroll
-      for (int tq = 0; tq < TQ; ++tq) {
-        const float v = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, P[tq][j]), sl));
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-          bool ahead;
-          if (j < i) ahead = v >= P[tq][i];
-          else if (j > i) ahead = v > P[tq][i];
-          else ahead = (v > P[tq][i]) | ((v == P[tq][i]) & (sl < lane));
-          rank[tq][i] += ahead ? 1 : 0;
-        }
-      }
-    }
-  }
-  __syncthreads();   // every wavefront is done reading its logits: rows of zs are reused below
+  // Top-k as k rounds of "take the largest remaining probability" (ties: lowest expert index), which
+  // yields the list in the order (probability desc, index asc) directly.  The maximum over the
+  // wavefront is order-free, so it uses the cheap lane-crossing modifiers (two quad permutes, two
+  // mirrors) inside a row of 16 lanes and four lane reads across rows.  The four tokens run side by
+  // side and a token that needs fewer than Kmax experts idles branch-free.
+  float work[TQ][NB];
+  int sel[TQ][NB];     // position of this lane's expert in the token's list, -1: not selected
+  float den[TQ];
+  int kk[TQ];
 #pragma unroll
   for (int tq = 0; tq < TQ; ++tq) {
-    const int tok = wave * TQ + tq;
-    const int k = is_visual[tt[tq]] ? k_visual : k_text;
+    kk[tq] = is_visual[tt[tq]] ? k_visual : k_text;
+    den[tq] = 0.0f;
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-      const int e = lane + 64 * i;
-      if (e < E && rank[tq][i] < k) {
-        zs[tok][rank[tq][i]] = P[tq][i];
-        zs[tok][FMOE_MAX_TOPK + rank[tq][i]] = __int_as_float(e);
-      }
+      work[tq][i] = P[tq][i];
+      sel[tq][i] = -1;
     }
   }
-  __syncthreads();
+  for (int r = 0; r < Kmax; ++r) {
+#pragma unroll
+    for (int tq = 0; tq < TQ; ++tq) {
+      float v = work[tq][0];
+#pragma unroll
+      for (int i = 1; i < NB; ++i) v = (work[tq][i] > v) ? work[tq][i] : v;
+      const float m = wave_max_all(v);
+      const bool active = r < kk[tq];
+      bool taken = false;
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {   // lowest expert index first: register i holds experts 64i..64i+63
+        const unsigned long long eq = __ballot(work[tq][i] == m);
+        const int owner = __ffsll((long long)eq) - 1;
+        if (active && !taken && lane == owner) {
+          sel[tq][i] = r;
+          work[tq][i] = -2.0f;
+        }
+        taken = taken || (eq != 0ull);
+      }
+      den[tq] = den[tq] + (active ? m : 0.0f);   // list order, sequential (Eq.5)
+    }
+  }
 #pragma unroll
   for (int tq = 0; tq < TQ; ++tq) {
-    const int tok = wave * TQ + tq;
-    const int k = is_visual[tt[tq]] ? k_visual : k_text;
-    float den = 0.0f;
-    for (int r = 0; r < k; ++r) den = den + zs[tok][r];   // list order, sequential (Eq.5)
-    if (tv[tq] && lane < Kmax) {
-      const bool live = lane < k;
-      const float pr = live ? zs[tok][lane] : 0.0f;
-      topk_idx[(size_t)tt[tq] * Kmax + lane] = live ? __float_as_int(zs[tok][FMOE_MAX_TOPK + lane]) : -1;
-      topk_gate[(size_t)tt[tq] * Kmax + lane] = live ? (renorm ? pr / den : pr) : 0.0f;
+    if (!tv[tq]) continue;
+    int32_t* oi = topk_idx + (size_t)tt[tq] * Kmax;
+    float* og = topk_gate + (size_t)tt[tq] * Kmax;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      if (sel[tq][i] >= 0) {
+        oi[sel[tq][i]] = lane + 64 * i;
+        og[sel[tq][i]] = renorm ? P[tq][i] / den[tq] : P[tq][i];
+      }
+    }
+    if (lane < Kmax && lane >= kk[tq]) {   // unused tail of the list
+      oi[lane] = -1;
+      og[lane] = 0.0f;
     }
   }
 }
