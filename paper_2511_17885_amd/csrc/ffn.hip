@@ -96,10 +96,14 @@ __device__ __forceinline__ void wait_vm_upto(int n) {   // n not known at compil
 // here nor touches the destination registers before the LDS counter has drained.
 template <int NRB>
 __device__ __forceinline__ void lds_read_frags(uint32_t addr, u32x4_t (&f)[NRB]) {
-  static_assert(NRB == 2 || NRB == 4 || NRB == 6 || NRB == 8, "one to four 32-row bands");
+  static_assert(NRB == 2 || NRB == 3 || NRB == 4 || NRB == 6 || NRB == 8, "supported fragment counts");
   if constexpr (NRB == 2) {
     asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:2048\n\ts_waitcnt lgkmcnt(0)"
                  : "=&v"(f[0]), "=&v"(f[1]) : "v"(addr) : "memory");
+  } else if constexpr (NRB == 3) {
+    asm volatile("ds_read_b128 %0, %3\n\tds_read_b128 %1, %3 offset:2048\n\t"
+                 "ds_read_b128 %2, %3 offset:4096\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]) : "v"(addr) : "memory");
   } else if constexpr (NRB == 4) {
     asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:2048\n\t"
                  "ds_read_b128 %2, %4 offset:4096\n\tds_read_b128 %3, %4 offset:6144\n\t"
@@ -155,10 +159,9 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
   const int N = P.N, K = P.K;
   const int NT = (K + SBK - 1) / SBK;
 
-  // this wavefront's weight stream: column block (nt*4 + wave) of the packing
-  int nbw = nt * 4 + wave;
-  nbw = nbw < P.nbw ? nbw : P.nbw - 1;     // past N: recompute the last block, never stored
-  const u32x4_t* bsrc = P.Bp + (size_t)group * P.group_stride + (size_t)nbw * P.ks * 128 + lane;
+  // this workgroup's weight stream: tile nt of the packing, 16 KB per k tile, 4 KB per wavefront
+  // (columns past N are zero in the packing and never stored)
+  const u32x4_t* bsrc = P.Bp + (size_t)group * P.group_stride + (size_t)nt * (P.ks / 2) * 1024 + wave * 256 + lane;
 
   // activation pieces of this lane: rows 32*it + 8*wave + lane/8, LDS position lane%8 of the row,
   // i.e. k chunk (lane%8) ^ ((row >> 1) & 7); rows past the tile reuse its last row
@@ -194,7 +197,7 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
 #pragma unroll
     for (int s = 0; s < 2; ++s)
 #pragma unroll
-      for (int f = 0; f < 2; ++f) breg[slot][s][f] = bsrc[(size_t)((t * 2 + s) * 2 + f) * 64];
+      for (int f = 0; f < 2; ++f) breg[slot][s][f] = bsrc[(size_t)t * 1024 + (s * 2 + f) * 64];
   };
   // k past K (ragged last tile): the address is clamped into the row; the packed weights are zero
   // there, so the product vanishes without predicating the load
@@ -217,13 +220,18 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
     for (int s = 0; s < 2; ++s) {
       const bf16x8_t fb0 = __builtin_bit_cast(bf16x8_t, breg[slot][s][0]);
       const bf16x8_t fb1 = __builtin_bit_cast(bf16x8_t, breg[slot][s][1]);
-      u32x4_t fa[NRB];
-      lds_read_frags<NRB>((s ? frag_a1 : frag_a0) + (uint32_t)stage * (SBM * SBK * 2), fa);
+      // operands are fetched HB row blocks at a time (register budget: three blocks per CU)
+      constexpr int HB = (NRB > 4) ? NRB / 2 : NRB;
 #pragma unroll
-      for (int rb = 0; rb < NRB; ++rb) {
-        const bf16x8_t a8 = __builtin_bit_cast(bf16x8_t, fa[rb]);
-        acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, fb0, acc[rb][0], 0, 0, 0);
-        acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, fb1, acc[rb][1], 0, 0, 0);
+      for (int h0 = 0; h0 < NRB; h0 += HB) {
+        u32x4_t fa[HB];
+        lds_read_frags<HB>((s ? frag_a1 : frag_a0) + (uint32_t)stage * (SBM * SBK * 2) + h0 * 2048, fa);
+#pragma unroll
+        for (int rb = 0; rb < HB; ++rb) {
+          const bf16x8_t a8 = __builtin_bit_cast(bf16x8_t, fa[rb]);
+          acc[h0 + rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, fb0, acc[h0 + rb][0], 0, 0, 0);
+          acc[h0 + rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, fb1, acc[h0 + rb][1], 0, 0, 0);
+        }
       }
     }
   };
@@ -378,21 +386,25 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(StreamArgs a) {
   }
 }
 
-// Packing: unit u (16 bytes = 8 consecutive k) -> (group, column block, k step, fragment, lane).
+// Packing: unit u (16 bytes = 8 consecutive k) -> (group, tile of 4 column blocks, 64-wide k tile,
+// column block in the tile = wavefront, 32-wide k step, fragment, lane): the 16 KB a workgroup
+// consumes per k tile are contiguous and its whole stream is one linear run of memory.
 //   gate/up (PAIR): column block = 16 output features, fragment 0 = gate rows, 1 = up rows
 //   down (!PAIR):   column block = 32 output features, fragment f = features 16f..16f+15
 // src rows are [group][n][k].
 template <bool PAIR>
 __global__ void pack_weights_kernel(const bf16_t* __restrict__ src0, const bf16_t* __restrict__ src1,
                                     u32x4_t* __restrict__ dst, int G, int N, int K, int nbw, int ks) {
-  const size_t total = (size_t)G * nbw * ks * 128;
+  const int nbt = (nbw + 3) / 4, NT = ks / 2;
+  const size_t total = (size_t)G * nbt * NT * 1024;
   for (size_t u = (size_t)blockIdx.x * blockDim.x + threadIdx.x; u < total;
        u += (size_t)gridDim.x * blockDim.x) {
-    const int lane = (int)(u & 63), f = (int)((u >> 6) & 1);
-    size_t q = u >> 7;
-    const int s = (int)(q % ks);
-    q /= ks;
-    const int b = (int)(q % nbw), g = (int)(q / nbw);
+    const int lane = (int)(u & 63), f = (int)((u >> 6) & 1), s2 = (int)((u >> 7) & 1), w = (int)((u >> 8) & 3);
+    size_t q = u >> 10;
+    const int kt = (int)(q % NT);
+    q /= NT;
+    const int bt = (int)(q % nbt), g = (int)(q / nbt);
+    const int b = bt * 4 + w, s = kt * 2 + s2;
     const int n = PAIR ? (b * 16 + (lane & 15)) : (b * 32 + f * 16 + (lane & 15));
     const int k = s * 32 + 8 * (lane >> 4);
     u32x4_t v = {0u, 0u, 0u, 0u};
@@ -634,6 +646,8 @@ __global__ __launch_bounds__(256) void build_tiles_kernel(const int32_t* __restr
 }
 
 inline int ks_steps(int K) { return ((K + SBK - 1) / SBK) * 2; }
+// 16-byte units of one packed group: column blocks padded to tiles of four, 128 units per block and k step
+inline size_t packed_units(int nbw, int ks) { return (size_t)((nbw + 3) / 4) * 4 * ks * 128; }
 
 }  // namespace
 
@@ -658,10 +672,10 @@ size_t fmoe_packed_bytes(const fmoe_ctx* ctx, int which) {
   if (c.dtype != FMOE_BF16) return 0;
   const size_t Ft = (size_t)c.n_shared * c.d_ffn_shared;
   switch (which) {
-    case 0: return (size_t)c.n_experts * ((c.d_ffn + 15) / 16) * ks_steps(c.d_model) * 2048;
-    case 1: return (size_t)c.n_experts * ((c.d_model + 31) / 32) * ks_steps(c.d_ffn) * 2048;
-    case 2: return Ft ? ((Ft + 15) / 16) * ks_steps(c.d_model) * 2048 : 0;
-    case 3: return Ft ? (size_t)c.n_shared * ((c.d_model + 31) / 32) * ks_steps(c.d_ffn_shared) * 2048 : 0;
+    case 0: return (size_t)c.n_experts * packed_units((c.d_ffn + 15) / 16, ks_steps(c.d_model)) * 16;
+    case 1: return (size_t)c.n_experts * packed_units((c.d_model + 31) / 32, ks_steps(c.d_ffn)) * 16;
+    case 2: return Ft ? packed_units(((int)Ft + 15) / 16, ks_steps(c.d_model)) * 16 : 0;
+    case 3: return Ft ? (size_t)c.n_shared * packed_units((c.d_model + 31) / 32, ks_steps(c.d_ffn_shared)) * 16 : 0;
   }
   return 0;
 }
@@ -765,7 +779,7 @@ int run_ffn_bf16(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, in
     StreamProblem& p = g1.p0;
     p.A = static_cast<const bf16_t*>(x); p.lda = d; p.map1 = perm_src; p.map2 = kept_idx; p.map1_limit = n_cap;
     p.Bp = static_cast<const u32x4_t*>(ctx->pk_gate_up);
-    p.nbw = (F + 15) / 16; p.ks = ks_steps(d); p.group_stride = (long long)p.nbw * p.ks * 128;
+    p.nbw = (F + 15) / 16; p.ks = ks_steps(d); p.group_stride = (long long)packed_units(p.nbw, p.ks);
     p.C = reinterpret_cast<bf16_t*>(base + L.h); p.ldc = F; p.N = F; p.K = d; p.n_col_tiles = geo.cols1;
     StreamProblem& q = g1.p1;
     q = p;
@@ -778,13 +792,13 @@ int run_ffn_bf16(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, in
     StreamProblem& p = g2.p0;
     p.A = reinterpret_cast<const bf16_t*>(base + L.h); p.lda = F; p.map1 = nullptr; p.map2 = nullptr; p.map1_limit = 0;
     p.Bp = static_cast<const u32x4_t*>(ctx->pk_down);
-    p.nbw = (d + 31) / 32; p.ks = ks_steps(F); p.group_stride = (long long)p.nbw * p.ks * 128;
+    p.nbw = (d + 31) / 32; p.ks = ks_steps(F); p.group_stride = (long long)packed_units(p.nbw, p.ks);
     p.C = static_cast<bf16_t*>(y); p.ldc = d; p.N = d; p.K = F; p.n_col_tiles = geo.cols2;
     StreamProblem& q = g2.p1;
     q = p;
     q.A = reinterpret_cast<const bf16_t*>(base + L.h_shared); q.lda = Ft; q.a_group_off = c.d_ffn_shared;
     q.Bp = static_cast<const u32x4_t*>(ctx->pk_sdown);
-    q.ks = ks_steps(c.d_ffn_shared > 0 ? c.d_ffn_shared : 1); q.group_stride = (long long)q.nbw * q.ks * 128;
+    q.ks = ks_steps(c.d_ffn_shared > 0 ? c.d_ffn_shared : 1); q.group_stride = (long long)packed_units(q.nbw, q.ks);
     q.C = static_cast<bf16_t*>(y_shared); q.c_group_off = (long long)n_cap * d; q.K = c.d_ffn_shared;
     q.n_col_tiles = geo.scols2;
   }

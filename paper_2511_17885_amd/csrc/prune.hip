@@ -295,6 +295,29 @@ __global__ void identity_kept_kernel(const uint8_t* __restrict__ is_visual,
   if (i <= B && new_cu != nullptr) new_cu[i] = clampi(cu[i], 0, T);
 }
 
+// v of lane (l xor 2^jb).  jb is a constant after unrolling: distances 1 and 2 are quad permutes,
+// 4 and 8 a pair of row shifts (lanes with the bit clear read upwards, the others downwards), all
+// executed inside the ALU; 16 and 32 cross rows and go through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+}
+__device__ __forceinline__ uint32_t lane_xor_pow2(int jb, uint32_t v, int lane) {
+  switch (jb) {
+    case 0: return dpp_mov<0xB1>(v);    // quad_perm [1,0,3,2]
+    case 1: return dpp_mov<0x4E>(v);    // quad_perm [2,3,0,1]
+    case 2: {
+      const uint32_t up = dpp_mov<0x104>(v), dn = dpp_mov<0x114>(v);   // row_shl:4, row_shr:4
+      return (lane & 4) ? dn : up;
+    }
+    case 3: {
+      const uint32_t up = dpp_mov<0x108>(v), dn = dpp_mov<0x118>(v);   // row_shl:8, row_shr:8
+      return (lane & 8) ? dn : up;
+    }
+    default: return (uint32_t)__shfl_xor((int)v, 1 << jb, 64);
+  }
+}
+
 // ---- E: small batches.  One 1024-thread block takes the whole chain after the window scores:
 // drop order, budget, compaction, permutation by expert and the grouped-GEMM tile lists, with the
 // intermediate arrays in LDS.  At a few thousand tokens each of those steps is a few microseconds
@@ -429,7 +452,10 @@ __global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallA
       const bool active = tid < N;   // whole wavefronts; the others only keep the barriers company
       int buf = 0;
       for (int k = 2; k <= N; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
+#pragma unroll
+        for (int jb = 9; jb >= 0; --jb) {   // partner distances 512 .. 1, those below k
+          const int j = 1 << jb;
+          if (j >= k) continue;             // uniform
           uint32_t pa = ka;
           unsigned long long pk = kk;
           if (j >= 64) {   // partner in another wavefront: through LDS, buffers alternate
@@ -444,10 +470,10 @@ __global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallA
             }
             buf ^= 1;
           } else if (active) {
-            const uint32_t lo = __shfl_xor((uint32_t)kk, j, 64);
-            const uint32_t hi = __shfl_xor((uint32_t)(kk >> 32), j, 64);
+            const uint32_t lo = lane_xor_pow2(jb, (uint32_t)kk, lane);
+            const uint32_t hi = lane_xor_pow2(jb, (uint32_t)(kk >> 32), lane);
             pk = ((unsigned long long)hi << 32) | lo;
-            if (has_attn) pa = __shfl_xor(ka, j, 64);
+            if (has_attn) pa = lane_xor_pow2(jb, ka, lane);
           }
           if (active) {
             const bool partner_first = (pa < ka) || (pa == ka && pk < kk);
