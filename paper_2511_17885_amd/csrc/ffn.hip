@@ -215,15 +215,36 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
   const uint32_t frag_row = lds0 + (uint32_t)(lane & 15) * (SBK * 2);
   const uint32_t frag_a0 = frag_row + (uint32_t)(((lane >> 4)) ^ ((lane & 15) >> 1)) * 16;
   const uint32_t frag_a1 = frag_row + (uint32_t)(((lane >> 4) + 4) ^ ((lane & 15) >> 1)) * 16;
-  auto compute = [&](int slot, int stage) {
+  // One k step: the products of tile `t_now` (weights in ring slot `slot`, activations in LDS stage
+  // `stage`) and, if `issue`, the loads of the tiles A_AHEAD / B_AHEAD steps further on.  The loads
+  // are dealt out over the step's groups of matrix instructions instead of being issued in one
+  // burst: the four wavefronts leave the barrier together, and 8 loads each at once would queue up
+  // at the CU's one address unit for several hundred cycles before any of them could start to
+  // multiply.
+  constexpr int HB = (NRB > 4) ? NRB / 2 : NRB;   // row blocks whose operands are fetched together
+  constexpr int NQ = 2 * (NRB / HB);              // groups per step
+  auto step = [&](int slot, int stage, bool issue, int new_slot, int new_stage, int t_a, int t_b) {
+    const int ka = t_a * SBK + a_kc;
+    const uint32_t a_off = (uint32_t)(ka < K ? ka : K - 8) * 2u;
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       const bf16x8_t fb0 = __builtin_bit_cast(bf16x8_t, breg[slot][s][0]);
       const bf16x8_t fb1 = __builtin_bit_cast(bf16x8_t, breg[slot][s][1]);
-      // operands are fetched HB row blocks at a time (register budget: three blocks per CU)
-      constexpr int HB = (NRB > 4) ? NRB / 2 : NRB;
 #pragma unroll
       for (int h0 = 0; h0 < NRB; h0 += HB) {
+        const int q = s * (NRB / HB) + h0 / HB;
+        if (issue) {
+#pragma unroll
+          for (int i = 0; i < PER_STEP; ++i) {   // load i of the step goes out with group i*NQ/PER_STEP
+            if ((i * NQ) / PER_STEP != q) continue;
+            if (i < NAB)
+              __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                  a_rsrc, FMOE_LPTR(As + new_stage * (SBM * SBK) + (32 * i + 8 * wave) * SBK), 16,
+                  a_src[i] + a_off, 0, 0, 0);
+            else
+              breg[new_slot][(i - NAB) >> 1][(i - NAB) & 1] = bsrc[(size_t)t_b * 1024 + (i - NAB) * 64];
+          }
+        }
         u32x4_t fa[HB];
         lds_read_frags<HB>((s ? frag_a1 : frag_a0) + (uint32_t)stage * (SBM * SBK * 2) + h0 * 2048, fa);
 #pragma unroll
@@ -260,9 +281,8 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
       for (int u = 0; u < UNROLL; ++u) {
         FMOE_WAIT_VM(NEWER);
         block_barrier();   // every wavefront's share of tile t+u is in LDS; all are done with tile t+u-1
-        loadA((u + A_AHEAD) % A_STAGES, t + u + A_AHEAD);
-        loadB((u + B_AHEAD) % B_SLOTS, t + u + B_AHEAD);
-        compute(u % B_SLOTS, u % A_STAGES);
+        step(u % B_SLOTS, u % A_STAGES, true, (u + B_AHEAD) % B_SLOTS, (u + A_AHEAD) % A_STAGES,
+             t + u + A_AHEAD, t + u + B_AHEAD);
       }
     }
   } else {
@@ -288,7 +308,7 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
         block_barrier();
         if (tt + A_AHEAD < NT) loadA((u + A_AHEAD) % A_STAGES, tt + A_AHEAD);
         if (tt + B_AHEAD < NT) loadB((u + B_AHEAD) % B_SLOTS, tt + B_AHEAD);
-        compute(u % B_SLOTS, u % A_STAGES);
+        step(u % B_SLOTS, u % A_STAGES, false, 0, 0, 0, 0);
       }
     }
   }
