@@ -109,11 +109,20 @@ def route(x, is_visual, router_w, router_bias, k_text, k_visual, renormalize=Tru
     return (probs, idx, gate, p64) if shadow else (probs, idx, gate)
 
 
+def gamma_hat(retain_ratio, window, stages=3):
+    """App. D: the merge rate at which merging alone reaches the token budget,
+    (1/beta - 1)/(W - 1) with the per-stage retain ratio beta = r^(1/stages)."""
+    beta = float(retain_ratio) ** (1.0 / stages)
+    return (1.0 / beta - 1.0) / (window - 1)
+
+
 def prune(probs, is_visual, cu_seqlens, retention, window, alpha=1.0, gamma=0.0, sim_mode=0,
-          attn=None):
-    """Sec. 3.2 (scores, budget, drop).  Returns kept_idx [T'] i32 ascending, new_cu_seqlens [B+1],
-    window scores C (sequences concatenated)."""
+          attn=None, x=None, is_bf16=False):
+    """Sec. 3.2 (scores, budget, merge, drop).  Returns kept_idx [T'] i32 ascending, new_cu_seqlens
+    [B+1], window scores C (sequences concatenated); with x [T,d] also is_merged [T'] u8 and the
+    layer input after merging x_merged [T',d] (needed when gamma > 0)."""
     probs, is_visual, cu, attn = _f32(probs), _u8(is_visual), _i32(cu_seqlens), _f32(attn)
+    x = _f32(x)
     T, E = probs.shape
     B = cu.shape[0] - 1
     offs = np.empty(B + 1, np.int32)
@@ -121,13 +130,19 @@ def prune(probs, is_visual, cu_seqlens, retention, window, alpha=1.0, gamma=0.0,
     kept = np.empty(max(T, 1), np.int32)
     new_cu = np.empty(B + 1, np.int32)
     scores = np.empty(max(nwin, 1), np.float32)
+    d = 0 if x is None else x.shape[1]
+    is_merged = None if x is None else np.zeros(max(T, 1), np.uint8)
+    x_merged = None if x is None else np.empty((max(T, 1), d), np.float32)
     n = lib().orc_prune(_p(probs, _f32p), _p(is_visual, _u8p), _p(cu, _i32p), B, T, E,
                         C.c_float(retention), int(window), C.c_float(alpha), C.c_float(gamma),
                         int(sim_mode), _p(attn, _f32p), _p(kept, _i32p), _p(new_cu, _i32p),
-                        _p(scores, _f32p))
+                        _p(scores, _f32p), _p(x, _f32p), int(d), int(bool(is_bf16)),
+                        _p(is_merged, _u8p), _p(x_merged, _f32p))
     if n < 0:
         raise ValueError("orc_prune: bad arguments")
-    return kept[:n].copy(), new_cu, scores[:nwin].copy()
+    if x is None:
+        return kept[:n].copy(), new_cu, scores[:nwin].copy()
+    return kept[:n].copy(), new_cu, scores[:nwin].copy(), is_merged[:n].copy(), x_merged[:n].copy()
 
 
 def permute(topk_idx, kept_idx, E):
@@ -216,6 +231,27 @@ def layer_forward(x, is_visual, cu_seqlens, w, *, k_text, k_visual, is_bf16, ret
     E = w.router_w.shape[0]
     d = x.shape[1]
     probs, idx, gate = route(x, is_visual, w.router_w, w.router_bias, k_text, k_visual, renormalize)
+    if do_prune and retention < 1.0 and gamma > 0.0:
+        # window merging changes the layer input: the kept rows are gathered (merged windows replaced by
+        # their merged token), every kept token is routed again on that tensor (only the merged ones can
+        # come out differently) and the rest of the layer runs on it
+        kept, new_cu, scores, is_merged, x_m = prune(probs, is_visual, cu_seqlens, retention, window,
+                                                     alpha, gamma, sim_mode, attn, x=x, is_bf16=is_bf16)
+        vis_m = _u8(is_visual)[kept]
+        probs_m, idx_m, gate_m = route(x_m, vis_m, w.router_w, w.router_bias, k_text, k_visual, renormalize)
+        ident = np.arange(kept.shape[0], dtype=np.int32)
+        offs, perm, inv = permute(idx_m, ident, E)
+        res = dict(probs=probs, topk_idx=idx_m, topk_gate=gate_m, kept_idx=kept, new_cu_seqlens=new_cu,
+                   scores=scores, expert_offsets=offs, perm_src=perm, inv_perm=inv, is_merged=is_merged,
+                   x_merged=x_m)
+        if ffn:
+            y = expert_ffn(x_m, ident, offs, perm, w.w_gate, w.w_up, w.w_down, is_bf16)
+            ysh = None
+            if w.ws_gate is not None:
+                ysh = shared_ffn(x_m, ident, ident.shape[0], w.ws_gate, w.ws_up, w.ws_down, is_bf16)
+            out, out64 = combine(y, ysh, inv, gate_m, ident, d, x_m if add_residual else None, is_bf16)
+            res.update(y=y, y_shared=ysh, out=out, out_f64=out64)
+        return res
     if do_prune and retention < 1.0:
         kept, new_cu, scores = prune(probs, is_visual, cu_seqlens, retention, window,
                                      alpha, gamma, sim_mode, attn)

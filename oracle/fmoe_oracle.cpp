@@ -300,14 +300,32 @@ int orc_window_counts(const uint8_t* is_visual, const int32_t* cu_seqlens, int B
 //     loses its last u tokens; then stop.  Exactly eta visual tokens survive;
 //  6. kept_idx = ascending global indices of all text tokens and surviving visual tokens;
 //     new_cu_seqlens counts them per sequence.
-// scores_out (nullable) receives C per window, sequences concatenated.  gamma (window merging,
-// Eq.14-18) must be 0 here.  Returns the number of kept tokens, or <0 on bad arguments.
+// scores_out (nullable) receives C per window, sequences concatenated.
+// Window merging (Sec. 3.2.3, Eq.14-18), gamma > 0, between steps 4 and 5:
+//  4a. at most m = floor(eta*gamma) windows are merged (Eq.14; the product is not an integer in
+//      general, the floor is this build's reading).  Walk the windows in the order (C descending,
+//      index ascending) -- the highest redundancy scores, Eq.15; a window of w >= 2 tokens is merged
+//      if the w-1 tokens this removes still fit in the budget u (u starts at eps, u -= w-1), until m
+//      windows are merged or the list ends.  (The paper's text subtracts the number of merges from
+//      eps; its derivation of the largest useful gamma needs every merge to remove W-1 tokens,
+//      which is the accounting used here.)
+//  4b. a merged window is replaced by ONE token at the position of its first token (the paper keeps
+//      the positions of merged tokens): the mean of its tokens (Eq.16-17, with the window's real size
+//      where the paper writes W), rescaled to the largest token norm of the window (Eq.18);
+//  5.  the drop walk then runs over the windows that were not merged, with the budget left.
+// x_in [T,d] (values already rounded to the storage type) is needed iff gamma > 0; is_merged
+// [kept] and x_merged [kept,d] (nullable) receive, per kept position, whether it is a merged token
+// and the layer input row after merging (rounded once to the storage type).
+// Returns the number of kept tokens, or <0 on bad arguments.
 int orc_prune(const float* probs, const uint8_t* is_visual, const int32_t* cu_seqlens, int B,
               int T, int E, float retention, int W, float alpha, float gamma, int sim_mode,
-              const float* attn, int32_t* kept_idx, int32_t* new_cu_seqlens, float* scores_out) {
-  if (W < 1 || !(retention > 0.0f) || retention > 1.0f || gamma != 0.0f) return -1;
+              const float* attn, int32_t* kept_idx, int32_t* new_cu_seqlens, float* scores_out,
+              const float* x_in, int d, int is_bf16, uint8_t* is_merged, float* x_merged) {
+  if (W < 1 || !(retention > 0.0f) || retention > 1.0f || !(gamma >= 0.0f) || gamma >= 1.0f) return -1;
+  if (gamma > 0.0f && !x_in) return -1;
   if (cu_seqlens[B] != T) return -1;
   std::vector<char> keep(T, 1);
+  std::vector<int> merge_w(T, 0);   // at the first token of a merged window: the window's size
   int score_base = 0;
   for (int b = 0; b < B; ++b) {
     std::vector<int> vis;
@@ -343,13 +361,35 @@ int orc_prune(const float* probs, const uint8_t* is_visual, const int32_t* cu_se
     int eta = (int)std::floor((double)retention * (double)Nv + 0.5);
     eta = std::max(std::min(1, Nv), std::min(eta, Nv));
     int u = Nv - eta;
-    std::vector<Win> order(win);
+    std::vector<char> merged(n, 0);
+    if (gamma > 0.0f) {
+      const int m = (int)std::floor((double)eta * (double)gamma);
+      std::vector<Win> by_score(win);
+      std::stable_sort(by_score.begin(), by_score.end(), [](const Win& p, const Win& q) {
+        if (p.C != q.C) return p.C > q.C;
+        return p.idx < q.idx;
+      });
+      int cnt = 0;
+      for (int j = 0; j < n && cnt < m; ++j) {
+        const Win& wj = by_score[j];
+        if (wj.w >= 2 && wj.w - 1 <= u) {
+          merged[wj.idx] = 1;
+          merge_w[vis[wj.first]] = wj.w;
+          for (int a = 1; a < wj.w; ++a) keep[vis[wj.first + a]] = 0;
+          u -= wj.w - 1;
+          ++cnt;
+        }
+      }
+    }
+    std::vector<Win> order;
+    for (int i = 0; i < n; ++i)
+      if (!merged[i]) order.push_back(win[i]);
     std::stable_sort(order.begin(), order.end(), [](const Win& p, const Win& q) {
       if (p.A != q.A) return p.A < q.A;
       if (p.C != q.C) return p.C > q.C;
       return p.idx < q.idx;
     });
-    for (int j = 0; j < n && u > 0; ++j) {
+    for (int j = 0; j < (int)order.size() && u > 0; ++j) {
       const Win& wj = order[j];
       if (wj.w <= u) {
         for (int a = 0; a < wj.w; ++a) keep[vis[wj.first + a]] = 0;
@@ -363,8 +403,45 @@ int orc_prune(const float* probs, const uint8_t* is_visual, const int32_t* cu_se
   int nk = 0;
   new_cu_seqlens[0] = 0;
   for (int b = 0; b < B; ++b) {
+    // the visual tokens after t in its sequence, for the members of a merged window
+    std::vector<int> vis;
     for (int t = cu_seqlens[b]; t < cu_seqlens[b + 1]; ++t)
-      if (keep[t]) kept_idx[nk++] = t;
+      if (is_visual[t]) vis.push_back(t);
+    size_t vpos = 0;
+    for (int t = cu_seqlens[b]; t < cu_seqlens[b + 1]; ++t) {
+      const size_t my_v = vpos;
+      if (is_visual[t]) ++vpos;
+      if (!keep[t]) continue;
+      if (is_merged) is_merged[nk] = merge_w[t] > 0 ? 1 : 0;
+      if (x_merged && x_in) {
+        float* out = x_merged + (size_t)nk * d;
+        if (merge_w[t] == 0) {
+          for (int c = 0; c < d; ++c) out[c] = x_in[(size_t)t * d + c];
+        } else {
+          const int w = merge_w[t];
+          std::vector<double> mean(d, 0.0);
+          double max_norm = 0.0;
+          for (int a = 0; a < w; ++a) {
+            const float* row = x_in + (size_t)vis[my_v + a] * d;
+            double nn = 0.0;
+            for (int c = 0; c < d; ++c) {
+              mean[c] += (double)row[c];
+              nn += (double)row[c] * (double)row[c];
+            }
+            max_norm = std::max(max_norm, std::sqrt(nn));
+          }
+          double mn = 0.0;
+          for (int c = 0; c < d; ++c) {
+            mean[c] /= (double)w;
+            mn += mean[c] * mean[c];
+          }
+          mn = std::sqrt(mn);
+          const double scale = mn > 0.0 ? max_norm / mn : 0.0;
+          for (int c = 0; c < d; ++c) out[c] = round_store(mean[c] * scale, is_bf16);
+        }
+      }
+      kept_idx[nk++] = t;
+    }
     new_cu_seqlens[b + 1] = nk;
   }
   return nk;
