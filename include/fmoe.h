@@ -65,7 +65,7 @@ typedef struct {
   float retention;    /* r in (0,1]: keep round(r*N_v) visual tokens per sequence; 1 = off */
   int32_t window;     /* W >= 1 consecutive visual tokens per window (Sec. 3.2.2)          */
   float alpha;        /* weight of routing similarity in the redundancy score (Eq.13)      */
-  float gamma;        /* merge rate (Eq.14); must be 0: window merging is not implemented  */
+  float gamma;        /* merge rate in [0,1) (Eq.14): at most floor(eta*gamma) windows merged; 0 = off */
   int32_t sim_mode;   /* 0: similarity to the window mean (Eq.9-10); 1: all pairs (Eq.8)   */
   int32_t prune_mode; /* 0: none; 1 or 2: prune between routing and the experts            */
 } fmoe_prune_params;
@@ -126,12 +126,21 @@ int fmoe_route(fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int32_t T
  * new_cu_seqlens [B+1] int32: per-sequence boundaries after pruning; new_cu_seqlens[B] = T'.
  * scores [T capacity] fp32 or NULL: the score C of window i of sequence b at
  * scores[cu_seqlens[b] + i].
- * x_in / x_merged are reserved for window merging (gamma > 0) and must be NULL. */
+ * Window merging (Sec. 3.2.3, Eq.14-18), params->gamma > 0: before the drop walk at most
+ * floor(eta*gamma) windows are merged, taken in the order (score descending, index ascending); a
+ * window of w >= 2 tokens is merged while the w-1 tokens this removes fit in the budget; the drop walk
+ * then runs over the remaining windows with the budget that is left, so exactly eta visual tokens
+ * survive as before.  A merged window is represented by ONE token at the position of its first
+ * token: the mean of its rows rescaled to the largest row norm of the window.
+ * x_in [T,H] dtype: the tensor whose rows are merged (the layer input); x_merged [T capacity, H] dtype:
+ * row p = x_in[kept_idx[p]], or the merged token if position p is one; is_merged [T capacity] u8 or
+ * NULL: 1 for merged positions.  All three must be NULL when gamma == 0; x_in and x_merged are
+ * required when gamma > 0.  The caller routes the merged rows again (fmoe_layer_forward does). */
 int fmoe_prune(fmoe_ctx* ctx, const fmoe_prune_params* params, const float* probs,
                const uint8_t* is_visual, const int32_t* cu_seqlens, int32_t B, int32_t T,
                const float* attn_importance, const void* x_in, int32_t* kept_idx,
-               int32_t* new_cu_seqlens, float* scores, void* x_merged, void* ws, size_t ws_bytes,
-               void* stream);
+               int32_t* new_cu_seqlens, float* scores, void* x_merged, uint8_t* is_merged, void* ws,
+               size_t ws_bytes, void* stream);
 
 /* Dispatch order (the paper leaves it to the framework): the rows are all (kept position p,
  * slot s) pairs with topk_idx >= 0, sorted by (expert ascending, p ascending).
@@ -171,7 +180,10 @@ int fmoe_combine(fmoe_ctx* ctx, const void* y, const void* y_shared, const int32
  * add_residual != 0 adds x[t] to the layer output (x <- x + MoE(x)).
  * Because an MoE layer acts on every token independently, dropping a token before the experts
  * gives the kept tokens the same outputs as dropping it after the layer; both prune modes
- * therefore run the experts on the kept tokens only. */
+ * therefore run the experts on the kept tokens only.
+ * Window merging (params->gamma > 0; prune_mode 1 only, FMOE_ERR_UNSUPPORTED otherwise): the rows of
+ * x are merged (fmoe_prune's x_merged), every kept token is routed again on the merged input, the
+ * experts run on it and add_residual adds the merged rows. */
 int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const void* x,
                        const uint8_t* is_visual, const int32_t* cu_seqlens, int32_t B, int32_t T,
                        const float* attn_importance, int add_residual, void* out,

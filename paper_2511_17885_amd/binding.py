@@ -64,7 +64,7 @@ def load():
     lib.fmoe_workspace_bytes.restype = sz
     lib.fmoe_route.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp]
     lib.fmoe_prune.argtypes = [vp, C.POINTER(FmoePruneParams), vp, vp, vp, i32, i32, vp, vp, vp, vp,
-                               vp, vp, vp, sz, vp]
+                               vp, vp, vp, vp, sz, vp]
     lib.fmoe_permute.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.fmoe_expert_ffn.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fmoe_combine.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
@@ -188,14 +188,22 @@ class FMoE:
                                    _ptr(gate), _stream()))
         return probs, idx[:, :self.kmax], gate[:, :self.kmax]
 
-    def prune(self, params, probs, is_visual, cu_seqlens, attn=None, want_scores=False):
+    def prune(self, params, probs, is_visual, cu_seqlens, attn=None, want_scores=False, x=None):
+        """Returns (kept_idx, new_cu_seqlens, scores or None); with window merging (params.gamma > 0,
+        x = the tensor whose rows are merged) also (is_merged, x_merged)."""
         T, B = probs.shape[0], cu_seqlens.shape[0] - 1
         kept, new_cu = self._i32(max(T, 1)), self._i32(B + 1)
         scores = self._f32(max(T, 1)) if want_scores else None
+        merging = params.gamma > 0
+        x_merged = torch.empty((max(T, 1), self.d), dtype=self.torch_dtype, device=self.device) if merging else None
+        is_merged = torch.zeros(max(T, 1), dtype=torch.uint8, device=self.device) if merging else None
         ws = self.workspace(T, B)
         _check(self.lib.fmoe_prune(self._ctx, C.byref(params), _ptr(probs), _ptr(is_visual),
-                                   _ptr(cu_seqlens), B, T, _ptr(attn), None, _ptr(kept), _ptr(new_cu),
-                                   _ptr(scores), None, _ptr(ws), ws.numel(), _stream()))
+                                   _ptr(cu_seqlens), B, T, _ptr(attn), _ptr(x) if merging else None,
+                                   _ptr(kept), _ptr(new_cu), _ptr(scores), _ptr(x_merged), _ptr(is_merged),
+                                   _ptr(ws), ws.numel(), _stream()))
+        if merging:
+            return kept, new_cu, scores, is_merged, x_merged
         return kept, new_cu, scores
 
     def permute(self, topk_idx, kept_idx, n_kept, n_kept_dev=None):

@@ -58,8 +58,8 @@ int check_prune(const fmoe_prune_params* p) {
     return fmoe_fail(FMOE_ERR_UNSUPPORTED, "prune: window %d > %d", p->window, FMOE_MAX_WINDOW);
   if (!(p->alpha >= 0.0f) || p->alpha > 1.0f)
     return fmoe_fail(FMOE_ERR_INVALID_ARG, "prune: alpha %g outside [0,1]", (double)p->alpha);
-  if (p->gamma != 0.0f)
-    return fmoe_fail(FMOE_ERR_UNSUPPORTED, "prune: window merging (gamma > 0) is not implemented");
+  if (!(p->gamma >= 0.0f) || p->gamma >= 1.0f)
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "prune: gamma %g outside [0,1)", (double)p->gamma);
   if (p->sim_mode != 0 && p->sim_mode != 1)
     return fmoe_fail(FMOE_ERR_INVALID_ARG, "prune: sim_mode %d", p->sim_mode);
   if (p->prune_mode < 0 || p->prune_mode > 2)
@@ -109,6 +109,12 @@ fmoe_ws_layout fmoe_layout(const fmoe_ctx* ctx, int32_t max_tokens, int32_t max_
   L.win_a = take(T * 4);
   L.drop_from = take(T * 4);
   L.keep_prefix = take((T + 1) * 4);
+  L.rank_c = take(T * 4);
+  L.win_merged = take(T * 4);
+  L.merged_before = take(T * 4);
+  L.is_merged = take(T);
+  L.vis_out = take(T);
+  L.x_merged = take(T * (size_t)c.d_model * es);
   L.slot_rank = take(rows * 4);
   L.blk_count = take(((T + FMOE_PERM_BLOCK - 1) / FMOE_PERM_BLOCK) * E * 4);
   L.expert_offsets = take((E + 1) * 4);
@@ -238,8 +244,8 @@ int fmoe_route(fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int32_t T
 int fmoe_prune(fmoe_ctx* ctx, const fmoe_prune_params* params, const float* probs,
                const uint8_t* is_visual, const int32_t* cu_seqlens, int32_t B, int32_t T,
                const float* attn_importance, const void* x_in, int32_t* kept_idx,
-               int32_t* new_cu_seqlens, float* scores, void* x_merged, void* ws, size_t ws_bytes,
-               void* stream) {
+               int32_t* new_cu_seqlens, float* scores, void* x_merged, uint8_t* is_merged, void* ws,
+               size_t ws_bytes, void* stream) {
   int rc = check_ctx(ctx, false);
   if (rc != FMOE_OK) return rc;
   if (!params) return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_prune: params is NULL");
@@ -249,12 +255,18 @@ int fmoe_prune(fmoe_ctx* ctx, const fmoe_prune_params* params, const float* prob
   if (!cu_seqlens || !new_cu_seqlens) return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_prune: cu_seqlens / new_cu_seqlens is NULL");
   if (T > 0 && (!probs || !is_visual || !kept_idx))
     return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_prune: probs / is_visual / kept_idx is NULL");
-  if (x_in || x_merged)
-    return fmoe_fail(FMOE_ERR_UNSUPPORTED, "fmoe_prune: x_in / x_merged are reserved for window merging and must be NULL");
+  const bool merging = params->gamma > 0.0f;
+  if (merging && T > 0 && (!x_in || !x_merged))
+    return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_prune: gamma > 0 needs x_in and x_merged");
+  if (!merging && (x_in || x_merged || is_merged))
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_prune: x_in / x_merged / is_merged belong to window merging (gamma > 0) and must be NULL without it");
+  if (!aligned16(x_in) || !aligned16(x_merged))
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_prune: x_in / x_merged not 16-byte aligned");
   if ((rc = check_ws(ctx, ws, ws_bytes, T, B)) != FMOE_OK) return rc;
   const fmoe_ws_layout L = fmoe_layout(ctx, T, B);
   return launch_prune(ctx, params, probs, is_visual, cu_seqlens, B, T, attn_importance, kept_idx,
-                      new_cu_seqlens, scores, nullptr, ws, L, static_cast<hipStream_t>(stream));
+                      new_cu_seqlens, scores, nullptr, x_in, x_merged, is_merged, ws, L,
+                      static_cast<hipStream_t>(stream));
 }
 
 int fmoe_permute(fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* kept_idx, int32_t n_kept,
@@ -344,7 +356,11 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
   void* y = base + L.y;
   void* y_shared = ctx->cfg.n_shared > 0 ? base + L.y_shared : nullptr;
 
-  const bool small = T > 0 && dispatch_small_fits(T, do_prune ? params->window : 1, do_prune);
+  const bool merging = do_prune && params->gamma > 0.0f;
+  if (merging && params->prune_mode != 1)
+    return fmoe_fail(FMOE_ERR_UNSUPPORTED, "fmoe_layer_forward: window merging (gamma > 0) is built for prune_mode 1 "
+                     "(merge the layer input, route the kept tokens again)");
+  const bool small = !merging && T > 0 && dispatch_small_fits(T, do_prune ? params->window : 1, do_prune);
   fmoe_ordinals_job ord{};
   if (small && do_prune)
     ord = fmoe_ordinals_job{cu_seqlens, B, reinterpret_cast<int32_t*>(base + L.vis_ord),
@@ -369,9 +385,30 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
     return launch_combine(ctx, y, y_shared, inv_perm, topk_gate, kept, T, n_dev, add_residual ? x : nullptr,
                           out, s);
   }
+  if (merging) {
+    // Window merging changes the layer input: the kept rows are gathered into a compact tensor (merged
+    // windows replaced by their merged token, Eq.16-18), every kept token is routed again on it (only
+    // the merged ones can come out differently) and the rest of the layer runs on that tensor.
+    if (T == 0)
+      return launch_identity_kept(is_visual, cu_seqlens, B, T, kept_idx, new_cu_seqlens, is_visual_out, s);
+    void* xm = base + L.x_merged;
+    uint8_t* vis_m = is_visual_out ? is_visual_out : reinterpret_cast<uint8_t*>(base + L.vis_out);
+    if ((rc = launch_prune(ctx, params, probs, is_visual, cu_seqlens, B, T, attn_importance, kept_idx,
+                           new_cu_seqlens, nullptr, vis_m, x, xm, nullptr, ws, L, s)) != FMOE_OK)
+      return rc;
+    n_dev = new_cu_seqlens + B;
+    if ((rc = launch_route(ctx, xm, vis_m, T, nullptr, topk_idx, topk_gate, fmoe_ordinals_job{}, s, n_dev)) != FMOE_OK)
+      return rc;
+    if ((rc = launch_permute(ctx, topk_idx, nullptr, T, n_dev, expert_offsets, perm_src, inv_perm, ws, L, true, s)) != FMOE_OK)
+      return rc;
+    if ((rc = launch_expert_ffn(ctx, xm, nullptr, T, n_dev, expert_offsets, perm_src, y, y_shared, ws, L, true, s)) != FMOE_OK)
+      return rc;
+    return launch_combine(ctx, y, y_shared, inv_perm, topk_gate, nullptr, T, n_dev, add_residual ? xm : nullptr,
+                          out, s);
+  }
   if (do_prune) {
     rc = launch_prune(ctx, params, probs, is_visual, cu_seqlens, B, T, attn_importance, kept_idx,
-                      new_cu_seqlens, nullptr, is_visual_out, ws, L, s);
+                      new_cu_seqlens, nullptr, is_visual_out, nullptr, nullptr, nullptr, ws, L, s);
     kept = kept_idx;
     n_dev = new_cu_seqlens + B;
   } else {

@@ -65,6 +65,8 @@ struct fmoe_ws_layout {
   size_t probs, topk_idx, topk_gate;            // layer_forward intermediates
   size_t vis_tok, vis_ord, seq_nv;              // prune
   size_t win_s, win_a, drop_from, keep_prefix;  // prune
+  size_t rank_c, win_merged, merged_before;     // prune with window merging
+  size_t is_merged, vis_out, x_merged;          // layer_forward with window merging
   size_t slot_rank, blk_count;                  // permute
   size_t expert_offsets, perm_src, inv_perm;    // layer_forward intermediates
   size_t tiles, tiles2, tile_count;             // grouped GEMM tile lists (gate/up, down)
@@ -104,13 +106,16 @@ struct fmoe_ordinals_job {
   int B;
   int32_t *vis_ord, *vis_tok, *seq_nv;
 };
+// T_dev (nullable): device count of the tokens actually present (<= T, the capacity).
 int launch_route(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int T, float* probs,
-                 int32_t* topk_idx, float* topk_gate, const fmoe_ordinals_job& ord, hipStream_t stream);
+                 int32_t* topk_idx, float* topk_gate, const fmoe_ordinals_job& ord, hipStream_t stream,
+                 const int32_t* T_dev = nullptr);
 
 int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* probs,
                  const uint8_t* is_visual, const int32_t* cu_seqlens, int B, int T,
                  const float* attn, int32_t* kept_idx, int32_t* new_cu_seqlens, float* scores_out,
-                 uint8_t* is_visual_out, void* ws, const fmoe_ws_layout& L, hipStream_t stream);
+                 uint8_t* is_visual_out, const void* x_in, void* x_merged, uint8_t* is_merged_out,
+                 void* ws, const fmoe_ws_layout& L, hipStream_t stream);
 
 // Small batches: window scores, then ONE block for drop order, compaction, permutation by expert and
 // the grouped-GEMM tile lists (prune == false: every token is kept).  Expects the visual ordinals in
@@ -162,6 +167,22 @@ __device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }
 template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+// One rounding from fp64 to the storage type.  bf16 goes through an fp32 value rounded to odd (the
+// truncated value with a sticky last bit), from which the nearest-even rounding to 8 significant
+// bits is the same as from the double itself.
+template <typename T> __device__ __forceinline__ T from_f64(double v);
+template <> __device__ __forceinline__ float from_f64<float>(double v) { return (float)v; }
+template <> __device__ __forceinline__ bf16_t from_f64<bf16_t>(double v) {
+  const float f = (float)v;
+  const double back = (double)f;
+  uint32_t u = __float_as_uint(f);
+  if (back != v) {
+    if (fabs(back) > fabs(v)) u -= 1u;   // step back towards zero: the truncated value
+    u |= 1u;
+  }
+  return f32_to_bf16(__uint_as_float(u));
+}
 
 // number of valid entries: the device-side count if given (clamped to the capacity), else cap
 __device__ __forceinline__ int resolve_count(int cap, const int32_t* n_dev) {

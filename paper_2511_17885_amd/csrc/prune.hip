@@ -40,11 +40,12 @@ __global__ __launch_bounds__(256) void window_score_kernel(
     const float* __restrict__ probs, const int32_t* __restrict__ cu, int B, int T, int E, int W,
     int sim_mode, const int32_t* __restrict__ vis_tok, const int32_t* __restrict__ seq_nv,
     const float* __restrict__ attn, float* __restrict__ win_s, float* __restrict__ win_a,
-    int32_t* __restrict__ precede) {
+    int32_t* __restrict__ precede, int32_t* __restrict__ rank_c) {
   const int lane = threadIdx.x & 63;
   const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (g >= T) return;
   if (lane == 0) precede[g] = 0;   // accumulated by select_kernel
+  if (lane == 0 && rank_c != nullptr) rank_c[g] = 0;
   const int b = find_seq(cu, B, g);
   int s, e;
   seq_range(cu, b, T, s, e);
@@ -148,7 +149,10 @@ constexpr int SEL_JC = 64;
 __global__ __launch_bounds__(256) void select_kernel(
     const int32_t* __restrict__ cu, int B, int T, int W, float alpha,
     const int32_t* __restrict__ seq_nv, const float* __restrict__ win_s,
-    const float* __restrict__ win_a, int32_t* __restrict__ precede, float* __restrict__ scores_out) {
+    const float* __restrict__ win_a, int32_t* __restrict__ precede, float* __restrict__ scores_out,
+    int32_t* __restrict__ rank_c, const int32_t* __restrict__ only_merged) {
+  // rank_c (window merging): also count the predecessors in the merge order (C desc, index asc).
+  // only_merged (second pass of window merging): count only predecessors whose flag is set.
   __shared__ __align__(16) unsigned long long tileK[SEL_JC];   // (~key(C) << 32) | index: ascending = drop order
   __shared__ __align__(16) uint32_t tileA[SEL_JC];             // key(A)
   __shared__ float red[4];
@@ -200,14 +204,14 @@ __global__ __launch_bounds__(256) void select_kernel(
       Ki = ((unsigned long long)(~float_order_key(c)) << 32) | (uint32_t)i;
       Ai = float_order_key(a);
     }
-    int count = 0, last_first = 0;
+    int count = 0, last_first = 0, count_c = 0;
     for (int j0 = jbase; j0 < n; j0 += (int)gridDim.y * SEL_JC) {   // uniform
       __syncthreads();
       if (threadIdx.x < SEL_JC) {
         const int jl = j0 + threadIdx.x;
         unsigned long long kj = ~0ull;   // sentinel: precedes nothing
         uint32_t aj = ~0u;
-        if (jl < n) {
+        if (jl < n && (only_merged == nullptr || only_merged[s + jl] != 0)) {
           float a;
           const float c = score(jl, a);
           kj = ((unsigned long long)(~float_order_key(c)) << 32) | (uint32_t)jl;
@@ -225,11 +229,47 @@ __global__ __launch_bounds__(256) void select_kernel(
           const int first = (int)(A < Ai) | ((int)(A == Ai) & (int)(K < Ki));
           count += first;
           last_first |= first & (int)(j0 + jj == n - 1);
+          count_c += (int)(K < Ki);
         }
       }
     }
     if (mine && (count | last_first)) atomicAdd(&precede[g], count + (last_first << 30));
+    if (mine && rank_c != nullptr && count_c) atomicAdd(&rank_c[g], count_c);
   }
+}
+
+// ---- C2: window merging (Sec. 3.2.3, Eq.14-15): which windows merge.  One thread per window slot;
+// the greedy walk is evaluated in closed form from the window's place in the merge order and the
+// place of the sequence's last window (merge_plan).  Also clears the counter of the second counting
+// pass.
+__global__ __launch_bounds__(256) void merge_decide_kernel(
+    const int32_t* __restrict__ cu, int B, int T, int W, float retention, float gamma,
+    const int32_t* __restrict__ seq_nv, const int32_t* __restrict__ rank_c,
+    int32_t* __restrict__ win_merged, int32_t* __restrict__ merged_before) {
+  const int g = blockIdx.x * 256 + threadIdx.x;
+  if (g >= T) return;
+  merged_before[g] = 0;
+  win_merged[g] = 0;
+  const int b = find_seq(cu, B, g);
+  int s, e;
+  seq_range(cu, b, T, s, e);
+  const int nv = seq_nv[b];
+  const int n = (nv + W - 1) / W;
+  const int i = g - s;
+  if (i < 0 || i >= n) return;
+  const int w_last = nv - (n - 1) * W;
+  const bool short_last = w_last < W;
+  const int L = short_last ? rank_c[s + n - 1] : n;
+  const fmoe_merge_plan p = merge_plan(nv, W, retention, gamma, L);
+  int m;
+  if (short_last && i == n - 1) {
+    m = p.last_m;
+  } else {
+    const int r = rank_c[g];
+    const int k = r - ((short_last && L < r) ? 1 : 0);   // place among the full-size windows
+    m = k < p.q_full ? 1 : 0;
+  }
+  win_merged[g] = m;
 }
 
 // ---- D: budget + compaction.  A single block walks the tokens in order, keeps text tokens and the
@@ -240,13 +280,17 @@ __global__ __launch_bounds__(1024) void compact_kernel(
     float retention, const int32_t* __restrict__ vis_ord, const int32_t* __restrict__ seq_nv,
     const int32_t* __restrict__ precede, int32_t* __restrict__ keep_prefix,
     int32_t* __restrict__ kept_idx,
-    int32_t* __restrict__ new_cu, uint8_t* __restrict__ is_visual_out) {
+    int32_t* __restrict__ new_cu, uint8_t* __restrict__ is_visual_out,
+    float gamma, const int32_t* __restrict__ rank_c, const int32_t* __restrict__ win_merged,
+    const int32_t* __restrict__ merged_before, uint8_t* __restrict__ is_merged_out) {
+  // gamma > 0 (window merging): a merged window keeps exactly its first token; the others follow the
+  // drop rule with the merged windows taken out of the walk and the budget merging left.
   __shared__ int wave_tot[16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int running = 0;
   for (int base = 0; base < T; base += 1024) {
     const int t = base + threadIdx.x;
-    bool keep = false;
+    bool keep = false, merged_tok = false;
     if (t < T) {
       const int ord = vis_ord[t];
       if (ord < 0) {
@@ -254,7 +298,20 @@ __global__ __launch_bounds__(1024) void compact_kernel(
       } else {
         const int b = find_seq(cu, B, t);
         const int s = clampi(cu[b], 0, T);
-        keep = (ord % W) < window_keep_lead(ord, seq_nv[b], W, retention, precede[s + ord / W]);
+        const int nv = seq_nv[b];
+        if (!(gamma > 0.0f)) {
+          keep = (ord % W) < window_keep_lead(ord, nv, W, retention, precede[s + ord / W]);
+        } else if (win_merged[s + ord / W]) {
+          keep = merged_tok = (ord % W) == 0;
+        } else {
+          const int n = (nv + W - 1) / W;
+          const bool short_last = nv - (n - 1) * W < W;
+          const int L = short_last ? rank_c[s + n - 1] : n;
+          const fmoe_merge_plan p = merge_plan(nv, W, retention, gamma, L);
+          keep = (ord % W) < window_keep_lead_merge(ord, nv, W, precede[s + ord / W],
+                                                    merged_before[s + ord / W],
+                                                    win_merged[s + n - 1] != 0, p.u_rem);
+        }
       }
     }
     const unsigned long long mask = __ballot(keep);
@@ -273,6 +330,7 @@ __global__ __launch_bounds__(1024) void compact_kernel(
       if (keep) {
         kept_idx[pos] = t;
         if (is_visual_out != nullptr) is_visual_out[pos] = is_visual[t];
+        if (is_merged_out != nullptr) is_merged_out[pos] = merged_tok ? 1 : 0;
       }
     }
     running += total;
@@ -281,6 +339,67 @@ __global__ __launch_bounds__(1024) void compact_kernel(
   if (threadIdx.x == 0) keep_prefix[T] = running;
   __syncthreads();
   for (int b = threadIdx.x; b <= B; b += 1024) new_cu[b] = keep_prefix[clampi(cu[b], 0, T)];
+}
+
+// ---- D2: the layer input after merging (Eq.16-18).  One block per kept position: an ordinary token's
+// row is copied; a merged token becomes the mean of its window's rows, rescaled to the largest row
+// norm of the window.  The few merged rows are computed in fp64 with one rounding to the storage
+// type, so that the routing decisions taken on them afterwards see the correctly rounded token.
+__device__ __forceinline__ double block_sum_f64(double v, double* red) {
+#pragma unroll
+  for (int sh = 32; sh >= 1; sh >>= 1) v += __shfl_xor(v, sh, 64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void merge_gather_kernel(
+    const T* __restrict__ x, int d, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ n_dev,
+    const uint8_t* __restrict__ is_merged, const int32_t* __restrict__ cu, int B, int Ttot, int W,
+    const int32_t* __restrict__ vis_ord, const int32_t* __restrict__ vis_tok,
+    const int32_t* __restrict__ seq_nv, T* __restrict__ x_merged) {
+  __shared__ double red[4];
+  const int p = blockIdx.x;
+  if (p >= *n_dev) return;
+  const int t = kept_idx[p];
+  const T* src = x + (size_t)t * d;
+  T* dst = x_merged + (size_t)p * d;
+  if (!is_merged[p]) {
+    for (int c = threadIdx.x; c < d; c += 256) dst[c] = src[c];
+    return;
+  }
+  const int b = find_seq(cu, B, t);
+  const int s = clampi(cu[b], 0, Ttot);
+  const int ord = vis_ord[t];
+  const int nv = seq_nv[b];
+  const int w = (nv - ord < W) ? (nv - ord) : W;
+  const int32_t* toks = vis_tok + s + ord;
+  double max_row_sq = 0.0;
+  for (int j = 0; j < w; ++j) {   // Eq.18: the largest token norm of the window
+    const T* row = x + (size_t)toks[j] * d;
+    double part = 0.0;
+    for (int c = threadIdx.x; c < d; c += 256) {
+      const double v = (double)to_f32(row[c]);
+      part += v * v;
+    }
+    const double tot = block_sum_f64(part, red);
+    max_row_sq = tot > max_row_sq ? tot : max_row_sq;
+  }
+  auto column_mean = [&](int c) -> double {   // Eq.16-17 with the window's real size
+    double acc = 0.0;
+    for (int j = 0; j < w; ++j) acc += (double)to_f32(x[(size_t)toks[j] * d + c]);
+    return acc / (double)w;
+  };
+  double mean_sq = 0.0;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const double mu = column_mean(c);
+    mean_sq += mu * mu;
+  }
+  const double mean_norm = sqrt(block_sum_f64(mean_sq, red));
+  const double scale = mean_norm > 0.0 ? sqrt(max_row_sq) / mean_norm : 0.0;
+  for (int c = threadIdx.x; c < d; c += 256) dst[c] = from_f64<T>(column_mean(c) * scale);
 }
 
 __global__ void identity_kept_kernel(const uint8_t* __restrict__ is_visual,
@@ -647,7 +766,8 @@ __global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallA
 int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* probs,
                  const uint8_t* is_visual, const int32_t* cu_seqlens, int B, int T,
                  const float* attn, int32_t* kept_idx, int32_t* new_cu_seqlens, float* scores_out,
-                 uint8_t* is_visual_out, void* ws, const fmoe_ws_layout& L, hipStream_t stream) {
+                 uint8_t* is_visual_out, const void* x_in, void* x_merged, uint8_t* is_merged_out,
+                 void* ws, const fmoe_ws_layout& L, hipStream_t stream) {
   char* base = static_cast<char*>(ws);
   int32_t* vis_tok = reinterpret_cast<int32_t*>(base + L.vis_tok);
   int32_t* vis_ord = reinterpret_cast<int32_t*>(base + L.vis_ord);
@@ -656,6 +776,12 @@ int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* 
   float* win_a = attn ? reinterpret_cast<float*>(base + L.win_a) : nullptr;
   int32_t* drop_from = reinterpret_cast<int32_t*>(base + L.drop_from);
   int32_t* keep_prefix = reinterpret_cast<int32_t*>(base + L.keep_prefix);
+  const bool merging = pp->gamma > 0.0f;
+  int32_t* rank_c = merging ? reinterpret_cast<int32_t*>(base + L.rank_c) : nullptr;
+  int32_t* win_merged = merging ? reinterpret_cast<int32_t*>(base + L.win_merged) : nullptr;
+  int32_t* merged_before = merging ? reinterpret_cast<int32_t*>(base + L.merged_before) : nullptr;
+  uint8_t* is_merged = is_merged_out;
+  if (merging && is_merged == nullptr) is_merged = reinterpret_cast<uint8_t*>(base + L.is_merged);
   const int E = ctx->cfg.n_experts;
   if (T == 0 || B == 0) return launch_identity_kept(is_visual, cu_seqlens, B, T, kept_idx,
                                                     new_cu_seqlens, is_visual_out, stream);
@@ -668,21 +794,43 @@ int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* 
   {
     fmoe_prof_scope prof(ctx, SLOT_SCORES, stream);
     hipLaunchKernelGGL(window_score_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, probs, cu_seqlens,
-                       B, T, E, pp->window, pp->sim_mode, vis_tok, seq_nv, attn, win_s, win_a, drop_from);
+                       B, T, E, pp->window, pp->sim_mode, vis_tok, seq_nv, attn, win_s, win_a, drop_from,
+                       rank_c);
   }
+  const int n_max = (T + pp->window - 1) / pp->window;   // no sequence has more windows
+  const int gy = (n_max + SEL_JC - 1) / SEL_JC;
+  const dim3 sel_grid((T + 255) / 256, gy < 4096 ? gy : 4096);
   {
     fmoe_prof_scope prof(ctx, SLOT_SELECT, stream);
-    const int n_max = (T + pp->window - 1) / pp->window;   // no sequence has more windows
-    const int gy = (n_max + SEL_JC - 1) / SEL_JC;
-    hipLaunchKernelGGL(select_kernel, dim3((T + 255) / 256, gy < 4096 ? gy : 4096), dim3(256), 0,
-                       stream, cu_seqlens, B, T, pp->window, pp->alpha, seq_nv, win_s, win_a, drop_from,
-                       scores_out);
+    hipLaunchKernelGGL(select_kernel, sel_grid, dim3(256), 0, stream, cu_seqlens, B, T, pp->window,
+                       pp->alpha, seq_nv, win_s, win_a, drop_from, scores_out, rank_c,
+                       static_cast<const int32_t*>(nullptr));
+  }
+  if (merging) {   // which windows merge, then how many merged windows precede each window in drop order
+    hipLaunchKernelGGL(merge_decide_kernel, dim3((T + 255) / 256), dim3(256), 0, stream, cu_seqlens, B, T,
+                       pp->window, pp->retention, pp->gamma, seq_nv, rank_c, win_merged, merged_before);
+    hipLaunchKernelGGL(select_kernel, sel_grid, dim3(256), 0, stream, cu_seqlens, B, T, pp->window,
+                       pp->alpha, seq_nv, win_s, win_a, merged_before, static_cast<float*>(nullptr),
+                       static_cast<int32_t*>(nullptr), static_cast<const int32_t*>(win_merged));
   }
   {
     fmoe_prof_scope prof(ctx, SLOT_COMPACT, stream);
     hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, stream, is_visual, cu_seqlens, B, T,
                        pp->window, pp->retention, vis_ord, seq_nv, drop_from, keep_prefix, kept_idx,
-                       new_cu_seqlens, is_visual_out);
+                       new_cu_seqlens, is_visual_out, pp->gamma, rank_c, win_merged, merged_before,
+                       merging ? is_merged : static_cast<uint8_t*>(nullptr));
+  }
+  if (merging) {
+    if (ctx->cfg.dtype == FMOE_BF16)
+      hipLaunchKernelGGL(merge_gather_kernel<bf16_t>, dim3(T), dim3(256), 0, stream,
+                         static_cast<const bf16_t*>(x_in), ctx->cfg.d_model, kept_idx, new_cu_seqlens + B,
+                         is_merged, cu_seqlens, B, T, pp->window, vis_ord, vis_tok, seq_nv,
+                         static_cast<bf16_t*>(x_merged));
+    else
+      hipLaunchKernelGGL(merge_gather_kernel<float>, dim3(T), dim3(256), 0, stream,
+                         static_cast<const float*>(x_in), ctx->cfg.d_model, kept_idx, new_cu_seqlens + B,
+                         is_merged, cu_seqlens, B, T, pp->window, vis_ord, vis_tok, seq_nv,
+                         static_cast<float*>(x_merged));
   }
   FMOE_HIP_CHECK(hipGetLastError());
   return FMOE_OK;
@@ -720,7 +868,8 @@ int launch_prune_dispatch_small(const fmoe_ctx* ctx, const fmoe_prune_params* pp
   if (prune) {   // the visual ordinals were produced in the router's launch
     fmoe_prof_scope prof(ctx, SLOT_SCORES, stream);
     hipLaunchKernelGGL(window_score_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, probs, cu_seqlens,
-                       B, T, E, pp->window, pp->sim_mode, vis_tok, seq_nv, attn, win_s, win_a, drop_from);
+                       B, T, E, pp->window, pp->sim_mode, vis_tok, seq_nv, attn, win_s, win_a, drop_from,
+                       static_cast<int32_t*>(nullptr));
   }
   SmallArgs a;
   a.prune = prune ? 1 : 0;

@@ -82,6 +82,69 @@ __device__ __forceinline__ float redundancy_score(float S, bool has_attn, float 
   return t1 - t2;
 }
 
+// eta = floor(r*N_v + 1/2) in fp64, clamped to [min(1,N_v), N_v] (Sec. 3.2.3, exact-count rule)
+__device__ __forceinline__ int token_budget(int nv, float retention) {
+  int eta = (int)floor((double)retention * (double)nv + 0.5);
+  eta = eta > nv ? nv : eta;
+  const int lo = nv < 1 ? nv : 1;
+  return eta < lo ? lo : eta;
+}
+
+// Outcome of the greedy merge walk of Sec. 3.2.3 (windows in the order (C desc, index asc); a window
+// of w >= 2 tokens merges if w-1 <= u, u -= w-1, at most m = floor(eta*gamma) merges) in closed form.
+// All windows cost W-1 except a shorter last one (w_last-1; not mergeable if w_last == 1), so the walk
+// is determined by L, the place of the last window in that order:
+//   full windows merge iff their place among the full windows is < q_full; the last window iff last_m.
+struct fmoe_merge_plan {
+  int q_full;     // number of merged full-size windows (the first q_full of them in merge order)
+  int last_m;     // 1: the (shorter) last window is merged
+  int u_rem;      // tokens still to drop after merging
+};
+__device__ __forceinline__ fmoe_merge_plan merge_plan(int nv, int W, float retention, float gamma, int L) {
+  fmoe_merge_plan p;
+  const int eta = token_budget(nv, retention);
+  const int eps = nv - eta;
+  p.q_full = 0; p.last_m = 0; p.u_rem = eps;
+  const int n = (nv + W - 1) / W;
+  if (!(gamma > 0.0f) || n == 0 || W < 2) return p;
+  const int m = (int)floor((double)eta * (double)gamma);
+  const int c = W - 1;
+  const int w_last = nv - (n - 1) * W;
+  const bool short_last = w_last < W;
+  if (!short_last) {                         // every window costs c
+    int q = eps / c;
+    q = q < m ? q : m;
+    q = q < n ? q : n;
+    p.q_full = q;
+    p.u_rem = eps - q * c;
+    return p;
+  }
+  const int n_full = n - 1;
+  const int c_last = w_last - 1;
+  int q0 = eps / c;                          // full windows that merge if nothing else interferes
+  q0 = q0 < m ? q0 : m;
+  q0 = q0 < n_full ? q0 : n_full;
+  if (q0 < L) {                              // the walk stalls on a full window before reaching the last one:
+    p.q_full = q0;                           // full windows never resume; the last one may still fit
+    const int u = eps - q0 * c;
+    p.last_m = (c_last >= 1 && q0 < m && c_last <= u) ? 1 : 0;
+    p.u_rem = u - p.last_m * c_last;
+    return p;
+  }
+  // the L full windows ahead of the last one all merge, then the last one gets its turn
+  int u = eps - L * c;
+  p.last_m = (c_last >= 1 && L < m && c_last <= u) ? 1 : 0;
+  u -= p.last_m * c_last;
+  int more = u / c;
+  const int room = m - L - p.last_m;
+  more = more < room ? more : room;
+  more = more < n_full - L ? more : n_full - L;
+  more = more > 0 ? more : 0;
+  p.q_full = L + more;
+  p.u_rem = u - more * c;
+  return p;
+}
+
 // Number of leading tokens of visual ordinal `ord`'s window that survive (Sec. 3.2.3 budget and the
 // drop rule): windows are dropped whole in drop order while they fit in eps = N_v - eta and the
 // next one loses its last tokens.  pc = number of windows ahead of this window in drop order, bit
@@ -89,16 +152,30 @@ __device__ __forceinline__ float redundancy_score(float S, bool has_attn, float 
 __device__ __forceinline__ int window_keep_lead(int ord, int nv, int W, float retention, int pc) {
   const int n = (nv + W - 1) / W;
   const int i = ord / W;
-  int eta = (int)floor((double)retention * (double)nv + 0.5);   // eta = floor(r*N_v + 1/2), fp64
-  eta = eta > nv ? nv : eta;
-  eta = eta < 1 ? 1 : eta;
-  const int eps = nv - eta;
+  const int eps = nv - token_budget(nv, retention);
   const int count = pc & 0x3fffffff, last_first = pc >> 30;
   const int w_last = nv - (n - 1) * W;
   const int before = count * W - (last_first ? (W - w_last) : 0);
   const int wi = (i == n - 1) ? w_last : W;
   if (before + wi <= eps) return 0;
   if (before < eps) return wi - (eps - before);
+  return wi;
+}
+
+// The same with window merging: `merged_before` merged windows are among the `pc` predecessors (they
+// are no longer part of the drop walk), the last window counts as a predecessor only if it was not
+// merged, and the budget is what merging left.
+__device__ __forceinline__ int window_keep_lead_merge(int ord, int nv, int W, int pc, int merged_before,
+                                                      bool last_merged, int u_rem) {
+  const int n = (nv + W - 1) / W;
+  const int i = ord / W;
+  const int count = (pc & 0x3fffffff) - (merged_before & 0x3fffffff);
+  const int last_first = (pc >> 30) && !last_merged;
+  const int w_last = nv - (n - 1) * W;
+  const int before = count * W - (last_first ? (W - w_last) : 0);
+  const int wi = (i == n - 1) ? w_last : W;
+  if (before + wi <= u_rem) return 0;
+  if (before < u_rem) return wi - (u_rem - before);
   return wi;
 }
 #endif

@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256) void route_kernel(
     const XT* __restrict__ x, const fx4_t* __restrict__ wp, const float* __restrict__ bias,
     const uint8_t* __restrict__ is_visual, int T, int d, int E, int Eb, int G, int nch, int k_text,
     int k_visual, int Kmax, int renorm, float* __restrict__ probs, int32_t* __restrict__ topk_idx,
-    float* __restrict__ topk_gate, int route_blocks, fmoe_ordinals_job ord) {
+    float* __restrict__ topk_gate, int route_blocks, fmoe_ordinals_job ord, const int32_t* __restrict__ T_dev) {
   __shared__ __align__(16) float xs[64 * RS];
   __shared__ float zs[TOKB][4 * NB * 16 + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -190,6 +190,11 @@ __global__ __launch_bounds__(256) void route_kernel(
     return;
   }
   const int t0 = blockIdx.x * TOKB;
+  if (T_dev != nullptr) {   // the batch holds fewer tokens than its capacity
+    const int Td = *T_dev;
+    T = Td < T ? Td : T;
+    if (t0 >= T) return;
+  }
 
   f32x4_t acc[NB];
 #pragma unroll
@@ -380,7 +385,7 @@ __global__ __launch_bounds__(256) void route_kernel(
 
 template <typename XT, int NB, int PF>
 int launch_route_t(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int T, float* probs,
-                   int32_t* topk_idx, float* topk_gate, const fmoe_ordinals_job& ord, hipStream_t stream) {
+                   int32_t* topk_idx, float* topk_gate, const fmoe_ordinals_job& ord, hipStream_t stream, const int32_t* T_dev) {
   const int d = ctx->cfg.d_model, E = ctx->cfg.n_experts;
   const int Eb = (E + 15) / 16, G = router_groups(d);
   const int nch = (((d + KC - 1) / KC + PF - 1) / PF) * PF;   // <= G / NG by construction
@@ -390,26 +395,26 @@ int launch_route_t(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual,
   hipLaunchKernelGGL((route_kernel<XT, NB, PF>), dim3(grid + riders), dim3(256), 0, stream,
                      static_cast<const XT*>(x), reinterpret_cast<const fx4_t*>(ctx->router_wp),
                      ctx->router_bias, is_visual, T, d, E, Eb, G, nch, ctx->cfg.k_text, ctx->cfg.k_visual,
-                     ctx->kmax, ctx->cfg.renormalize, probs, topk_idx, topk_gate, grid, ord);
+                     ctx->kmax, ctx->cfg.renormalize, probs, topk_idx, topk_gate, grid, ord, T_dev);
   FMOE_HIP_CHECK(hipGetLastError());
   return FMOE_OK;
 }
 
 template <typename XT>
 int launch_route_x(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int T, float* probs,
-                   int32_t* topk_idx, float* topk_gate, const fmoe_ordinals_job& ord, hipStream_t stream) {
+                   int32_t* topk_idx, float* topk_gate, const fmoe_ordinals_job& ord, hipStream_t stream, const int32_t* T_dev) {
   const int E = ctx->cfg.n_experts;
   const int chunks = (ctx->cfg.d_model + KC - 1) / KC;
   if (E <= 64) {
-    if (chunks < 4) return launch_route_t<XT, 1, 1>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream);
-    if (chunks % 5 == 0) return launch_route_t<XT, 1, 5>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream);
-    return launch_route_t<XT, 1, 4>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream);
+    if (chunks < 4) return launch_route_t<XT, 1, 1>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream, T_dev);
+    if (chunks % 5 == 0) return launch_route_t<XT, 1, 5>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream, T_dev);
+    return launch_route_t<XT, 1, 4>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream, T_dev);
   }
   if (E <= 128) {
-    if (chunks < 2) return launch_route_t<XT, 2, 1>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream);
-    return launch_route_t<XT, 2, 2>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream);
+    if (chunks < 2) return launch_route_t<XT, 2, 1>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream, T_dev);
+    return launch_route_t<XT, 2, 2>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream, T_dev);
   }
-  return launch_route_t<XT, 4, 1>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream);
+  return launch_route_t<XT, 4, 1>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream, T_dev);
 }
 
 }  // namespace
@@ -435,9 +440,9 @@ int launch_pack_router(const fmoe_ctx* ctx, const void* router_w, float* wp, hip
 }
 
 int launch_route(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int T, float* probs,
-                 int32_t* topk_idx, float* topk_gate, const fmoe_ordinals_job& ord, hipStream_t stream) {
+                 int32_t* topk_idx, float* topk_gate, const fmoe_ordinals_job& ord, hipStream_t stream, const int32_t* T_dev) {
   if (T == 0) return FMOE_OK;
   if (ctx->cfg.dtype == FMOE_BF16)
-    return launch_route_x<bf16_t>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream);
-  return launch_route_x<float>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream);
+    return launch_route_x<bf16_t>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream, T_dev);
+  return launch_route_x<float>(ctx, x, is_visual, T, probs, topk_idx, topk_gate, ord, stream, T_dev);
 }

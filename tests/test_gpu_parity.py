@@ -163,6 +163,89 @@ def test_prune_tied_scores_identical_windows():
     assert list(o_kept) == list(range(Wn * n // 2, Wn * n))     # the first half of the windows goes
 
 
+# ---------------------------------------------------------------- prune with window merging
+def _merge_gammas(wl):
+    g = [0.05, 0.3]
+    if wl.window > 1 and wl.retention < 1.0:
+        g.append(min(oracle.gamma_hat(wl.retention, wl.window, stages=1), 0.95))   # App. D: merging alone
+    return g
+
+
+def _check_merged_rows(x_m, o_xm, o_is_merged, dtype):
+    """Ordinary rows are copies (bit-exact); merged rows are one rounding of an fp64 result on both
+    sides, so they may differ by one unit in the last place where the fp64 sums disagree."""
+    plain = o_is_merged == 0
+    assert np.array_equal(x_m[plain], o_xm[plain])
+    if (~plain).any():
+        assert max_rel_err(x_m[~plain], o_xm[~plain]) <= TOL[dtype]
+        assert (x_m[~plain] != o_xm[~plain]).mean() <= 1e-3
+
+
+@pytest.mark.parametrize("seed,kw", SMALL)
+def test_prune_merge(seed, kw):
+    wl = _wl(seed, kw)
+    bf = wl.dtype == W.BF16
+    o_probs, _, _ = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias,
+                                 wl.k_text, wl.k_visual)
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    for gamma in _merge_gammas(wl):
+        o_kept, o_cu, _, o_mrg, o_xm = oracle.prune(o_probs, wl.is_visual, wl.cu_seqlens, wl.retention,
+                                                    wl.window, gamma=gamma, x=wl.x, is_bf16=bf)
+        pp = binding.prune_params(retention=wl.retention, window=wl.window, gamma=gamma)
+        kept, new_cu, _, mrg, x_m = m.prune(pp, dev(o_probs), vis, cu, x=x)
+        torch.cuda.synchronize()
+        new_cu = host(new_cu)
+        n = int(new_cu[-1])
+        assert np.array_equal(new_cu, o_cu), gamma
+        assert np.array_equal(host(kept)[:n], o_kept), gamma
+        assert np.array_equal(host(mrg)[:n], o_mrg), gamma
+        _check_merged_rows(host(x_m)[:n], o_xm, o_mrg, wl.dtype)
+
+
+@pytest.mark.parametrize("gamma", [0.02, 0.2, 0.7])
+def test_prune_merge_with_attention_and_short_last_window(gamma):
+    # N_v = 77 and 32 with W = 5: both sequences end in a 2-token window; the attention term moves the
+    # last window around in the merge order
+    wl = W.small_random(116, T_v=[77, 32], T_t=[6, 5], d=96, E=24, F=32, k_text=4, k_visual=2,
+                        retention=0.4, window=5, n_components=5, interleave=True)
+    rng = np.random.default_rng(7)
+    attn = rng.random(wl.T).astype(np.float32) ** 2
+    o_probs, _, _ = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, None, 4, 2)
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    for alpha in (1.0, 0.5):
+        a = None if alpha == 1.0 else attn
+        o_kept, o_cu, _, o_mrg, o_xm = oracle.prune(o_probs, wl.is_visual, wl.cu_seqlens, 0.4, 5, alpha=alpha,
+                                                    gamma=gamma, attn=a, x=wl.x)
+        pp = binding.prune_params(retention=0.4, window=5, alpha=alpha, gamma=gamma)
+        kept, new_cu, _, mrg, x_m = m.prune(pp, dev(o_probs), vis, cu, attn=dev(a), x=x)
+        new_cu = host(new_cu)
+        n = int(new_cu[-1])
+        assert np.array_equal(new_cu, o_cu) and np.array_equal(host(kept)[:n], o_kept)
+        assert np.array_equal(host(mrg)[:n], o_mrg)
+        _check_merged_rows(host(x_m)[:n], o_xm, o_mrg, wl.dtype)
+
+
+def test_prune_merge_many_windows_several_blocks():
+    # more windows than one counting tile and one compaction pass hold
+    wl = W.small_random(117, T_v=[2600, 1301], T_t=[40, 9], d=64, E=16, F=32, k_text=2, k_visual=1,
+                        retention=0.5, window=3, n_components=20)
+    o_probs, _, _ = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, None, 2, 1)
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    for gamma in (0.05, oracle.gamma_hat(0.5, 3, stages=1) * 0.9):
+        o_kept, o_cu, _, o_mrg, o_xm = oracle.prune(o_probs, wl.is_visual, wl.cu_seqlens, 0.5, 3, gamma=gamma,
+                                                    x=wl.x)
+        kept, new_cu, _, mrg, x_m = m.prune(binding.prune_params(retention=0.5, window=3, gamma=gamma),
+                                            dev(o_probs), vis, cu, x=x)
+        new_cu = host(new_cu)
+        n = int(new_cu[-1])
+        assert np.array_equal(new_cu, o_cu) and np.array_equal(host(kept)[:n], o_kept)
+        assert np.array_equal(host(mrg)[:n], o_mrg) and o_mrg.sum() > 50
+        _check_merged_rows(host(x_m)[:n], o_xm, o_mrg, wl.dtype)
+
+
 # ---------------------------------------------------------------- permute
 @pytest.mark.parametrize("seed,kw", SMALL)
 def test_permute(seed, kw):
@@ -264,6 +347,34 @@ def test_layer_forward_equals_chained_calls_and_no_prune_path():
         assert np.array_equal(host(kept3), np.arange(wl.T))
         o = _oracle(wl, retention=1.0)
         assert max_rel_err(host(out3), o["out_f64"]) <= TOL[wl.dtype]
+
+
+@pytest.mark.parametrize("seed,kw", SMALL)
+def test_layer_forward_merge(seed, kw):
+    # Sec. 3.2.3 inside the layer: merged layer input, kept tokens routed again, experts on that tensor
+    wl = _wl(seed, kw)
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    for gamma in _merge_gammas(wl)[-2:]:
+        o = _oracle(wl, add_residual=True, gamma=gamma)
+        pp = binding.prune_params(retention=wl.retention, window=wl.window, gamma=gamma)
+        out, kept, new_cu, vis_out = m.layer_forward(x, vis, cu, pp, add_residual=True, want_mask=True)
+        torch.cuda.synchronize()
+        new_cu = host(new_cu)
+        n = int(new_cu[-1])
+        assert np.array_equal(new_cu, o["new_cu_seqlens"])
+        assert np.array_equal(host(kept)[:n], o["kept_idx"])
+        assert np.array_equal(host(vis_out)[:n], wl.is_visual[o["kept_idx"]])
+        if n:
+            assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
+
+
+def test_layer_forward_merge_rejects_router_only_mode():
+    wl = _wl(100, SMALL[0].values[1])
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    with pytest.raises(RuntimeError):
+        m.layer_forward(x, vis, cu, binding.prune_params(retention=0.5, window=3, gamma=0.1, prune_mode=2))
 
 
 # ---------------------------------------------------------------- the benchmark configurations

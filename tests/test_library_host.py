@@ -70,14 +70,14 @@ def test_set_topk_and_null_argument_paths(lib):
     assert lib.fmoe_set_weights(ctx, None, None, None, None, None, None, None, None, None) == -2
     # prune argument validation (host side only)
     pp = binding.prune_params(retention=0.5, window=3)
-    assert lib.fmoe_prune(ctx, None, None, None, None, 1, 4, None, None, None, None, None, None, None, 0, None) == -2
+    assert lib.fmoe_prune(ctx, None, None, None, None, 1, 4, None, None, None, None, None, None, None, None, 0, None) == -2
     bad = binding.prune_params(retention=1.5, window=3)
-    assert lib.fmoe_prune(ctx, C.byref(bad), None, None, None, 1, 4, None, None, None, None, None, None, None, 0, None) == -1
+    assert lib.fmoe_prune(ctx, C.byref(bad), None, None, None, 1, 4, None, None, None, None, None, None, None, None, 0, None) == -1
     bad = binding.prune_params(retention=0.5, window=0)
-    assert lib.fmoe_prune(ctx, C.byref(bad), None, None, None, 1, 4, None, None, None, None, None, None, None, 0, None) == -1
-    bad = binding.prune_params(retention=0.5, window=3, gamma=0.05)
-    assert lib.fmoe_prune(ctx, C.byref(bad), None, None, None, 1, 4, None, None, None, None, None, None, None, 0, None) == -5
-    assert lib.fmoe_prune(ctx, C.byref(pp), None, None, None, 1, 4, None, None, None, None, None, None, None, 0, None) == -2
+    assert lib.fmoe_prune(ctx, C.byref(bad), None, None, None, 1, 4, None, None, None, None, None, None, None, None, 0, None) == -1
+    bad = binding.prune_params(retention=0.5, window=3, gamma=1.0)        # merge rate outside [0,1)
+    assert lib.fmoe_prune(ctx, C.byref(bad), None, None, None, 1, 4, None, None, None, None, None, None, None, None, 0, None) == -1
+    assert lib.fmoe_prune(ctx, C.byref(pp), None, None, None, 1, 4, None, None, None, None, None, None, None, None, 0, None) == -2
     # permute: missing workspace
     dummy = C.c_void_p(0x1000)
     assert lib.fmoe_permute(ctx, dummy, None, 8, None, dummy, dummy, dummy, None, 0, None) == -4
