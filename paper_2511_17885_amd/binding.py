@@ -257,44 +257,69 @@ class FMoE:
         return out, kept_idx, new_cu, is_visual_out
 
 
+def kept_visual_lens(visual_lens, retention):
+    """Per-sequence visual token counts after one pruning stage, on the host: eta_b = floor(r*N_v + 1/2)
+    clamped to [min(1,N_v), N_v] (Sec. 3.2.3).  `retention` is taken at fp32 precision, as the library
+    receives it.  Pure integer bookkeeping that lets a caller size the next layer's call without
+    reading the device."""
+    r = C.c_float(float(retention)).value
+    out = []
+    for nv in visual_lens:
+        eta = int(math.floor(r * nv + 0.5))
+        out.append(min(max(eta, min(1, nv)), nv))
+    return out
+
+
 def kept_count(visual_lens, text_lens, retention):
-    """T' of a pruned batch, on the host: eta_b = floor(r*N_v + 1/2) clamped to [min(1,N_v), N_v] visual
-    tokens of every sequence survive (Sec. 3.2.3), all text tokens do.  Pure integer bookkeeping that
-    lets a caller size the next layer's call without reading the device."""
-    total = 0
-    for nv, nt in zip(visual_lens, text_lens):
-        eta = int(math.floor(float(retention) * nv + 0.5))
-        eta = min(max(eta, min(1, nv)), nv)
-        total += eta + nt
-    return total
+    """T' of a pruned batch, on the host: every sequence keeps eta_b visual tokens (kept_visual_lens)
+    and all its text tokens."""
+    return sum(kept_visual_lens(visual_lens, retention)) + sum(text_lens)
+
+
+def stage_schedule(retention, prune_layers, **prune_kw):
+    """App. D: a cumulative retain ratio r reached in len(prune_layers) stages of equal per-stage ratio
+    beta = r^(1/stages).  Returns {layer: prune params with retention = beta}; the other fields
+    (window, alpha, gamma, sim_mode, prune_mode) are shared by the stages."""
+    stages = len(prune_layers)
+    beta = float(retention) ** (1.0 / stages) if stages else 1.0
+    return {int(l): prune_params(retention=beta, **prune_kw) for l in prune_layers}
 
 
 class FMoEStack:
-    """A stack of MoE layers with x <- x + MoE_l(x), per-layer (k_text, k_visual) and one pruning
-    point (Sec. 3.1: reduced activation from layer l_v on; Sec. 3.2: pruning once the routing has
-    settled).  Host-side sequencing only: every layer is one fmoe_layer_forward enqueue; the token
-    count handed to the layers after the pruning point comes from `kept_count`."""
+    """A stack of MoE layers with x <- x + MoE_l(x), per-layer (k_text, k_visual) (Sec. 3.1: reduced
+    activation from layer l_v on) and pruning stages at chosen layers (Sec. 3.2; App. D: several stages
+    of equal per-stage ratio).  Host-side sequencing only: every layer is one fmoe_layer_forward
+    enqueue; the token count handed to the layers after a pruning stage comes from
+    `kept_visual_lens`, so nothing is read back from the device."""
 
-    def __init__(self, layers, k_schedule, prune_after_layer=None, params=None):
+    def __init__(self, layers, k_schedule, prune_after_layer=None, params=None, prune_schedule=None):
         self.layers = list(layers)
         self.k_schedule = [tuple(k) for k in k_schedule]
-        self.prune_after_layer = prune_after_layer
-        self.params = params
+        self.prune_schedule = dict(prune_schedule or {})
+        if prune_after_layer is not None and params is not None:
+            self.prune_schedule[int(prune_after_layer)] = params
         assert len(self.layers) == len(self.k_schedule)
 
-    def forward(self, x, is_visual, cu_seqlens, visual_lens, text_lens):
-        """visual_lens / text_lens: per-sequence token counts on the host.  Returns (x_out [T', d],
-        kept_idx [T'] indices into the input batch or None, new_cu_seqlens)."""
+    def forward(self, x, is_visual, cu_seqlens, visual_lens, text_lens, attn=None):
+        """visual_lens / text_lens: per-sequence token counts on the host.  attn: {layer: importance
+        [T at that layer]} for stages that use the attention term.  Returns (x_out [T', d], kept_idx
+        [T'] indices into the input batch or None, new_cu_seqlens)."""
         T = x.shape[0]
         kept_total = None
+        visual_lens = list(visual_lens)
         for l, layer in enumerate(self.layers):
             layer.set_topk(*self.k_schedule[l])
-            if l == self.prune_after_layer and self.params is not None:
-                out, kept, new_cu, vis_out = layer.layer_forward(x, is_visual, cu_seqlens, self.params,
+            params = self.prune_schedule.get(l)
+            if params is not None:
+                a = attn.get(l) if attn else None
+                out, kept, new_cu, vis_out = layer.layer_forward(x, is_visual, cu_seqlens, params, attn=a,
                                                                  add_residual=True, want_mask=True)
-                T = kept_count(visual_lens, text_lens, self.params.retention)
+                if params.prune_mode != 0 and params.retention < 1.0:
+                    visual_lens = kept_visual_lens(visual_lens, params.retention)
+                T = sum(visual_lens) + sum(text_lens)
                 x, is_visual, cu_seqlens = out[:T], vis_out[:T], new_cu
-                kept_total = kept[:T]
+                # index bookkeeping across stages: positions in the input batch of what is still there
+                kept_total = kept[:T] if kept_total is None else kept_total[kept[:T].long()]
             else:
                 out, _, _, _ = layer.layer_forward(x, is_visual, cu_seqlens, None, add_residual=True)
                 x = out[:T]

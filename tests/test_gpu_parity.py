@@ -441,28 +441,35 @@ def test_config3_full_activation_no_pruning_sampled():
 
 
 # ---------------------------------------------------------------- the ragged multi-layer stack
-def _oracle_stack(wl):
-    """x <- x + MoE_l(x) layer by layer on the CPU; pruning once, after `prune_after_layer`."""
+def _oracle_stack(wl, schedule=None):
+    """x <- x + MoE_l(x) layer by layer on the CPU; `schedule` = {layer: dict(retention, window, alpha,
+    gamma)} (default: one stage after `prune_after_layer`)."""
     is_bf16 = wl.dtype == W.BF16
+    if schedule is None:
+        schedule = {wl.prune_after_layer: dict(retention=wl.retention, window=wl.window)}
     x, vis, cu = wl.x, wl.is_visual, wl.cu_seqlens
     kept_total = None
     for l, lw in enumerate(wl.layers):
         kt, kv = wl.k_schedule[l]
-        prune_here = l == wl.prune_after_layer
+        st = schedule.get(l)
         o = oracle.layer_forward(x, vis, cu, lw, k_text=kt, k_visual=kv, is_bf16=is_bf16,
-                                 retention=wl.retention if prune_here else 1.0, window=wl.window,
-                                 add_residual=True, do_prune=prune_here)
-        if prune_here:
-            kept_total = o["kept_idx"]
-            vis, cu = vis[kept_total], o["new_cu_seqlens"]
+                                 add_residual=True, do_prune=st is not None,
+                                 **(st if st is not None else dict(retention=1.0, window=wl.window)))
+        if st is not None:
+            kept = o["kept_idx"]
+            kept_total = kept if kept_total is None else kept_total[kept]
+            vis, cu = vis[kept], o["new_cu_seqlens"]
         x = o["out"]
     return x, kept_total, cu
 
 
-def _gpu_stack(wl):
+def _gpu_stack(wl, schedule=None):
     layers = [make_layer(wl, layer=l) for l in range(len(wl.layers))]
-    stack = binding.FMoEStack(layers, wl.k_schedule, wl.prune_after_layer,
-                              binding.prune_params(retention=wl.retention, window=wl.window, prune_mode=2))
+    if schedule is None:
+        stack = binding.FMoEStack(layers, wl.k_schedule, wl.prune_after_layer,
+                                  binding.prune_params(retention=wl.retention, window=wl.window, prune_mode=2))
+    else:
+        stack = binding.FMoEStack(layers, wl.k_schedule, prune_schedule=schedule)
     x, vis, cu = inputs(wl)
     lens = np.diff(wl.cu_seqlens)
     nv = [int(wl.is_visual[s:e].sum()) for s, e in zip(wl.cu_seqlens[:-1], wl.cu_seqlens[1:])]
@@ -470,6 +477,28 @@ def _gpu_stack(wl):
     out, kept, new_cu = stack.forward(x, vis, cu, nv, nt)
     torch.cuda.synchronize()
     return host(out), host(kept), host(new_cu), nv, nt
+
+
+@pytest.mark.parametrize("gamma", [0.0, 0.05])
+def test_stack_three_stage_schedule_fp32(gamma):
+    # App. D: r = 0.5 reached in three stages of beta = r^(1/3) after layers 2, 5, 8 (the DeepSeek-VL2
+    # setting of App. A: W = 3, gamma = 0.05), reduced top-k from layer 2 on; fp32 so that every
+    # decision down the stack is compared bit for bit
+    wl = W.config5(n_layers=10, d=128, E=64, F=64, len_div=32, text_len=128, dtype=W.F32)
+    sched = binding.stage_schedule(0.5, [2, 5, 8], window=3, gamma=gamma)
+    assert abs(sched[2].retention ** 3 - 0.5) < 1e-6
+    o_sched = {l: dict(retention=p.retention, window=p.window, alpha=p.alpha, gamma=p.gamma)
+               for l, p in sched.items()}
+    out, kept, new_cu, nv, nt = _gpu_stack(wl, sched)
+    ref, ref_kept, ref_cu = _oracle_stack(wl, o_sched)
+    assert np.array_equal(new_cu, ref_cu)
+    assert np.array_equal(kept, ref_kept)
+    lens = nv
+    for _ in range(3):
+        lens = binding.kept_visual_lens(lens, sched[2].retention)
+    assert out.shape[0] == sum(lens) + sum(nt) == ref.shape[0]
+    assert abs(sum(lens) / sum(nv) - 0.5) < 0.02           # the cumulative ratio of App. D
+    assert max_rel_err(out, ref) <= 10 * TOL[W.F32]
 
 
 def test_stack_ragged_12_layers_fp32():

@@ -92,3 +92,31 @@ def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libfmoe.so")
     with pytest.raises(RuntimeError):
         binding.load()
+
+
+def test_stage_bookkeeping_matches_the_oracles_counts():
+    """Host logic of the stack driver: the per-stage token counts (Sec. 3.2.3 budget, App. D equal
+    per-stage ratio) must be the counts the pruning itself produces, stage after stage, with or
+    without window merging."""
+    import numpy as np
+    import oracle
+    rng = np.random.default_rng(11)
+    sched = binding.stage_schedule(0.25, [5, 8, 12], window=5, gamma=0.1)
+    assert sorted(sched) == [5, 8, 12] and sched[5].window == 5
+    beta = sched[5].retention
+    assert abs(beta ** 3 - 0.25) < 1e-6
+    nv, nt = [57, 5, 0, 301], [3, 0, 4, 10]
+    vis = np.concatenate([np.r_[np.ones(v, np.uint8), np.zeros(t, np.uint8)] for v, t in zip(nv, nt)])
+    cu = np.concatenate([[0], np.cumsum([v + t for v, t in zip(nv, nt)])]).astype(np.int32)
+    lens = list(nv)
+    for _ in range(3):
+        T = int(cu[-1])
+        probs = rng.random((T, 12)).astype(np.float32)
+        probs /= probs.sum(1, keepdims=True)
+        x = rng.standard_normal((T, 8)).astype(np.float32)
+        kept, new_cu, _, _, _ = oracle.prune(probs, vis, cu, beta, 5, gamma=0.1, x=x)
+        lens = binding.kept_visual_lens(lens, beta)
+        assert list(np.diff(new_cu)) == [v + t for v, t in zip(lens, nt)]
+        assert int(new_cu[-1]) == binding.kept_count(lens, nt, 1.0)
+        vis, cu = vis[kept], new_cu
+    assert lens[2] == 0 and lens[1] >= 1                      # empty stays empty; N_v > 0 keeps >= 1
