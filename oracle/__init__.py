@@ -268,3 +268,44 @@ def layer_forward(x, is_visual, cu_seqlens, w, *, k_text, k_visual, is_bf16, ret
         out, out64 = combine(y, ysh, inv, gate, kept, d, x if add_residual else None, is_bf16)
         res.update(y=y, y_shared=ysh, out=out, out_f64=out64)
     return res
+
+
+def adjacent_similarity(probs, is_visual, cu_seqlens):
+    """Fig. 1 statistic.  Returns pair_sim [T] f32 (-2 where no pair starts), mean [2] f64 (text,
+    vision), count [2] i32."""
+    probs, is_visual, cu = _f32(probs), _u8(is_visual), _i32(cu_seqlens)
+    T, E = probs.shape
+    pair = np.empty(max(T, 1), np.float32)
+    mean = np.zeros(2, np.float64)
+    count = np.zeros(2, np.int32)
+    lib().orc_adjacent_similarity(_p(probs, _f32p), _p(is_visual, _u8p), _p(cu, _i32p), cu.shape[0] - 1, T, E,
+                                  _p(pair, _f32p), _p(mean, _f64p), _p(count, _i32p))
+    return pair[:T], mean, count
+
+
+def magnitude_stability(y, row_is_visual):
+    """App. B.  Returns row_norm [M] f32 and stats [2,4] f64 = (mu, sigma, CV, V) for text, vision."""
+    y, vis = _f32(y), _u8(row_is_visual)
+    M, d = y.shape
+    norms = np.empty(max(M, 1), np.float32)
+    stats = np.zeros((2, 4), np.float64)
+    lib().orc_magnitude_stability(_p(y, _f32p), M, d, _p(vis, _u8p), _p(norms, _f32p), _p(stats, _f64p))
+    return norms[:M], stats
+
+
+def row_cosine(a, b):
+    a, b = _f32(a), _f32(b)
+    assert a.shape == b.shape
+    out = np.empty(max(a.shape[0], 1), np.float32)
+    lib().orc_row_cosine(_p(a, _f32p), _p(b, _f32p), a.shape[0], a.shape[1], _p(out, _f32p))
+    return out[:a.shape[0]]
+
+
+def gate_cosine(gates, m):
+    """App. C closed form from each token's K gates in descending order."""
+    gates = _f32(gates)
+    T, K = gates.shape
+    out = np.empty(max(T, 1), np.float32)
+    if lib().orc_gate_cosine(_p(gates, _f32p), T, K, int(m), _p(out, _f32p)) != 0:
+        raise ValueError("orc_gate_cosine: bad arguments")
+    return out[:T]

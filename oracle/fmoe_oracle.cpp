@@ -586,6 +586,110 @@ int orc_token_outputs(const float* x, const int32_t* tokens, int n_tokens, int d
   return 0;
 }
 
+// -------- analysis statistics of the paper (diagnostics; they feed no decision of the layer).
+//
+// Fig. 1: routing similarity of adjacent tokens -- Eq.8 on a two-token window: the cosine of the
+// routing-probability rows of tokens t and t+1.  A pair counts when both tokens lie in the same
+// sequence and have the same modality (the paper compares consecutive visual tokens with
+// consecutive text tokens; pairs across a modality switch belong to neither curve).
+// pair_sim [T]: cosine for the pair (t, t+1), -2 where t starts no pair; mean/count [2]: index 0
+// text pairs, 1 visual pairs (mean 0 when there is no pair).
+int orc_adjacent_similarity(const float* probs, const uint8_t* is_visual, const int32_t* cu_seqlens, int B,
+                            int T, int E, float* pair_sim, double* mean, int32_t* count) {
+  double sum[2] = {0.0, 0.0};
+  count[0] = count[1] = 0;
+  for (int t = 0; t < T; ++t) pair_sim[t] = -2.0f;
+  for (int b = 0; b < B; ++b) {
+    for (int t = cu_seqlens[b]; t + 1 < cu_seqlens[b + 1]; ++t) {
+      const int m = is_visual[t] ? 1 : 0;
+      if ((is_visual[t + 1] ? 1 : 0) != m) continue;
+      const float* a = probs + (size_t)t * E;
+      const float* c = a + E;
+      double ab = 0.0, aa = 0.0, cc = 0.0;
+      for (int e = 0; e < E; ++e) {
+        ab += (double)a[e] * c[e];
+        aa += (double)a[e] * a[e];
+        cc += (double)c[e] * c[e];
+      }
+      const double den = std::sqrt(aa) * std::sqrt(cc);
+      const double cosv = den > 0.0 ? ab / den : 0.0;
+      pair_sim[t] = (float)cosv;
+      sum[m] += cosv;
+      count[m] += 1;
+    }
+  }
+  for (int m = 0; m < 2; ++m) mean[m] = count[m] ? sum[m] / count[m] : 0.0;
+  return 0;
+}
+
+// App. B: magnitude stability of expert outputs.  l = Euclidean norm of every expert-output row
+// (before the gate-weighted fusion); per modality mu, sigma (population), CV = sigma/mu and
+// V = 1/(1+CV).  row_is_visual [M]; row_norm [M] out (nullable); stats [2][4] = {mu, sigma, CV, V}
+// for text (0) and vision (1); a modality without rows, or with mu = 0, reports CV = 0, V = 1.
+int orc_magnitude_stability(const float* y, int M, int d, const uint8_t* row_is_visual, float* row_norm,
+                            double* stats) {
+  double s1[2] = {0, 0}, s2[2] = {0, 0};
+  long n[2] = {0, 0};
+  std::vector<double> norms(M);
+  for (int r = 0; r < M; ++r) {
+    double q = 0.0;
+    for (int c = 0; c < d; ++c) q += (double)y[(size_t)r * d + c] * y[(size_t)r * d + c];
+    norms[r] = std::sqrt(q);
+    if (row_norm) row_norm[r] = (float)norms[r];
+    const int m = row_is_visual[r] ? 1 : 0;
+    s1[m] += norms[r];
+    n[m] += 1;
+  }
+  for (int m = 0; m < 2; ++m) {
+    const double mu = n[m] ? s1[m] / n[m] : 0.0;
+    for (int r = 0; r < M; ++r)
+      if ((row_is_visual[r] ? 1 : 0) == m) s2[m] += (norms[r] - mu) * (norms[r] - mu);
+    const double sigma = n[m] ? std::sqrt(s2[m] / n[m]) : 0.0;
+    const double cv = mu > 0.0 ? sigma / mu : 0.0;
+    stats[m * 4 + 0] = mu;
+    stats[m * 4 + 1] = sigma;
+    stats[m * 4 + 2] = cv;
+    stats[m * 4 + 3] = 1.0 / (1.0 + cv);
+  }
+  return 0;
+}
+
+// cosine of the angle between corresponding rows of two [n,d] tensors (the measured angle between
+// the layer output with K experts and with m experts, App. C); 0 where a row is all zero.
+int orc_row_cosine(const float* a, const float* b, int n, int d, float* out) {
+  for (int r = 0; r < n; ++r) {
+    double ab = 0.0, aa = 0.0, bb = 0.0;
+    for (int c = 0; c < d; ++c) {
+      const double u = a[(size_t)r * d + c], v = b[(size_t)r * d + c];
+      ab += u * v;
+      aa += u * u;
+      bb += v * v;
+    }
+    const double den = std::sqrt(aa) * std::sqrt(bb);
+    out[r] = (float)(den > 0.0 ? ab / den : 0.0);
+  }
+  return 0;
+}
+
+// App. C: the angle predicted for orthonormal expert outputs, cos(theta) = sqrt(sum_{i<=m} a_i^2 /
+// sum_{i<=K} a_i^2), from a token's K gates in descending order (a common scale cancels, so the
+// gates may be normalised or not); rows whose first K entries are not all positive report 0.
+int orc_gate_cosine(const float* gates, int T, int K, int m, float* out) {
+  if (m < 0 || m > K) return -1;
+  for (int t = 0; t < T; ++t) {
+    double top = 0.0, all = 0.0;
+    bool ok = K > 0;
+    for (int i = 0; i < K; ++i) {
+      const double a = gates[(size_t)t * K + i];
+      if (!(a > 0.0)) ok = false;
+      all += a * a;
+      if (i < m) top += a * a;
+    }
+    out[t] = ok ? (float)std::sqrt(top / all) : 0.0f;
+  }
+  return 0;
+}
+
 int orc_num_threads(void) {
   int n = 1;
 #ifdef _OPENMP

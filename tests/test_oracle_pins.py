@@ -614,3 +614,80 @@ def test_gamma_hat_against_the_papers_table():
             assert abs(g - 0.065) < 5e-4 and abs(g - printed) > 0.01
         else:
             assert abs(g - printed) < 0.005
+
+
+# ---------------------------------------------------------------- analysis statistics (diagnostics)
+def test_adjacent_similarity_pairs_modalities_and_boundaries():
+    # Fig. 1 statistic: hand-made rows with known angles
+    a, b = [0.6, 0.8, 0.0], [0.8, 0.6, 0.0]                 # cos = 0.96
+    e0, e1 = [1.0, 0.0, 0.0], [0.0, 1.0, 0.0]               # orthogonal
+    probs = np.array([a, b, b, e0, e1, e1, a, a], np.float32)
+    vis = np.array([1, 1, 1, 0, 0, 0, 0, 1], np.uint8)      # tokens 0-2 visual, 3-6 text, 7 visual
+    cu = np.array([0, 6, 8], np.int32)                      # second sequence: tokens 6, 7
+    pair, mean, count = oracle.adjacent_similarity(probs, vis, cu)
+    #   (0,1) visual .96   (1,2) visual 1   (2,3) switch   (3,4) text 0   (4,5) text 1
+    #   (5,6) sequence boundary   (6,7) switch   7: last token
+    assert np.allclose(pair, [0.96, 1.0, -2, 0.0, 1.0, -2, -2, -2], atol=1e-6)
+    assert list(count) == [2, 2]
+    assert abs(mean[1] - 0.98) < 1e-6 and abs(mean[0] - 0.5) < 1e-6
+
+
+def test_adjacent_similarity_equals_exact_window_similarity_of_two_token_windows():
+    # Eq.8 with W = 2 is the cosine of the two rows: the pruning code's exact mode, written
+    # independently, must give the same numbers on windows (0,1), (2,3), ...
+    rng = np.random.default_rng(21)
+    probs = rng.random((40, 12)).astype(np.float32)
+    probs /= probs.sum(1, keepdims=True)
+    vis = np.ones(40, np.uint8)
+    cu = np.array([0, 40], np.int32)
+    pair, mean, count = oracle.adjacent_similarity(probs, vis, cu)
+    _, _, scores = oracle.prune(probs, vis, cu, 0.5, 2, sim_mode=1)
+    assert count[1] == 39 and count[0] == 0
+    assert np.abs(pair[0:40:2] - scores).max() <= 2e-6
+    assert abs(mean[1] - pair[:39].astype(np.float64).mean()) < 1e-7   # pair_sim is the fp32 rounding
+
+
+def test_magnitude_stability_closed_forms():
+    # App. B: V = 1/(1+CV); norms {1,3} in equal numbers: mu 2, sigma 1, CV 1/2, V 2/3
+    y = np.zeros((6, 4), np.float32)
+    y[0, 0], y[1, 1] = 1.0, -1.0
+    y[2, :2], y[3, 2] = [0.0, 3.0], 3.0
+    y[4], y[5] = [3.0, 4.0, 0.0, 0.0], [0.0, 0.0, -5.0, 0.0]          # text rows, both of norm 5
+    row_vis = np.array([1, 1, 1, 1, 0, 0], np.uint8)
+    norms, st = oracle.magnitude_stability(y, row_vis)
+    assert np.allclose(norms, [1, 1, 3, 3, 5, 5])
+    assert np.allclose(st[1], [2.0, 1.0, 0.5, 2.0 / 3.0])
+    assert np.allclose(st[0], [5.0, 0.0, 0.0, 1.0])                    # equal norms: perfectly stable
+    _, st2 = oracle.magnitude_stability(7.5 * y, row_vis)              # CV is scale-free
+    assert np.allclose(st2[:, 2:], st[:, 2:]) and np.allclose(st2[:, 0], 7.5 * st[:, 0])
+    _, st3 = oracle.magnitude_stability(y[:4], row_vis[:4])            # no text rows at all
+    assert np.allclose(st3[0], [0, 0, 0, 1])
+
+
+def test_row_cosine_known_angles():
+    a = np.array([[1, 0, 0], [1, 0, 0], [2, 0, 0], [0, 0, 0], [1, 2, 3]], np.float32)
+    b = np.array([[0.5, np.sqrt(0.75), 0], [-3, 0, 0], [0, 5, 0], [1, 1, 1], [10, 20, 30]], np.float32)
+    assert np.allclose(oracle.row_cosine(a, b), [0.5, -1.0, 0.0, 0.0, 1.0], atol=1e-6)
+
+
+def test_gate_cosine_is_the_angle_between_full_and_reduced_outputs():
+    # App. C: with orthonormal expert outputs p_i, y = sum_{i<=K} a_i p_i and y' = sum_{i<=m} a'_i p_i
+    # (a' renormalised over the first m) enclose the angle with cos = sqrt(sum_m a^2 / sum_K a^2)
+    rng = np.random.default_rng(22)
+    T, K, m = 50, 8, 3
+    g = np.sort(rng.random((T, K)).astype(np.float32) + 0.01, axis=1)[:, ::-1]
+    g = (g / g.sum(1, keepdims=True)).astype(np.float32)
+    pvec = np.eye(K, 16)                                              # orthonormal expert outputs
+    y_full = g.astype(np.float64) @ pvec
+    a_red = g[:, :m].astype(np.float64) / g[:, :m].astype(np.float64).sum(1, keepdims=True)
+    y_red = a_red @ pvec[:m]
+    measured = oracle.row_cosine(y_full, y_red)
+    closed = oracle.gate_cosine(g, m)
+    assert np.abs(measured - closed).max() <= 2e-6
+    assert (closed >= np.sqrt(m / K) - 1e-6).all()                     # the lower bound
+    assert np.allclose(oracle.gate_cosine(np.full((3, K), 1.0 / K, np.float32), m), np.sqrt(m / K))
+    assert np.allclose(oracle.gate_cosine(g, K), 1.0)
+    assert np.allclose(oracle.gate_cosine(5.0 * g, m), closed, atol=1e-6)   # a common scale cancels
+    bad = g.copy()
+    bad[0, 5] = 0.0                                                    # fewer than K active experts
+    assert oracle.gate_cosine(bad, m)[0] == 0.0
