@@ -201,6 +201,45 @@ int fmoe_profile_slots(void);
 const char* fmoe_profile_name(int slot);
 int fmoe_profile_read(fmoe_ctx* ctx, float* ms);
 
+/* ---- Diagnostics: the paper's analysis statistics on the layer's tensors.  They feed no decision
+ * of the layer.  All pointers are device pointers unless marked [host]; nothing is allocated and
+ * the host is not synchronised; results are reproducible run to run (fixed reduction orders).
+ *
+ * fmoe_adjacent_similarity -- routing similarity of adjacent tokens (Fig. 1; Eq.8 on a two-token
+ * window): pair_sim[t] = cosine of the routing-probability rows probs[t] and probs[t+1] ([T,E] fp32,
+ * E = the context's n_experts) when t and t+1 lie in the same sequence of cu_seqlens [B+1] and have
+ * the same modality in is_visual [T]; -2 where t starts no such pair (pair_sim [T], out).
+ * mean [2] / count [2] (out): average and number of the pairs, index 0 text, 1 vision (mean 0
+ * without pairs).
+ *
+ * fmoe_magnitude_stability -- magnitude stability of expert outputs (App. B): row_norm[r] =
+ * Euclidean norm of row r of y [M, d_model] (the routed experts' outputs before the gate-weighted
+ * sum, as fmoe_expert_ffn writes them; context dtype), for the first M rows or *M_dev of them when
+ * M_dev is not NULL (a device count such as expert_offsets + E).  The modality of row r is that of
+ * the token is_visual[kept_idx[perm_src[r]]] (kept_idx NULL: is_visual[perm_src[r]]).  stats [2][4]
+ * (out) = mean, population standard deviation, CV = sigma/mean and V = 1/(1+CV) of the norms of
+ * text rows (index 0) and vision rows (index 1); a modality without rows reports 0, 0, 0, 1.
+ * row_norm [M] is an output and the scratch of the call.
+ *
+ * fmoe_row_cosine -- out[r] = cosine between row r of a and of b ([n, d_model], context dtype; 0
+ * where a row is all zero), e.g. the measured angle between the layer outputs with K and with m
+ * active experts (App. C).  n_dev as above.
+ *
+ * fmoe_gate_cosine -- the angle App. C predicts for orthonormal expert outputs: out[t] =
+ * sqrt(sum_{i<m} g_i^2 / sum_{i<K} g_i^2) from gates [T,K] fp32, each row a token's K gates in
+ * descending order (fmoe_route's topk_gate for tokens routed with K experts; a common scale
+ * cancels); 0 for rows with fewer than K positive gates.  FMOE_ERR_INVALID_ARG unless 0 <= m <= K. */
+int fmoe_adjacent_similarity(fmoe_ctx* ctx, const float* probs, const uint8_t* is_visual,
+                             const int32_t* cu_seqlens, int32_t B, int32_t T, float* pair_sim, float* mean,
+                             int32_t* count, void* stream);
+int fmoe_magnitude_stability(fmoe_ctx* ctx, const void* y, int32_t M, const int32_t* M_dev,
+                             const int32_t* perm_src, const int32_t* kept_idx, const uint8_t* is_visual,
+                             float* row_norm, float* stats, void* stream);
+int fmoe_row_cosine(fmoe_ctx* ctx, const void* a, const void* b, int32_t n, const int32_t* n_dev, float* out,
+                    void* stream);
+int fmoe_gate_cosine(fmoe_ctx* ctx, const float* gates, int32_t T, int32_t K, int32_t m, float* out,
+                     void* stream);
+
 #ifdef __cplusplus
 }
 #endif

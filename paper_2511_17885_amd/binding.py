@@ -20,7 +20,8 @@ FMOE_F32, FMOE_BF16 = 0, 1
 EXPORTS = ["fmoe_version", "fmoe_last_error", "fmoe_create", "fmoe_destroy", "fmoe_set_topk",
            "fmoe_set_weights", "fmoe_workspace_bytes", "fmoe_route", "fmoe_prune", "fmoe_permute",
            "fmoe_expert_ffn", "fmoe_combine", "fmoe_layer_forward", "fmoe_profile_enable",
-           "fmoe_profile_slots", "fmoe_profile_name", "fmoe_profile_read"]
+           "fmoe_profile_slots", "fmoe_profile_name", "fmoe_profile_read", "fmoe_adjacent_similarity",
+           "fmoe_magnitude_stability", "fmoe_row_cosine", "fmoe_gate_cosine"]
 
 
 class FmoeConfig(C.Structure):
@@ -70,6 +71,10 @@ def load():
     lib.fmoe_combine.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.fmoe_layer_forward.argtypes = [vp, C.POINTER(FmoePruneParams), vp, vp, vp, i32, i32, vp,
                                        C.c_int, vp, vp, vp, vp, vp, sz, vp]
+    lib.fmoe_adjacent_similarity.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.fmoe_magnitude_stability.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.fmoe_row_cosine.argtypes = [vp, vp, vp, i32, vp, vp, vp]
+    lib.fmoe_gate_cosine.argtypes = [vp, vp, i32, i32, i32, vp, vp]
     lib.fmoe_profile_enable.argtypes = [vp, C.c_int]
     lib.fmoe_profile_slots.argtypes = []
     lib.fmoe_profile_name.argtypes = [C.c_int]
@@ -255,6 +260,36 @@ class FMoE:
                                            _ptr(new_cu), _ptr(is_visual_out), _ptr(ws), ws.numel(),
                                            _stream()))
         return out, kept_idx, new_cu, is_visual_out
+
+
+    # ---- diagnostics
+    def adjacent_similarity(self, probs, is_visual, cu_seqlens):
+        """Returns (pair_sim [T], mean [2], count [2]); index 0 text pairs, 1 vision pairs."""
+        T, B = probs.shape[0], cu_seqlens.shape[0] - 1
+        pair, mean, count = self._f32(max(T, 1)), self._f32(2), self._i32(2)
+        _check(self.lib.fmoe_adjacent_similarity(self._ctx, _ptr(probs), _ptr(is_visual), _ptr(cu_seqlens), B, T,
+                                                 _ptr(pair), _ptr(mean), _ptr(count), _stream()))
+        return pair[:T], mean, count
+
+    def magnitude_stability(self, y, M, perm_src, kept_idx, is_visual, M_dev=None):
+        """Returns (row_norm [M], stats [2,4] = mean, sigma, CV, V for text / vision rows)."""
+        norms, stats = self._f32(max(M, 1)), self._f32(2, 4)
+        _check(self.lib.fmoe_magnitude_stability(self._ctx, _ptr(y), M, _ptr(M_dev), _ptr(perm_src),
+                                                 _ptr(kept_idx), _ptr(is_visual), _ptr(norms), _ptr(stats),
+                                                 _stream()))
+        return norms[:M], stats
+
+    def row_cosine(self, a, b, n=None, n_dev=None):
+        n = a.shape[0] if n is None else n
+        out = self._f32(max(n, 1))
+        _check(self.lib.fmoe_row_cosine(self._ctx, _ptr(a), _ptr(b), n, _ptr(n_dev), _ptr(out), _stream()))
+        return out[:n]
+
+    def gate_cosine(self, gates, m):
+        T, K = gates.shape
+        out = self._f32(max(T, 1))
+        _check(self.lib.fmoe_gate_cosine(self._ctx, _ptr(gates), T, K, int(m), _ptr(out), _stream()))
+        return out[:T]
 
 
 def kept_visual_lens(visual_lens, retention):

@@ -25,6 +25,7 @@ SOURCES = {
     "permute.hip": [],
     "ffn.hip": [],
     "combine.hip": [],
+    "diag.hip": [],
 }
 
 

@@ -424,6 +424,56 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
                         out, s);
 }
 
+int fmoe_adjacent_similarity(fmoe_ctx* ctx, const float* probs, const uint8_t* is_visual,
+                             const int32_t* cu_seqlens, int32_t B, int32_t T, float* pair_sim, float* mean,
+                             int32_t* count, void* stream) {
+  int rc = check_ctx(ctx, false);
+  if (rc != FMOE_OK) return rc;
+  if ((rc = check_tokens(T)) != FMOE_OK) return rc;
+  if (B < 0) return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_adjacent_similarity: B %d is negative", B);
+  if (!cu_seqlens || !mean || !count)
+    return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_adjacent_similarity: cu_seqlens / mean / count is NULL");
+  if (T > 0 && (!probs || !is_visual || !pair_sim))
+    return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_adjacent_similarity: probs / is_visual / pair_sim is NULL");
+  if (T > 0 && B == 0)
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_adjacent_similarity: %d tokens but no sequence", T);
+  return launch_adjacent_similarity(probs, is_visual, cu_seqlens, B, T, ctx->cfg.n_experts, pair_sim, mean,
+                                    count, static_cast<hipStream_t>(stream));
+}
+
+int fmoe_magnitude_stability(fmoe_ctx* ctx, const void* y, int32_t M, const int32_t* M_dev,
+                             const int32_t* perm_src, const int32_t* kept_idx, const uint8_t* is_visual,
+                             float* row_norm, float* stats, void* stream) {
+  int rc = check_ctx(ctx, false);
+  if (rc != FMOE_OK) return rc;
+  if (M < 0) return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_magnitude_stability: M %d is negative", M);
+  if (!stats) return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_magnitude_stability: stats is NULL");
+  if (M > 0 && (!y || !perm_src || !is_visual || !row_norm))
+    return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_magnitude_stability: y / perm_src / is_visual / row_norm is NULL");
+  return launch_magnitude_stability(ctx, y, M, M_dev, perm_src, kept_idx, is_visual, row_norm, stats,
+                                    static_cast<hipStream_t>(stream));
+}
+
+int fmoe_row_cosine(fmoe_ctx* ctx, const void* a, const void* b, int32_t n, const int32_t* n_dev, float* out,
+                    void* stream) {
+  int rc = check_ctx(ctx, false);
+  if (rc != FMOE_OK) return rc;
+  if ((rc = check_tokens(n)) != FMOE_OK) return rc;
+  if (n > 0 && (!a || !b || !out)) return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_row_cosine: a / b / out is NULL");
+  return launch_row_cosine(ctx, a, b, n, n_dev, out, static_cast<hipStream_t>(stream));
+}
+
+int fmoe_gate_cosine(fmoe_ctx* ctx, const float* gates, int32_t T, int32_t K, int32_t m, float* out,
+                     void* stream) {
+  int rc = check_ctx(ctx, false);
+  if (rc != FMOE_OK) return rc;
+  if ((rc = check_tokens(T)) != FMOE_OK) return rc;
+  if (K < 1 || m < 0 || m > K)
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_gate_cosine: need K >= 1 and 0 <= m <= K (K %d, m %d)", K, m);
+  if (T > 0 && (!gates || !out)) return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_gate_cosine: gates / out is NULL");
+  return launch_gate_cosine(gates, T, K, m, out, static_cast<hipStream_t>(stream));
+}
+
 int fmoe_profile_slots(void) { return SLOT_COUNT; }
 
 const char* fmoe_profile_name(int slot) {

@@ -149,6 +149,16 @@ int launch_combine(const fmoe_ctx* ctx, const void* y, const void* y_shared, con
                    const float* topk_gate, const int32_t* kept_idx, int n_cap, const int32_t* n_dev,
                    const void* residual, void* out, hipStream_t stream);
 
+// ---- diagnostics (diag.hip)
+int launch_adjacent_similarity(const float* probs, const uint8_t* is_visual, const int32_t* cu, int B, int T,
+                               int E, float* pair_sim, float* mean, int32_t* count, hipStream_t stream);
+int launch_magnitude_stability(const fmoe_ctx* ctx, const void* y, int M, const int32_t* M_dev,
+                               const int32_t* perm_src, const int32_t* kept_idx, const uint8_t* is_visual,
+                               float* row_norm, float* stats, hipStream_t stream);
+int launch_row_cosine(const fmoe_ctx* ctx, const void* a, const void* b, int n, const int32_t* n_dev, float* out,
+                      hipStream_t stream);
+int launch_gate_cosine(const float* gates, int T, int K, int m, float* out, hipStream_t stream);
+
 // ---- device helpers
 #if defined(__HIPCC__)
 typedef uint16_t bf16_t;  // raw bfloat16 bits

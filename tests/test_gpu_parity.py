@@ -527,3 +527,52 @@ def test_stack_ragged_bf16_prune_point():
     assert same >= 0.98                                   # kept sets agree but for flipped near-ties
     if np.array_equal(kept, ref_kept):
         assert max_rel_err(out, ref) <= 3 * TOL[W.BF16]
+
+
+# ---------------------------------------------------------------- diagnostics (the paper's analysis statistics)
+DIAG_TOL = 2e-5   # fp32 arithmetic inside a row against the fp64 oracle; the statistics are O(1)
+
+
+@pytest.mark.parametrize("seed,kw", [SMALL[1], SMALL[3], SMALL[8]])
+def test_adjacent_similarity(seed, kw):
+    wl = _wl(seed, kw)
+    o_probs, _, _ = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias,
+                                 wl.k_text, wl.k_visual)
+    o_pair, o_mean, o_count = oracle.adjacent_similarity(o_probs, wl.is_visual, wl.cu_seqlens)
+    m = make_layer(wl)
+    pair, mean, count = m.adjacent_similarity(dev(o_probs), dev(wl.is_visual), dev(wl.cu_seqlens))
+    pair, mean, count = host(pair), host(mean), host(count)
+    assert np.array_equal(count, o_count)
+    assert np.array_equal(pair < -1.5, o_pair < -1.5)            # the same pairs exist
+    assert np.abs(pair - o_pair).max() <= DIAG_TOL
+    assert np.abs(mean - o_mean).max() <= DIAG_TOL
+
+
+@pytest.mark.parametrize("seed,kw", [SMALL[1], SMALL[3], SMALL[5], SMALL[8]])
+def test_magnitude_stability_and_output_angle(seed, kw):
+    wl = _wl(seed, kw)
+    o = _oracle(wl)
+    n, M = len(o["kept_idx"]), int(o["expert_offsets"][-1])
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    # App. B on the routed experts' outputs of the layer (the oracle's rows, rounded to the dtype)
+    y_rows = dev(np.asarray(o["y"], np.float32), torch_dtype(wl))
+    row_vis = wl.is_visual[o["kept_idx"][o["perm_src"]]]
+    o_norm, o_stats = oracle.magnitude_stability(host(y_rows), row_vis)
+    m_dev = dev(np.array([M], np.int32))
+    norms, stats = m.magnitude_stability(y_rows, M, dev(o["perm_src"]), dev(o["kept_idx"]), vis, M_dev=m_dev)
+    assert np.abs(host(norms) - o_norm).max() <= DIAG_TOL * max(1.0, o_norm.max())
+    assert np.abs(host(stats) - o_stats).max() <= DIAG_TOL * max(1.0, np.abs(o_stats).max())
+    # App. C: angle between the layer output with all K experts and with the reduced k_visual
+    full = _oracle(wl, k_visual=wl.k_text)
+    assert np.array_equal(full["kept_idx"], o["kept_idx"])       # pruning does not look at k
+    a, b = dev(full["out"], torch_dtype(wl)), dev(o["out"], torch_dtype(wl))
+    cos = host(m.row_cosine(a, b))
+    assert np.abs(cos - oracle.row_cosine(host(a), host(b))).max() <= DIAG_TOL
+    # and the closed form from the K gates
+    K = wl.k_text
+    o_probs, _, o_gate = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias, K, K)
+    pred = host(m.gate_cosine(dev(o_gate), wl.k_visual))
+    assert np.abs(pred - oracle.gate_cosine(o_gate, wl.k_visual)).max() <= DIAG_TOL
+    if wl.k_visual > 0:
+        assert (pred >= np.sqrt(wl.k_visual / K) - 1e-5).all()
