@@ -109,6 +109,37 @@ def route(x, is_visual, router_w, router_bias, k_text, k_visual, renormalize=Tru
     return (probs, idx, gate, p64) if shadow else (probs, idx, gate)
 
 
+TOPK, RANDOMK, MINK = 0, 1, 2
+
+
+def splitmix64_nth(seed: int, n: int) -> int:
+    lib().orc_splitmix64_nth.restype = C.c_uint64
+    lib().orc_splitmix64_nth.argtypes = [C.c_uint64, C.c_uint64]
+    return int(lib().orc_splitmix64_nth(seed, n))
+
+
+def route_select(x, is_visual, router_w, router_bias, k_text, k_visual, strategy, k_base, seed=0,
+                 renormalize=True):
+    """Routing with the selection-strategy ablation of Sec. 4 (TopK / RandomK / MinK among the token's
+    top-k_base experts, for tokens whose k is below k_base).  Returns probs, topk_idx, topk_gate."""
+    x, router_w, router_bias, is_visual = _f32(x), _f32(router_w), _f32(router_bias), _u8(is_visual)
+    T, d = x.shape
+    E = router_w.shape[0]
+    Kmax = max(k_text, k_visual)
+    probs = np.empty((T, E), np.float32)
+    idx = np.empty((T, Kmax), np.int32)
+    gate = np.empty((T, Kmax), np.float32)
+    fn = lib().orc_route_select
+    fn.argtypes = [_f32p, _u8p, C.c_int, C.c_int, C.c_int, _f32p, _f32p, C.c_int, C.c_int, C.c_int, C.c_int,
+                   C.c_int, C.c_uint64, _f32p, _i32p, _f32p]
+    rc = fn(_p(x, _f32p), _p(is_visual, _u8p), T, d, E, _p(router_w, _f32p), _p(router_bias, _f32p),
+            int(k_text), int(k_visual), int(bool(renormalize)), int(strategy), int(k_base), int(seed),
+            _p(probs, _f32p), _p(idx, _i32p), _p(gate, _f32p))
+    if rc != 0:
+        raise ValueError("orc_route_select: bad arguments")
+    return probs, idx, gate
+
+
 def gamma_hat(retain_ratio, window, stages=3):
     """App. D: the merge rate at which merging alone reaches the token budget,
     (1/beta - 1)/(W - 1) with the per-stage retain ratio beta = r^(1/stages)."""
@@ -117,7 +148,7 @@ def gamma_hat(retain_ratio, window, stages=3):
 
 
 def prune(probs, is_visual, cu_seqlens, retention, window, alpha=1.0, gamma=0.0, sim_mode=0,
-          attn=None, x=None, is_bf16=False):
+          attn=None, x=None, is_bf16=False, merge_mean=False):
     """Sec. 3.2 (scores, budget, merge, drop).  Returns kept_idx [T'] i32 ascending, new_cu_seqlens
     [B+1], window scores C (sequences concatenated); with x [T,d] also is_merged [T'] u8 and the
     layer input after merging x_merged [T',d] (needed when gamma > 0)."""
@@ -137,7 +168,7 @@ def prune(probs, is_visual, cu_seqlens, retention, window, alpha=1.0, gamma=0.0,
                         C.c_float(retention), int(window), C.c_float(alpha), C.c_float(gamma),
                         int(sim_mode), _p(attn, _f32p), _p(kept, _i32p), _p(new_cu, _i32p),
                         _p(scores, _f32p), _p(x, _f32p), int(d), int(bool(is_bf16)),
-                        _p(is_merged, _u8p), _p(x_merged, _f32p))
+                        _p(is_merged, _u8p), _p(x_merged, _f32p), int(bool(merge_mean)))
     if n < 0:
         raise ValueError("orc_prune: bad arguments")
     if x is None:
@@ -224,21 +255,31 @@ def token_outputs(x, tokens, topk_idx, topk_gate, w, is_bf16, add_residual=False
 
 def layer_forward(x, is_visual, cu_seqlens, w, *, k_text, k_visual, is_bf16, retention=1.0,
                   window=1, alpha=1.0, gamma=0.0, sim_mode=0, attn=None, add_residual=False,
-                  renormalize=True, do_prune=True, ffn=True):
+                  renormalize=True, do_prune=True, ffn=True, merge_mean=False, strategy=TOPK, k_base=0,
+                  seed=0):
     """The whole path: route -> prune -> permute -> experts -> combine (the steps chained, nothing
-    else).  Returns a dict with every intermediate."""
+    else).  Returns a dict with every intermediate.  strategy / k_base / seed: the selection-strategy
+    ablation (route_select); merge_mean: plain mean instead of MLERP for merged tokens."""
     T = x.shape[0]
     E = w.router_w.shape[0]
     d = x.shape[1]
-    probs, idx, gate = route(x, is_visual, w.router_w, w.router_bias, k_text, k_visual, renormalize)
+
+    def _route(xx, vv):
+        if strategy == TOPK:
+            return route(xx, vv, w.router_w, w.router_bias, k_text, k_visual, renormalize)
+        return route_select(xx, vv, w.router_w, w.router_bias, k_text, k_visual, strategy, k_base, seed,
+                            renormalize)
+
+    probs, idx, gate = _route(x, is_visual)
     if do_prune and retention < 1.0 and gamma > 0.0:
         # window merging changes the layer input: the kept rows are gathered (merged windows replaced by
         # their merged token), every kept token is routed again on that tensor (only the merged ones can
         # come out differently) and the rest of the layer runs on it
         kept, new_cu, scores, is_merged, x_m = prune(probs, is_visual, cu_seqlens, retention, window,
-                                                     alpha, gamma, sim_mode, attn, x=x, is_bf16=is_bf16)
+                                                     alpha, gamma, sim_mode, attn, x=x, is_bf16=is_bf16,
+                                                     merge_mean=merge_mean)
         vis_m = _u8(is_visual)[kept]
-        probs_m, idx_m, gate_m = route(x_m, vis_m, w.router_w, w.router_bias, k_text, k_visual, renormalize)
+        probs_m, idx_m, gate_m = _route(x_m, vis_m)
         ident = np.arange(kept.shape[0], dtype=np.int32)
         offs, perm, inv = permute(idx_m, ident, E)
         res = dict(probs=probs, topk_idx=idx_m, topk_gate=gate_m, kept_idx=kept, new_cu_seqlens=new_cu,

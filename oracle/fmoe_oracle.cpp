@@ -182,6 +182,50 @@ void topk_gates_row(const float* P, int E, int k, int Kmax, int renorm,
   for (int s = 0; s < k; ++s) gate[s] = renorm ? (P[idx[s]] / den) : P[idx[s]];
 }
 
+// ---------------------------------------------------------------- selection-strategy ablation (Sec. 4)
+// Which k of a token's K_base highest-probability experts stay active when its activation is
+// reduced: the k highest (TopK, strategy 0 -- the method itself), k chosen at random (RandomK, 1)
+// or the k lowest (MinK, 2).  The candidates are the token's top-K_base list in the order of
+// topk_gates_row; the kept experts are listed in that same order and the gates are renormalised
+// over them (Eq.5).  The paper does not say how RandomK draws; here every candidate position r of
+// token t gets the 64-bit key splitmix64(seed, n = 16 t + r + 1) (the n-th output of the SplitMix64
+// generator started at `seed`) and the k smallest keys win (equal keys: lower position).
+uint64_t splitmix64_nth(uint64_t seed, uint64_t n) {
+  uint64_t z = seed + n * 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+void select_gates_row(const float* P, int E, int k, int k_base, int strategy, uint64_t seed, int t,
+                      int Kmax, int renorm, int32_t* idx, float* gate) {
+  std::vector<int32_t> cand(k_base);
+  std::vector<float> unused(k_base);
+  topk_gates_row(P, E, k_base, k_base, 0, cand.data(), unused.data());
+  std::vector<int> keep;   // kept candidate positions, ascending
+  if (strategy == 2) {
+    for (int r = k_base - k; r < k_base; ++r) keep.push_back(r);
+  } else if (strategy == 1) {
+    std::vector<uint64_t> key(k_base);
+    for (int r = 0; r < k_base; ++r) key[r] = splitmix64_nth(seed, (uint64_t)t * 16u + (uint64_t)r + 1u);
+    for (int r = 0; r < k_base; ++r) {
+      int rank = 0;
+      for (int q = 0; q < k_base; ++q)
+        if (key[q] < key[r] || (key[q] == key[r] && q < r)) ++rank;
+      if (rank < k) keep.push_back(r);
+    }
+  } else {
+    for (int r = 0; r < k; ++r) keep.push_back(r);
+  }
+  for (int s = 0; s < Kmax; ++s) { idx[s] = -1; gate[s] = 0.0f; }
+  float den = 0.0f;
+  for (int s = 0; s < k; ++s) {
+    idx[s] = cand[keep[s]];
+    den = den + P[idx[s]];
+  }
+  for (int s = 0; s < k; ++s) gate[s] = renorm ? (P[idx[s]] / den) : P[idx[s]];
+}
+
 // ---------------------------------------------------------------- Eq.8-10: window similarity
 float norm_canon(const float* v, int E) { return std::sqrt(dot_canon(v, v, E)); }
 
@@ -275,6 +319,32 @@ int orc_route(const float* x, const uint8_t* is_visual, int T, int d, int E,
   return 0;
 }
 
+// -------- the same with a selection strategy for tokens whose k is below k_base (see
+// select_gates_row); tokens with k >= k_base are routed as in orc_route.
+uint64_t orc_splitmix64_nth(uint64_t seed, uint64_t n) { return splitmix64_nth(seed, n); }
+
+int orc_route_select(const float* x, const uint8_t* is_visual, int T, int d, int E,
+                     const float* router_w, const float* router_bias, int k_text, int k_visual,
+                     int renormalize, int strategy, int k_base, uint64_t seed, float* probs,
+                     int32_t* topk_idx, float* topk_gate) {
+  if (k_text < 0 || k_visual < 0 || k_text > E || k_visual > E) return -1;
+  if (strategy < 0 || strategy > 2 || k_base < 0 || k_base > E || k_base > 16) return -1;
+  int Kmax = std::max(k_text, k_visual);
+#pragma omp parallel for schedule(dynamic, 16)
+  for (int t = 0; t < T; ++t) {
+    const float* P = probs + (size_t)t * E;
+    route_probs_row(x + (size_t)t * d, d, E, router_w, router_bias, probs + (size_t)t * E);
+    int k = is_visual[t] ? k_visual : k_text;
+    if (Kmax == 0) continue;
+    if (k < k_base)
+      select_gates_row(P, E, k, k_base, strategy, seed, t, Kmax, renormalize, topk_idx + (size_t)t * Kmax,
+                       topk_gate + (size_t)t * Kmax);
+    else
+      topk_gates_row(P, E, k, Kmax, renormalize, topk_idx + (size_t)t * Kmax, topk_gate + (size_t)t * Kmax);
+  }
+  return 0;
+}
+
 // -------- Sec. 3.2.2: number of windows per sequence, n = ceil(N_v / W); returns the total.
 int orc_window_counts(const uint8_t* is_visual, const int32_t* cu_seqlens, int B, int W,
                       int32_t* win_offsets /*[B+1]*/) {
@@ -320,7 +390,7 @@ int orc_window_counts(const uint8_t* is_visual, const int32_t* cu_seqlens, int B
 int orc_prune(const float* probs, const uint8_t* is_visual, const int32_t* cu_seqlens, int B,
               int T, int E, float retention, int W, float alpha, float gamma, int sim_mode,
               const float* attn, int32_t* kept_idx, int32_t* new_cu_seqlens, float* scores_out,
-              const float* x_in, int d, int is_bf16, uint8_t* is_merged, float* x_merged) {
+              const float* x_in, int d, int is_bf16, uint8_t* is_merged, float* x_merged, int merge_mean) {
   if (W < 1 || !(retention > 0.0f) || retention > 1.0f || !(gamma >= 0.0f) || gamma >= 1.0f) return -1;
   if (gamma > 0.0f && !x_in) return -1;
   if (cu_seqlens[B] != T) return -1;
@@ -436,7 +506,8 @@ int orc_prune(const float* probs, const uint8_t* is_visual, const int32_t* cu_se
             mn += mean[c] * mean[c];
           }
           mn = std::sqrt(mn);
-          const double scale = mn > 0.0 ? max_norm / mn : 0.0;
+          // merge_mean: the plain arithmetic mean the paper compares MLERP with (merge-method ablation)
+          const double scale = merge_mean ? 1.0 : (mn > 0.0 ? max_norm / mn : 0.0);
           for (int c = 0; c < d; ++c) out[c] = round_store(mean[c] * scale, is_bf16);
         }
       }

@@ -691,3 +691,86 @@ def test_gate_cosine_is_the_angle_between_full_and_reduced_outputs():
     bad = g.copy()
     bad[0, 5] = 0.0                                                    # fewer than K active experts
     assert oracle.gate_cosine(bad, m)[0] == 0.0
+
+
+# ---------------------------------------------------------------- ablation switches (Sec. 4)
+def _sel_case(seed=31, T=400, d=32, E=24):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    w = (0.3 * rng.standard_normal((E, d))).astype(np.float32)
+    vis = (rng.random(T) < 0.8).astype(np.uint8)
+    return x, w, vis
+
+
+def test_splitmix64_published_outputs():
+    # the first outputs of SplitMix64 started at 0 (the generator's reference test values)
+    assert oracle.splitmix64_nth(0, 1) == 0xE220A8397B1DCDAF
+    assert oracle.splitmix64_nth(0, 2) == 0x6E789E6AA1B965F4
+    assert oracle.splitmix64_nth(0, 3) == 0x06C45D188009454F
+
+
+def test_selection_mink_and_topk_against_argsort():
+    x, w, vis = _sel_case()
+    K, kv = 8, 3
+    probs, idx_top, gate_top = oracle.route(x, vis, w, None, K, kv)
+    p2, idx0, gate0 = oracle.route_select(x, vis, w, None, K, kv, oracle.TOPK, K)
+    assert np.array_equal(p2, probs) and np.array_equal(idx0, idx_top) and np.array_equal(gate0, gate_top)
+    _, idx_min, gate_min = oracle.route_select(x, vis, w, None, K, kv, oracle.MINK, K)
+    for t in range(x.shape[0]):
+        order = np.lexsort((np.arange(probs.shape[1]), -probs[t].astype(np.float64)))[:K]
+        if vis[t]:
+            want = order[K - kv:]                                  # the kv lowest of the top K, in list order
+            assert list(idx_min[t, :kv]) == list(want) and (idx_min[t, kv:] == -1).all()
+            g = probs[t, want].astype(np.float64)
+            assert np.abs(gate_min[t, :kv] - g / g.sum()).max() <= 1e-6
+        else:
+            assert list(idx_min[t]) == list(order)                 # full-k tokens are left alone
+            assert np.array_equal(gate_min[t], gate_top[t])
+
+
+def test_selection_randomk_is_a_seeded_uniform_subset_of_the_top_k():
+    x, w, vis = _sel_case(T=3000)
+    K, kv = 8, 4
+    probs, idx_full, _ = oracle.route(x, vis, w, None, K, K)
+    _, idx_a, gate_a = oracle.route_select(x, vis, w, None, K, kv, oracle.RANDOMK, K, seed=5)
+    _, idx_b, _ = oracle.route_select(x, vis, w, None, K, kv, oracle.RANDOMK, K, seed=5)
+    _, idx_c, _ = oracle.route_select(x, vis, w, None, K, kv, oracle.RANDOMK, K, seed=6)
+    assert np.array_equal(idx_a, idx_b) and not np.array_equal(idx_a, idx_c)
+    hist = np.zeros(K)
+    nv = 0
+    for t in np.nonzero(vis)[0]:
+        pos = [list(idx_full[t]).index(e) for e in idx_a[t, :kv]]
+        assert pos == sorted(pos) and len(set(pos)) == kv           # a subset, in list order
+        assert (idx_a[t, kv:] == -1).all()
+        assert abs(gate_a[t, :kv].sum() - 1.0) < 1e-5
+        hist[pos] += 1
+        nv += 1
+    # every candidate position is kept with probability kv/K: binomial, 5 sigma
+    sigma = np.sqrt(nv * 0.5 * 0.5)
+    assert np.abs(hist - nv * kv / K).max() < 5 * sigma
+    # the keys are the documented ones: recompute one token's choice from the generator
+    t = int(np.nonzero(vis)[0][7])
+    keys = [oracle.splitmix64_nth(5, 16 * t + r + 1) for r in range(K)]
+    chosen = sorted(sorted(range(K), key=lambda r: (keys[r], r))[:kv])
+    assert list(idx_a[t, :kv]) == [idx_full[t][r] for r in chosen]
+
+
+def test_merge_mean_mode_is_the_numpy_mean():
+    rng = np.random.default_rng(33)
+    Nv, Wn, E, d = 60, 3, 10, 16
+    probs = rng.random((Nv, E)).astype(np.float32)
+    probs /= probs.sum(1, keepdims=True)
+    x = rng.standard_normal((Nv, d)).astype(np.float32)
+    vis = np.ones(Nv, np.uint8)
+    cu = np.array([0, Nv], np.int32)
+    kept, _, _, is_m, xm = oracle.prune(probs, vis, cu, 0.5, Wn, gamma=0.2, x=x, merge_mean=True)
+    kept2, _, _, is_m2, xm2 = oracle.prune(probs, vis, cu, 0.5, Wn, gamma=0.2, x=x)
+    assert np.array_equal(kept, kept2) and np.array_equal(is_m, is_m2) and is_m.sum() == 6
+    for p in np.nonzero(is_m)[0]:
+        t = kept[p]
+        rows = x[t:t + Wn].astype(np.float64)
+        assert np.abs(xm[p] - rows.mean(0)).max() <= 1e-6
+        # MLERP: the same direction, rescaled to the largest token norm of the window
+        scale = np.linalg.norm(rows, axis=1).max() / np.linalg.norm(rows.mean(0))
+        assert np.abs(xm2[p] - rows.mean(0) * scale).max() <= 1e-5
+    assert np.array_equal(xm[is_m == 0], xm2[is_m == 0])
