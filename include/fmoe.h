@@ -68,6 +68,8 @@ typedef struct {
   float gamma;        /* merge rate in [0,1) (Eq.14): at most floor(eta*gamma) windows merged; 0 = off */
   int32_t sim_mode;   /* 0: similarity to the window mean (Eq.9-10); 1: all pairs (Eq.8)   */
   int32_t prune_mode; /* 0: none; 1 or 2: prune between routing and the experts            */
+  int32_t merge_mode; /* merged token: 0 = MLERP (Eq.16-18: mean rescaled to the largest token norm),
+                         1 = plain mean (the alternative of the merge-method ablation, Sec. 4)  */
 } fmoe_prune_params;
 
 typedef struct fmoe_ctx fmoe_ctx;
@@ -86,6 +88,17 @@ void fmoe_destroy(fmoe_ctx* ctx);
 /* Change K and K_v of an existing context (the per-layer l_v switch of Sec. 3.1).
  * Kmax = max(k_text,k_visual) changes with it, and so do the [*,Kmax] tensor shapes. */
 int fmoe_set_topk(fmoe_ctx* ctx, int32_t k_text, int32_t k_visual);
+
+/* Expert selection strategy for tokens with reduced activation (the ablation of Sec. 4, "Selection
+ * Strategy for Expert Activation Reduction").  A token whose k (k_text or k_visual) is below k_base
+ * first lists its k_base highest-probability experts (ties: lower index) and keeps k of them:
+ * strategy 0 = the k highest (TopK: the method itself, the default), 1 = k at random (RandomK),
+ * 2 = the k lowest (MinK).  The kept experts stay in list order and the gates are renormalised over
+ * them (Eq.5).  RandomK is reproducible: candidate position r of token t (its index in the routed
+ * batch) gets the key SplitMix64(seed) output number 16 t + r + 1 and the k smallest keys win.
+ * Tokens with k >= k_base are routed as usual.  Affects fmoe_route and fmoe_layer_forward.
+ * FMOE_ERR_INVALID_ARG unless 0 <= strategy <= 2 and 0 <= k_base <= min(E, 16). */
+int fmoe_set_selection(fmoe_ctx* ctx, int32_t strategy, int32_t k_base, uint64_t seed);
 
 /* Register the layer's weights (Eq.1, Eq.4).  Pointers are borrowed until the next call or
  * fmoe_destroy.  router_w [E,H] dtype; router_bias [E] fp32 or NULL (added to the logits

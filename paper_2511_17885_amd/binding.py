@@ -17,7 +17,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfmoe.so")
 
 FMOE_F32, FMOE_BF16 = 0, 1
+TOPK, RANDOMK, MINK = 0, 1, 2   # fmoe_set_selection strategies
 EXPORTS = ["fmoe_version", "fmoe_last_error", "fmoe_create", "fmoe_destroy", "fmoe_set_topk",
+           "fmoe_set_selection",
            "fmoe_set_weights", "fmoe_workspace_bytes", "fmoe_route", "fmoe_prune", "fmoe_permute",
            "fmoe_expert_ffn", "fmoe_combine", "fmoe_layer_forward", "fmoe_profile_enable",
            "fmoe_profile_slots", "fmoe_profile_name", "fmoe_profile_read", "fmoe_adjacent_similarity",
@@ -32,7 +34,8 @@ class FmoeConfig(C.Structure):
 
 class FmoePruneParams(C.Structure):
     _fields_ = [("retention", C.c_float), ("window", C.c_int32), ("alpha", C.c_float),
-                ("gamma", C.c_float), ("sim_mode", C.c_int32), ("prune_mode", C.c_int32)]
+                ("gamma", C.c_float), ("sim_mode", C.c_int32), ("prune_mode", C.c_int32),
+                ("merge_mode", C.c_int32)]
 
 
 class FmoeError(RuntimeError):
@@ -60,6 +63,7 @@ def load():
     lib.fmoe_destroy.argtypes = [vp]
     lib.fmoe_destroy.restype = None
     lib.fmoe_set_topk.argtypes = [vp, i32, i32]
+    lib.fmoe_set_selection.argtypes = [vp, i32, i32, C.c_uint64]
     lib.fmoe_set_weights.argtypes = [vp] + [vp] * 8 + [vp]
     lib.fmoe_workspace_bytes.argtypes = [vp, i32, i32]
     lib.fmoe_workspace_bytes.restype = sz
@@ -104,9 +108,9 @@ def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def prune_params(retention=1.0, window=1, alpha=1.0, gamma=0.0, sim_mode=0, prune_mode=1):
+def prune_params(retention=1.0, window=1, alpha=1.0, gamma=0.0, sim_mode=0, prune_mode=1, merge_mode=0):
     return FmoePruneParams(float(retention), int(window), float(alpha), float(gamma), int(sim_mode),
-                           int(prune_mode))
+                           int(prune_mode), int(merge_mode))
 
 
 class FMoE:
@@ -151,6 +155,10 @@ class FMoE:
     def set_topk(self, k_text, k_visual):
         _check(self.lib.fmoe_set_topk(self._ctx, k_text, k_visual))
         self.cfg.k_text, self.cfg.k_visual = k_text, k_visual
+
+    def set_selection(self, strategy, k_base, seed=0):
+        """Selection-strategy ablation: TOPK / RANDOMK / MINK among the token's top-k_base experts."""
+        _check(self.lib.fmoe_set_selection(self._ctx, int(strategy), int(k_base), int(seed)))
 
     def set_weights(self, router_w, router_bias, w_gate, w_up, w_down, ws_gate=None, ws_up=None,
                     ws_down=None):

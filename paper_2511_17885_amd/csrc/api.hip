@@ -58,6 +58,8 @@ int check_prune(const fmoe_prune_params* p) {
     return fmoe_fail(FMOE_ERR_UNSUPPORTED, "prune: window %d > %d", p->window, FMOE_MAX_WINDOW);
   if (!(p->alpha >= 0.0f) || p->alpha > 1.0f)
     return fmoe_fail(FMOE_ERR_INVALID_ARG, "prune: alpha %g outside [0,1]", (double)p->alpha);
+  if (p->merge_mode != 0 && p->merge_mode != 1)
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "prune: merge_mode %d is neither 0 (MLERP) nor 1 (mean)", p->merge_mode);
   if (!(p->gamma >= 0.0f) || p->gamma >= 1.0f)
     return fmoe_fail(FMOE_ERR_INVALID_ARG, "prune: gamma %g outside [0,1)", (double)p->gamma);
   if (p->sim_mode != 0 && p->sim_mode != 1)
@@ -180,6 +182,19 @@ int fmoe_set_topk(fmoe_ctx* ctx, int32_t k_text, int32_t k_visual) {
   if (rc != FMOE_OK) return rc;
   ctx->cfg = c;
   ctx->kmax = k_text > k_visual ? k_text : k_visual;
+  return FMOE_OK;
+}
+
+int fmoe_set_selection(fmoe_ctx* ctx, int32_t strategy, int32_t k_base, uint64_t seed) {
+  int rc = check_ctx(ctx, false);
+  if (rc != FMOE_OK) return rc;
+  if (strategy < 0 || strategy > 2)
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_set_selection: strategy %d is not 0 (TopK), 1 (RandomK) or 2 (MinK)", strategy);
+  if (k_base < 0 || k_base > ctx->cfg.n_experts || k_base > FMOE_MAX_TOPK)
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_set_selection: k_base %d outside [0, min(E, %d)]", k_base, FMOE_MAX_TOPK);
+  ctx->sel_strategy = strategy;
+  ctx->sel_k_base = k_base;
+  ctx->sel_seed = seed;
   return FMOE_OK;
 }
 

@@ -37,6 +37,8 @@ struct fmoe_ctx {
   // bf16 contexts: private copies of the expert weights in matrix-core operand order (ffn.hip)
   void *pk_gate_up, *pk_down, *pk_sgate_up, *pk_sdown;
   bool weights_set;
+  int sel_strategy, sel_k_base;   // selection-strategy ablation (fmoe_set_selection); 0 = off
+  unsigned long long sel_seed;
   fmoe_prof* prof;           // nullptr unless fmoe_profile_enable was called
 };
 

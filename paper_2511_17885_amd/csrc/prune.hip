@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256) void merge_gather_kernel(
     const T* __restrict__ x, int d, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ n_dev,
     const uint8_t* __restrict__ is_merged, const int32_t* __restrict__ cu, int B, int Ttot, int W,
     const int32_t* __restrict__ vis_ord, const int32_t* __restrict__ vis_tok,
-    const int32_t* __restrict__ seq_nv, T* __restrict__ x_merged) {
+    const int32_t* __restrict__ seq_nv, T* __restrict__ x_merged, int mean_only) {
   __shared__ double red[4];
   const int p = blockIdx.x;
   if (p >= *n_dev) return;
@@ -398,7 +398,8 @@ __global__ __launch_bounds__(256) void merge_gather_kernel(
     mean_sq += mu * mu;
   }
   const double mean_norm = sqrt(block_sum_f64(mean_sq, red));
-  const double scale = mean_norm > 0.0 ? sqrt(max_row_sq) / mean_norm : 0.0;
+  // mean_only: the plain mean of the merge-method ablation instead of MLERP's rescaling
+  const double scale = mean_only ? 1.0 : (mean_norm > 0.0 ? sqrt(max_row_sq) / mean_norm : 0.0);
   for (int c = threadIdx.x; c < d; c += 256) dst[c] = from_f64<T>(column_mean(c) * scale);
 }
 
@@ -825,12 +826,12 @@ int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* 
       hipLaunchKernelGGL(merge_gather_kernel<bf16_t>, dim3(T), dim3(256), 0, stream,
                          static_cast<const bf16_t*>(x_in), ctx->cfg.d_model, kept_idx, new_cu_seqlens + B,
                          is_merged, cu_seqlens, B, T, pp->window, vis_ord, vis_tok, seq_nv,
-                         static_cast<bf16_t*>(x_merged));
+                         static_cast<bf16_t*>(x_merged), pp->merge_mode);
     else
       hipLaunchKernelGGL(merge_gather_kernel<float>, dim3(T), dim3(256), 0, stream,
                          static_cast<const float*>(x_in), ctx->cfg.d_model, kept_idx, new_cu_seqlens + B,
                          is_merged, cu_seqlens, B, T, pp->window, vis_ord, vis_tok, seq_nv,
-                         static_cast<float*>(x_merged));
+                         static_cast<float*>(x_merged), pp->merge_mode);
   }
   FMOE_HIP_CHECK(hipGetLastError());
   return FMOE_OK;

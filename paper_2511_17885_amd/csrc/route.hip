@@ -175,12 +175,29 @@ template <> struct XStage<float> {
   }
 };
 
-template <typename XT, int NB, int PF>
+// Selection-strategy ablation (Sec. 4): which k of a token's k_base highest experts stay active.
+struct fmoe_selection {
+  int strategy;              // 0 the k highest (the method), 1 k at random, 2 the k lowest
+  int k_base;
+  unsigned long long seed;
+};
+
+// n-th output of the SplitMix64 generator started at `seed` (the key of a candidate position for
+// the random strategy)
+__device__ __forceinline__ unsigned long long splitmix64_nth(unsigned long long seed, unsigned long long n) {
+  unsigned long long z = seed + n * 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+template <typename XT, int NB, int PF, bool SEL>
 __global__ __launch_bounds__(256) void route_kernel(
     const XT* __restrict__ x, const fx4_t* __restrict__ wp, const float* __restrict__ bias,
     const uint8_t* __restrict__ is_visual, int T, int d, int E, int Eb, int G, int nch, int k_text,
     int k_visual, int Kmax, int renorm, float* __restrict__ probs, int32_t* __restrict__ topk_idx,
-    float* __restrict__ topk_gate, int route_blocks, fmoe_ordinals_job ord, const int32_t* __restrict__ T_dev) {
+    float* __restrict__ topk_gate, int route_blocks, fmoe_ordinals_job ord, const int32_t* __restrict__ T_dev,
+    fmoe_selection selp) {
   __shared__ __align__(16) float xs[64 * RS];
   __shared__ float zs[TOKB][4 * NB * 16 + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -342,14 +359,19 @@ __global__ __launch_bounds__(256) void route_kernel(
       sel[tq][i] = -1;
     }
   }
-  for (int r = 0; r < Kmax; ++r) {
+  // with a selection strategy a token with k < k_base first lists its k_base candidates
+  int kc[TQ];
+#pragma unroll
+  for (int tq = 0; tq < TQ; ++tq) kc[tq] = (SEL && kk[tq] < selp.k_base) ? selp.k_base : kk[tq];
+  const int rounds = (SEL && selp.k_base > Kmax) ? selp.k_base : Kmax;
+  for (int r = 0; r < rounds; ++r) {
 #pragma unroll
     for (int tq = 0; tq < TQ; ++tq) {
       float v = work[tq][0];
 #pragma unroll
       for (int i = 1; i < NB; ++i) v = (work[tq][i] > v) ? work[tq][i] : v;
       const float m = wave_max_all(v);
-      const bool active = r < kk[tq];
+      const bool active = r < kc[tq];
       bool taken = false;
 #pragma unroll
       for (int i = 0; i < NB; ++i) {   // lowest expert index first: register i holds experts 64i..64i+63
@@ -362,6 +384,48 @@ __global__ __launch_bounds__(256) void route_kernel(
         taken = taken || (eq != 0ull);
       }
       den[tq] = den[tq] + (active ? m : 0.0f);   // list order, sequential (Eq.5)
+    }
+  }
+  if constexpr (SEL) {
+    // random strategy: lane 16q + r holds the key of candidate position r of the wavefront's q-th
+    // token; a position is kept when fewer than k keys of its token are smaller (ties: lower position)
+    unsigned long long random_masks = 0ull;
+    if (selp.strategy == 1) {
+      const int q = lane >> 4, r = lane & 15;
+      const int tq_t = q == 0 ? tt[0] : (q == 1 ? tt[1] : (q == 2 ? tt[2] : tt[3]));
+      const int tq_k = q == 0 ? kk[0] : (q == 1 ? kk[1] : (q == 2 ? kk[2] : kk[3]));
+      const unsigned long long key = splitmix64_nth(selp.seed, (unsigned long long)tq_t * 16ull + (unsigned long long)r + 1ull);
+      int rank = 0;
+      for (int o = 0; o < 16; ++o) {
+        const int src = (lane & 48) + o;
+        const unsigned int lo = (unsigned int)__shfl((int)(unsigned int)key, src, 64);
+        const unsigned int hi = (unsigned int)__shfl((int)(unsigned int)(key >> 32), src, 64);
+        const unsigned long long ok = ((unsigned long long)hi << 32) | lo;
+        rank += (o < selp.k_base && (ok < key || (ok == key && o < r))) ? 1 : 0;
+      }
+      random_masks = __ballot(r < selp.k_base && rank < tq_k);
+    }
+#pragma unroll
+    for (int tq = 0; tq < TQ; ++tq) {
+      if (kk[tq] >= selp.k_base) continue;   // not reduced: the list stands (uniform over the wavefront)
+      const int k = kk[tq];
+      unsigned int mask;   // kept candidate positions
+      if (selp.strategy == 1) mask = (unsigned int)(random_masks >> (16 * tq)) & 0xffffu;
+      else if (selp.strategy == 2) mask = ((1u << k) - 1u) << (selp.k_base - k);
+      else mask = (1u << k) - 1u;
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const int p = sel[tq][i];
+        if (p >= 0) sel[tq][i] = ((mask >> p) & 1u) ? __popc(mask & ((1u << p) - 1u)) : -1;
+      }
+      float d2 = 0.0f;   // Eq.5 over the kept experts, in list order
+      for (int sl = 0; sl < k; ++sl) {
+        float v = -1.0f;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) v = (sel[tq][i] == sl) ? P[tq][i] : v;
+        d2 = d2 + wave_max_all(v);
+      }
+      den[tq] = d2;
     }
   }
 #pragma unroll
@@ -392,10 +456,17 @@ int launch_route_t(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual,
   const int grid = (T + TOKB - 1) / TOKB;
   fmoe_prof_scope prof(ctx, SLOT_ROUTE, stream);
   const int riders = ord.cu != nullptr ? ord.B : 0;
-  hipLaunchKernelGGL((route_kernel<XT, NB, PF>), dim3(grid + riders), dim3(256), 0, stream,
-                     static_cast<const XT*>(x), reinterpret_cast<const fx4_t*>(ctx->router_wp),
-                     ctx->router_bias, is_visual, T, d, E, Eb, G, nch, ctx->cfg.k_text, ctx->cfg.k_visual,
-                     ctx->kmax, ctx->cfg.renormalize, probs, topk_idx, topk_gate, grid, ord, T_dev);
+  const fmoe_selection selp{ctx->sel_strategy, ctx->sel_k_base, ctx->sel_seed};
+  if (ctx->sel_strategy != 0)
+    hipLaunchKernelGGL((route_kernel<XT, NB, PF, true>), dim3(grid + riders), dim3(256), 0, stream,
+                       static_cast<const XT*>(x), reinterpret_cast<const fx4_t*>(ctx->router_wp),
+                       ctx->router_bias, is_visual, T, d, E, Eb, G, nch, ctx->cfg.k_text, ctx->cfg.k_visual,
+                       ctx->kmax, ctx->cfg.renormalize, probs, topk_idx, topk_gate, grid, ord, T_dev, selp);
+  else
+    hipLaunchKernelGGL((route_kernel<XT, NB, PF, false>), dim3(grid + riders), dim3(256), 0, stream,
+                       static_cast<const XT*>(x), reinterpret_cast<const fx4_t*>(ctx->router_wp),
+                       ctx->router_bias, is_visual, T, d, E, Eb, G, nch, ctx->cfg.k_text, ctx->cfg.k_visual,
+                       ctx->kmax, ctx->cfg.renormalize, probs, topk_idx, topk_gate, grid, ord, T_dev, selp);
   FMOE_HIP_CHECK(hipGetLastError());
   return FMOE_OK;
 }

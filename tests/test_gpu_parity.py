@@ -576,3 +576,68 @@ def test_magnitude_stability_and_output_angle(seed, kw):
     assert np.abs(pred - oracle.gate_cosine(o_gate, wl.k_visual)).max() <= DIAG_TOL
     if wl.k_visual > 0:
         assert (pred >= np.sqrt(wl.k_visual / K) - 1e-5).all()
+
+
+# ---------------------------------------------------------------- ablation switches (Sec. 4)
+@pytest.mark.parametrize("strategy", [binding.TOPK, binding.RANDOMK, binding.MINK])
+@pytest.mark.parametrize("seed,kw", [SMALL[1], SMALL[3], SMALL[4], SMALL[5], SMALL[8]])
+def test_route_selection_strategies(seed, kw, strategy):
+    wl = _wl(seed, kw)
+    k_base = wl.k_text
+    m = make_layer(wl)
+    m.set_selection(strategy, k_base, seed=1234 + seed)
+    x, vis, cu = inputs(wl)
+    probs, idx, gate = m.route(x, vis)
+    o_probs, o_idx, o_gate = oracle.route_select(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias,
+                                                 wl.k_text, wl.k_visual, strategy, k_base, seed=1234 + seed)
+    assert np.array_equal(host(probs), o_probs)
+    assert np.array_equal(host(idx), o_idx)
+    assert np.abs(host(gate) - o_gate).max() <= 1e-6
+    if strategy != binding.TOPK and wl.k_visual > 0:
+        _, idx_top, _ = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias,
+                                     wl.k_text, wl.k_visual)
+        assert not np.array_equal(o_idx, idx_top)              # the switch does something
+
+
+def test_selection_k_base_above_kmax_and_text_reduction():
+    # reduce BOTH modalities (the "All" row of the modality ablation) from a candidate list longer
+    # than either k: k_base = 8 > Kmax = 4
+    wl = W.small_random(118, T_v=[70], T_t=[30], d=64, E=32, F=32, k_text=4, k_visual=2, retention=0.5,
+                        window=3, bias_std=1.0)
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    for strategy in (binding.RANDOMK, binding.MINK):
+        m.set_selection(strategy, 8, seed=9)
+        _, idx, gate = m.route(x, vis)
+        _, o_idx, o_gate = oracle.route_select(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias,
+                                               4, 2, strategy, 8, seed=9)
+        assert np.array_equal(host(idx), o_idx) and np.abs(host(gate) - o_gate).max() <= 1e-6
+    with pytest.raises(RuntimeError):
+        m.set_selection(3, 8)
+    with pytest.raises(RuntimeError):
+        m.set_selection(1, 33)
+
+
+@pytest.mark.parametrize("seed,kw", [SMALL[3], SMALL[8]])
+def test_layer_forward_ablation_switches(seed, kw):
+    # MinK selection + plain-mean merging through the whole layer
+    wl = _wl(seed, kw)
+    m = make_layer(wl)
+    m.set_selection(binding.MINK, wl.k_text)
+    x, vis, cu = inputs(wl)
+    o = _oracle(wl, add_residual=True, gamma=0.3, merge_mean=True, strategy=oracle.MINK, k_base=wl.k_text)
+    pp = binding.prune_params(retention=wl.retention, window=wl.window, gamma=0.3, merge_mode=1)
+    out, kept, new_cu, _ = m.layer_forward(x, vis, cu, pp, add_residual=True)
+    new_cu = host(new_cu)
+    n = int(new_cu[-1])
+    assert np.array_equal(new_cu, o["new_cu_seqlens"]) and np.array_equal(host(kept)[:n], o["kept_idx"])
+    assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
+    # mean mode alone, through fmoe_prune
+    o_probs, _, _ = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias,
+                                 wl.k_text, wl.k_visual)
+    o_kept, o_cu, _, o_mrg, o_xm = oracle.prune(o_probs, wl.is_visual, wl.cu_seqlens, wl.retention, wl.window,
+                                                gamma=0.3, x=wl.x, is_bf16=wl.dtype == W.BF16, merge_mean=True)
+    kept, new_cu, _, mrg, x_m = m.prune(pp, dev(o_probs), vis, cu, x=x)
+    n = int(host(new_cu)[-1])
+    assert np.array_equal(host(kept)[:n], o_kept) and np.array_equal(host(mrg)[:n], o_mrg)
+    _check_merged_rows(host(x_m)[:n], o_xm, o_mrg, wl.dtype)
