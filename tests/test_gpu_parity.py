@@ -440,6 +440,25 @@ def test_config3_full_activation_no_pruning_sampled():
     assert _check_config(wl, sample=32) == wl.T
 
 
+def test_config5_layer_full_size_ragged_sampled():
+    # one layer of config 5 at its real size: 8 packed sequences of 1152..6528 tokens (22k tokens here),
+    # d = 2048, 64 experts + 2 shared; the pruning layer's configuration (k 6/3, r = 0.5, W = 3)
+    wl = W.config5(n_layers=1)
+    lens = np.diff(wl.cu_seqlens)
+    nv = [int(wl.is_visual[s:e].sum()) for s, e in zip(wl.cu_seqlens[:-1], wl.cu_seqlens[1:])]
+    nt = [int(n - v) for n, v in zip(lens, nv)]
+    assert wl.B == 8 and wl.T > 16384                      # far beyond the single-workgroup dispatch path
+    assert _check_config(wl, sample=24) == binding.kept_count(nv, nt, wl.retention)
+
+
+def test_config5_layer_full_size_full_activation_sampled():
+    # the same layer as layers 0-1 run it: top-6 for every token, no pruning (~2900 rows per expert:
+    # the compute-bound end of the expert GEMM)
+    wl = W.config5(n_layers=1)
+    wl.k_visual, wl.retention = 6, 1.0
+    assert _check_config(wl, sample=24) == wl.T
+
+
 # ---------------------------------------------------------------- the ragged multi-layer stack
 def _oracle_stack(wl, schedule=None):
     """x <- x + MoE_l(x) layer by layer on the CPU; `schedule` = {layer: dict(retention, window, alpha,
