@@ -30,7 +30,7 @@ VALU_F32_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the dominant kernel on workload c2 from two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB; the factors are what a 256 MiB device copy reads on the
 # same counters) -- profiles/ffn_stream_c2_hbm_traffic.md.  Other workloads: not measured.
-MEASURED_TRAFFIC_BYTES = {"c2": int((85117.0 * 2.0 + 7617.4) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"c2": int((85963.6 * 2.0 + 7616.0) * 1024)}
 
 
 def main():
@@ -38,7 +38,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5_layer", "c5_layer_full"],
+                    help="c2 is the configuration the metric is quoted on; the others are context "
+                         "(c5_layer: one layer of the ragged 8-sequence batch with pruning, "
+                         "c5_layer_full: the same layer with top-6 for every token and no pruning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=30)
     ap.add_argument("--copy-calib", action="store_true",
@@ -54,7 +57,13 @@ def main():
     from paper_2511_17885_amd import binding, workloads as W
 
     torch.cuda.set_device(0)
-    wl = {"c1": W.config1, "c2": W.config2, "c3": W.config3, "c4": W.config4}[args.workload]()
+    def c5_layer_full():
+        w5 = W.config5(n_layers=1)
+        w5.k_visual, w5.retention, w5.name = 6, 1.0, w5.name + "_full_activation"
+        return w5
+
+    wl = {"c1": W.config1, "c2": W.config2, "c3": W.config3, "c4": W.config4,
+          "c5_layer": lambda: W.config5(n_layers=1), "c5_layer_full": c5_layer_full}[args.workload]()
     is_bf16 = wl.dtype == W.BF16
     td = torch.bfloat16 if is_bf16 else torch.float32
     es = 2 if is_bf16 else 4
