@@ -42,6 +42,8 @@ def main():
                     help="c2 is the configuration the metric is quoted on; the others are context "
                          "(c5_layer: one layer of the ragged 8-sequence batch with pruning, "
                          "c5_layer_full: the same layer with top-6 for every token and no pruning)")
+    ap.add_argument("--gamma", type=float, default=0.0,
+                    help="merge rate of Sec. 3.2.3 (context runs; the metric is quoted at 0, i.e. without merging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=30)
     ap.add_argument("--copy-calib", action="store_true",
@@ -81,7 +83,7 @@ def main():
     m.set_weights(dev(lw.router_w, td), dev(lw.router_bias), dev(lw.w_gate, td), dev(lw.w_up, td),
                   dev(lw.w_down, td), dev(lw.ws_gate, td), dev(lw.ws_up, td), dev(lw.ws_down, td))
     x, vis, cu = dev(wl.x, td), dev(wl.is_visual), dev(wl.cu_seqlens)
-    pp = binding.prune_params(retention=wl.retention, window=wl.window)
+    pp = binding.prune_params(retention=wl.retention, window=wl.window, gamma=args.gamma)
     T, B = wl.T, wl.B
     out = torch.empty((T, wl.d), dtype=td, device="cuda")
     kept = torch.empty(T, dtype=torch.int32, device="cuda")
@@ -181,7 +183,7 @@ def main():
         while passes == 0 or (time.time() - t0 < 10.0 and passes < 1000):   # about 10 s of CPU work
             oracle.layer_forward(wl.x, wl.is_visual, wl.cu_seqlens, lw, k_text=wl.k_text,
                                  k_visual=wl.k_visual, is_bf16=is_bf16, retention=wl.retention,
-                                 window=wl.window)
+                                 window=wl.window, gamma=args.gamma)
             passes += 1
         dt = time.time() - t0
         cpu = {"value": round(passes * T / dt, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
@@ -197,7 +199,8 @@ def main():
         "config": {"workload": wl.name, "tokens": T, "visual": n_vis, "d_model": d, "experts": E,
                    "d_ffn": F, "shared_experts": Ns, "k_text": wl.k_text, "k_visual": wl.k_visual,
                    "retention": wl.retention, "window": wl.window, "kept_tokens": n_kept,
-                   "routed_rows": M, "experts_touched": touched},
+                   "routed_rows": M, "experts_touched": touched,
+                   **({"gamma": args.gamma} if args.gamma > 0 else {})},
         "roofline": roofline, "cpu_baseline": cpu,
         "kernel_sum_us": round(sum(kms.values()) * 1e3, 2), "kernels": kernels,
     }

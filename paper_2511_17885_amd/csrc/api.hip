@@ -376,8 +376,11 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
     return fmoe_fail(FMOE_ERR_UNSUPPORTED, "fmoe_layer_forward: window merging (gamma > 0) is built for prune_mode 1 "
                      "(merge the layer input, route the kept tokens again)");
   const bool small = !merging && T > 0 && dispatch_small_fits(T, do_prune ? params->window : 1, do_prune);
+  // with merging the pruning decisions take the general kernels, but a small batch still gets its
+  // ordinals from the router's launch and its permutation from the single-workgroup kernel
+  const bool small_merge = merging && T > 0 && dispatch_small_fits(T, 1, false);
   fmoe_ordinals_job ord{};
-  if (small && do_prune)
+  if ((small && do_prune) || small_merge)
     ord = fmoe_ordinals_job{cu_seqlens, B, reinterpret_cast<int32_t*>(base + L.vis_ord),
                             reinterpret_cast<int32_t*>(base + L.vis_tok),
                             reinterpret_cast<int32_t*>(base + L.seq_nv)};
@@ -409,13 +412,18 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
     void* xm = base + L.x_merged;
     uint8_t* vis_m = is_visual_out ? is_visual_out : reinterpret_cast<uint8_t*>(base + L.vis_out);
     if ((rc = launch_prune(ctx, params, probs, is_visual, cu_seqlens, B, T, attn_importance, kept_idx,
-                           new_cu_seqlens, nullptr, vis_m, x, xm, nullptr, ws, L, s)) != FMOE_OK)
+                           new_cu_seqlens, nullptr, vis_m, x, xm, nullptr, ws, L, s, small_merge)) != FMOE_OK)
       return rc;
     n_dev = new_cu_seqlens + B;
     if ((rc = launch_route(ctx, xm, vis_m, T, nullptr, topk_idx, topk_gate, fmoe_ordinals_job{}, s, n_dev)) != FMOE_OK)
       return rc;
-    if ((rc = launch_permute(ctx, topk_idx, nullptr, T, n_dev, expert_offsets, perm_src, inv_perm, ws, L, true, s)) != FMOE_OK)
-      return rc;
+    if (small_merge)
+      rc = launch_prune_dispatch_small(ctx, params, false, nullptr, vis_m, new_cu_seqlens, B, T, nullptr, topk_idx,
+                                       kept_idx, new_cu_seqlens, nullptr, expert_offsets, perm_src, inv_perm,
+                                       ws, L, s, n_dev, false);
+    else
+      rc = launch_permute(ctx, topk_idx, nullptr, T, n_dev, expert_offsets, perm_src, inv_perm, ws, L, true, s);
+    if (rc != FMOE_OK) return rc;
     if ((rc = launch_expert_ffn(ctx, xm, nullptr, T, n_dev, expert_offsets, perm_src, y, y_shared, ws, L, true, s)) != FMOE_OK)
       return rc;
     return launch_combine(ctx, y, y_shared, inv_perm, topk_gate, nullptr, T, n_dev, add_residual ? xm : nullptr,

@@ -117,18 +117,20 @@ int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* 
                  const uint8_t* is_visual, const int32_t* cu_seqlens, int B, int T,
                  const float* attn, int32_t* kept_idx, int32_t* new_cu_seqlens, float* scores_out,
                  uint8_t* is_visual_out, const void* x_in, void* x_merged, uint8_t* is_merged_out,
-                 void* ws, const fmoe_ws_layout& L, hipStream_t stream);
+                 void* ws, const fmoe_ws_layout& L, hipStream_t stream, bool ordinals_ready = false);
 
 // Small batches: window scores, then ONE block for drop order, compaction, permutation by expert and
 // the grouped-GEMM tile lists (prune == false: every token is kept).  Expects the visual ordinals in
-// the workspace (fmoe_ordinals_job) when pruning.
+// the workspace (fmoe_ordinals_job) when pruning.  T_dev (nullable): device count of the tokens present;
+// write_kept = false: permutation and tile lists only (kept_idx / new_cu_seqlens / is_visual_out untouched).
 bool dispatch_small_fits(int T, int window, bool prune);
 int launch_prune_dispatch_small(const fmoe_ctx* ctx, const fmoe_prune_params* pp, bool prune,
                                 const float* probs, const uint8_t* is_visual, const int32_t* cu_seqlens,
                                 int B, int T, const float* attn, const int32_t* topk_idx,
                                 int32_t* kept_idx, int32_t* new_cu_seqlens, uint8_t* is_visual_out,
                                 int32_t* expert_offsets, int32_t* perm_src, int32_t* inv_perm, void* ws,
-                                const fmoe_ws_layout& L, hipStream_t stream);
+                                const fmoe_ws_layout& L, hipStream_t stream, const int32_t* T_dev = nullptr,
+                                bool write_kept = true);
 
 int launch_identity_kept(const uint8_t* is_visual, const int32_t* cu_seqlens, int B, int T,
                          int32_t* kept_idx, int32_t* new_cu_seqlens, uint8_t* is_visual_out,

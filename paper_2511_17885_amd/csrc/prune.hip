@@ -458,6 +458,8 @@ constexpr int SB_MAX_B = 512;                  // sequences whose bounds are cac
 
 struct SmallArgs {
   int prune;                       // 0: keep every token
+  const int32_t* T_dev;            // nullable: device count of the tokens present (<= T)
+  int write_kept;                  // 0: permutation only -- kept_idx / new_cu / is_visual_out stay untouched
   const uint8_t* is_visual;
   const int32_t* cu;
   int B, T, W;
@@ -503,7 +505,12 @@ __global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallA
   unsigned long long* mask = reinterpret_cast<unsigned long long*>(s_u);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int T = a.T, W = a.W, E = a.E, Kmax = a.Kmax, B = a.B;
+  const int W = a.W, E = a.E, Kmax = a.Kmax, B = a.B;
+  int T = a.T;
+  if (a.T_dev != nullptr) {
+    const int Td = *a.T_dev;
+    T = Td < T ? (Td > 0 ? Td : 0) : T;
+  }
 
   // ---- all global inputs of this thread's tokens
   int ord_r[SB_TP];
@@ -732,7 +739,7 @@ __global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallA
 
   // ---- outputs
   if (tid <= E) a.expert_offsets[tid] = s_off[tid];
-  for (int b = tid; b <= B; b += SB_THREADS) {   // new_cu[b] = kept tokens before the sequence start
+  for (int b = tid; b <= B && a.write_kept; b += SB_THREADS) {   // new_cu[b] = kept tokens before the sequence start
     const int c = clampi(cu[b], 0, T);
     int lo = 0, hi = n;
     while (lo < hi) {
@@ -745,8 +752,10 @@ __global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallA
   for (int k = 0; k < SB_TP; ++k) {
     const int p = pos_r[k];
     if (p >= 0) {
-      a.kept_idx[p] = k * SB_THREADS + tid;
-      if (a.is_visual_out != nullptr) a.is_visual_out[p] = vis_r[k];
+      if (a.write_kept) {
+        a.kept_idx[p] = k * SB_THREADS + tid;
+        if (a.is_visual_out != nullptr) a.is_visual_out[p] = vis_r[k];
+      }
 #pragma unroll
       for (int sl = 0; sl < KM; ++sl) {
         if (sl < Kmax) {
@@ -768,7 +777,7 @@ int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* 
                  const uint8_t* is_visual, const int32_t* cu_seqlens, int B, int T,
                  const float* attn, int32_t* kept_idx, int32_t* new_cu_seqlens, float* scores_out,
                  uint8_t* is_visual_out, const void* x_in, void* x_merged, uint8_t* is_merged_out,
-                 void* ws, const fmoe_ws_layout& L, hipStream_t stream) {
+                 void* ws, const fmoe_ws_layout& L, hipStream_t stream, bool ordinals_ready) {
   char* base = static_cast<char*>(ws);
   int32_t* vis_tok = reinterpret_cast<int32_t*>(base + L.vis_tok);
   int32_t* vis_ord = reinterpret_cast<int32_t*>(base + L.vis_ord);
@@ -787,7 +796,7 @@ int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* 
   if (T == 0 || B == 0) return launch_identity_kept(is_visual, cu_seqlens, B, T, kept_idx,
                                                     new_cu_seqlens, is_visual_out, stream);
 
-  {
+  if (!ordinals_ready) {
     fmoe_prof_scope prof(ctx, SLOT_ORDINALS, stream);
     hipLaunchKernelGGL(seq_ordinals_kernel, dim3(B), dim3(256), 0, stream, is_visual, cu_seqlens, T,
                        vis_ord, vis_tok, seq_nv);
@@ -857,7 +866,8 @@ int launch_prune_dispatch_small(const fmoe_ctx* ctx, const fmoe_prune_params* pp
                                 int B, int T, const float* attn, const int32_t* topk_idx,
                                 int32_t* kept_idx, int32_t* new_cu_seqlens, uint8_t* is_visual_out,
                                 int32_t* expert_offsets, int32_t* perm_src, int32_t* inv_perm, void* ws,
-                                const fmoe_ws_layout& L, hipStream_t stream) {
+                                const fmoe_ws_layout& L, hipStream_t stream, const int32_t* T_dev,
+                                bool write_kept) {
   char* base = static_cast<char*>(ws);
   int32_t* vis_tok = reinterpret_cast<int32_t*>(base + L.vis_tok);
   int32_t* vis_ord = reinterpret_cast<int32_t*>(base + L.vis_ord);
@@ -874,6 +884,8 @@ int launch_prune_dispatch_small(const fmoe_ctx* ctx, const fmoe_prune_params* pp
   }
   SmallArgs a;
   a.prune = prune ? 1 : 0;
+  a.T_dev = T_dev;
+  a.write_kept = write_kept ? 1 : 0;
   a.is_visual = is_visual;
   a.cu = cu_seqlens;
   a.B = B; a.T = T; a.W = prune ? pp->window : 1;
