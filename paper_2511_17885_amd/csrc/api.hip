@@ -377,10 +377,11 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
                      "(merge the layer input, route the kept tokens again)");
   const bool small = !merging && T > 0 && dispatch_small_fits(T, do_prune ? params->window : 1, do_prune);
   // with merging the pruning decisions take the general kernels, but a small batch still gets its
-  // ordinals from the router's launch and its permutation from the single-workgroup kernel
+  // permutation and tile lists from the single-workgroup kernel
   const bool small_merge = merging && T > 0 && dispatch_small_fits(T, 1, false);
+  // whenever the layer prunes, the router's launch carries the per-sequence ordinal blocks
   fmoe_ordinals_job ord{};
-  if ((small && do_prune) || small_merge)
+  if (do_prune && T > 0)
     ord = fmoe_ordinals_job{cu_seqlens, B, reinterpret_cast<int32_t*>(base + L.vis_ord),
                             reinterpret_cast<int32_t*>(base + L.vis_tok),
                             reinterpret_cast<int32_t*>(base + L.seq_nv)};
@@ -412,7 +413,7 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
     void* xm = base + L.x_merged;
     uint8_t* vis_m = is_visual_out ? is_visual_out : reinterpret_cast<uint8_t*>(base + L.vis_out);
     if ((rc = launch_prune(ctx, params, probs, is_visual, cu_seqlens, B, T, attn_importance, kept_idx,
-                           new_cu_seqlens, nullptr, vis_m, x, xm, nullptr, ws, L, s, small_merge)) != FMOE_OK)
+                           new_cu_seqlens, nullptr, vis_m, x, xm, nullptr, ws, L, s, true)) != FMOE_OK)
       return rc;
     n_dev = new_cu_seqlens + B;
     if ((rc = launch_route(ctx, xm, vis_m, T, nullptr, topk_idx, topk_gate, fmoe_ordinals_job{}, s, n_dev)) != FMOE_OK)
@@ -431,7 +432,7 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
   }
   if (do_prune) {
     rc = launch_prune(ctx, params, probs, is_visual, cu_seqlens, B, T, attn_importance, kept_idx,
-                      new_cu_seqlens, nullptr, is_visual_out, nullptr, nullptr, nullptr, ws, L, s);
+                      new_cu_seqlens, nullptr, is_visual_out, nullptr, nullptr, nullptr, ws, L, s, true);
     kept = kept_idx;
     n_dev = new_cu_seqlens + B;
   } else {

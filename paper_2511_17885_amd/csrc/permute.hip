@@ -82,22 +82,46 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(int n_cap, const int3
   const int nblk = (n + PB - 1) / PB;
   const int e = threadIdx.x;
   if (e < E) {
+    // SC blocks at a time: their counts are fetched together (independent loads), then turned into
+    // bases -- one memory latency per SC blocks instead of one per block
+    constexpr int SC = 16;
     int running = 0;
-    for (int b = 0; b < nblk; ++b) {
-      const int c = blk_count[(size_t)b * E + e];
-      blk_count[(size_t)b * E + e] = running;
-      running += c;
+    for (int b0 = 0; b0 < nblk; b0 += SC) {
+      int c[SC];
+#pragma unroll
+      for (int i = 0; i < SC; ++i) c[i] = (b0 + i < nblk) ? blk_count[(size_t)(b0 + i) * E + e] : 0;
+#pragma unroll
+      for (int i = 0; i < SC; ++i) {
+        if (b0 + i < nblk) blk_count[(size_t)(b0 + i) * E + e] = running;
+        running += c[i];
+      }
     }
     total[e] = running;
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int acc = 0;
-    for (int i = 0; i < E; ++i) {
-      expert_offsets[i] = acc;
-      acc += total[i];
+  if (threadIdx.x < 64) {   // exclusive scan of the (at most 256) totals by one wavefront, four per lane
+    const int lane = threadIdx.x;
+    int c[4], sum = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int i = 4 * lane + q;
+      c[q] = (i < E) ? total[i] : 0;
+      sum += c[q];
     }
-    expert_offsets[E] = acc;
+    int incl = sum;
+#pragma unroll
+    for (int sh = 1; sh < 64; sh <<= 1) {
+      const int o = __shfl_up(incl, sh, 64);
+      if (lane >= sh) incl += o;
+    }
+    int excl = incl - sum;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int i = 4 * lane + q;
+      if (i < E) expert_offsets[i] = excl;
+      excl += c[q];
+    }
+    if (lane == 63) expert_offsets[E] = incl;
   }
   if (build) {   // fused layer path: the grouped-GEMM work lists come out of the same scan
     __threadfence_block();

@@ -285,55 +285,102 @@ __global__ __launch_bounds__(1024) void compact_kernel(
     const int32_t* __restrict__ merged_before, uint8_t* __restrict__ is_merged_out) {
   // gamma > 0 (window merging): a merged window keeps exactly its first token; the others follow the
   // drop rule with the merged windows taken out of the walk and the budget merging left.
-  __shared__ int wave_tot[16];
+  // CQ chunks of 1024 tokens per round.  A token's decision is a chain of dependent loads (its visual
+  // ordinal -> its window's counters); the round issues each link of the chain for all its chunks
+  // before using any of them, so that the memory latencies overlap, and the sequence bounds are
+  // searched in LDS.  One barrier pair serves the round's prefix sums.
+  constexpr int CQ = 4;
+  constexpr int CB = 1024;   // sequences whose bounds are cached in LDS
+  __shared__ int wave_tot[CQ][16];
+  __shared__ int s_cu[CB + 1], s_nv[CB];
+  const bool cached = B <= CB;
+  if (cached) {
+    for (int b = threadIdx.x; b <= B; b += 1024) s_cu[b] = clampi(cu[b], 0, T);
+    for (int b = threadIdx.x; b < B; b += 1024) s_nv[b] = seq_nv[b];
+  }
+  __syncthreads();
+  const int32_t* cuc = cached ? s_cu : cu;   // clamping a clamped bound changes nothing
+  const int32_t* nvc = cached ? s_nv : seq_nv;
+  const bool merging = gamma > 0.0f;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int running = 0;
-  for (int base = 0; base < T; base += 1024) {
-    const int t = base + threadIdx.x;
-    bool keep = false, merged_tok = false;
-    if (t < T) {
-      const int ord = vis_ord[t];
-      if (ord < 0) {
-        keep = true;
-      } else {
-        const int b = find_seq(cu, B, t);
-        const int s = clampi(cu[b], 0, T);
-        const int nv = seq_nv[b];
-        if (!(gamma > 0.0f)) {
-          keep = (ord % W) < window_keep_lead(ord, nv, W, retention, precede[s + ord / W]);
-        } else if (win_merged[s + ord / W]) {
-          keep = merged_tok = (ord % W) == 0;
-        } else {
-          const int n = (nv + W - 1) / W;
-          const bool short_last = nv - (n - 1) * W < W;
-          const int L = short_last ? rank_c[s + n - 1] : n;
-          const fmoe_merge_plan p = merge_plan(nv, W, retention, gamma, L);
-          keep = (ord % W) < window_keep_lead_merge(ord, nv, W, precede[s + ord / W],
-                                                    merged_before[s + ord / W],
-                                                    win_merged[s + n - 1] != 0, p.u_rem);
+  for (int base = 0; base < T; base += CQ * 1024) {
+    int ord_q[CQ], s_q[CQ], nv_q[CQ], pc_q[CQ], wm_q[CQ], mb_q[CQ], rl_q[CQ], lm_q[CQ];
+#pragma unroll
+    for (int q = 0; q < CQ; ++q) {
+      const int t = base + q * 1024 + threadIdx.x;
+      ord_q[q] = (t < T) ? vis_ord[t] : -2;   // -2: past the end, -1: text
+    }
+#pragma unroll
+    for (int q = 0; q < CQ; ++q) {
+      const int t = base + q * 1024 + threadIdx.x;
+      s_q[q] = 0; nv_q[q] = 0; pc_q[q] = 0; wm_q[q] = 0; mb_q[q] = 0; rl_q[q] = 0; lm_q[q] = 0;
+      if (ord_q[q] >= 0) {
+        const int b = find_seq(cuc, B, t);
+        s_q[q] = clampi(cuc[b], 0, T);
+        nv_q[q] = nvc[b];
+        const int slot = s_q[q] + ord_q[q] / W;
+        pc_q[q] = precede[slot];
+        if (merging) {
+          const int n = (nv_q[q] + W - 1) / W;
+          wm_q[q] = win_merged[slot];
+          mb_q[q] = merged_before[slot];
+          rl_q[q] = rank_c[s_q[q] + n - 1];
+          lm_q[q] = win_merged[s_q[q] + n - 1];
         }
       }
     }
-    const unsigned long long mask = __ballot(keep);
-    const int before = __popcll(mask & ((1ull << lane) - 1ull));
-    if (lane == 0) wave_tot[wave] = __popcll(mask);
-    __syncthreads();
-    int wave_base = 0, total = 0;
+    bool keep_q[CQ], merged_q[CQ];
 #pragma unroll
-    for (int w = 0; w < 16; ++w) {
-      if (w < wave) wave_base += wave_tot[w];
-      total += wave_tot[w];
-    }
-    if (t < T) {
-      const int pos = running + wave_base + before;
-      keep_prefix[t] = pos;
-      if (keep) {
-        kept_idx[pos] = t;
-        if (is_visual_out != nullptr) is_visual_out[pos] = is_visual[t];
-        if (is_merged_out != nullptr) is_merged_out[pos] = merged_tok ? 1 : 0;
+    for (int q = 0; q < CQ; ++q) {
+      const int ord = ord_q[q];
+      bool keep = (ord == -1), merged_tok = false;
+      if (ord >= 0) {
+        const int nv = nv_q[q];
+        const int in_win = ord % W;
+        if (!merging) {
+          keep = in_win < window_keep_lead(ord, nv, W, retention, pc_q[q]);
+        } else if (wm_q[q]) {
+          keep = merged_tok = in_win == 0;
+        } else {
+          const int n = (nv + W - 1) / W;
+          const bool short_last = nv - (n - 1) * W < W;
+          const int L = short_last ? rl_q[q] : n;
+          const fmoe_merge_plan p = merge_plan(nv, W, retention, gamma, L);
+          keep = in_win < window_keep_lead_merge(ord, nv, W, pc_q[q], mb_q[q], lm_q[q] != 0, p.u_rem);
+        }
       }
+      keep_q[q] = keep;
+      merged_q[q] = merged_tok;
     }
-    running += total;
+    int before_q[CQ];
+#pragma unroll
+    for (int q = 0; q < CQ; ++q) {
+      const unsigned long long mask = __ballot(keep_q[q]);
+      before_q[q] = __popcll(mask & ((1ull << lane) - 1ull));
+      if (lane == 0) wave_tot[q][wave] = __popcll(mask);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < CQ; ++q) {
+      int wave_base = 0, total = 0;
+#pragma unroll
+      for (int w = 0; w < 16; ++w) {
+        if (w < wave) wave_base += wave_tot[q][w];
+        total += wave_tot[q][w];
+      }
+      const int t = base + q * 1024 + threadIdx.x;
+      if (t < T) {
+        const int pos = running + wave_base + before_q[q];
+        keep_prefix[t] = pos;
+        if (keep_q[q]) {
+          kept_idx[pos] = t;
+          if (is_visual_out != nullptr) is_visual_out[pos] = is_visual[t];
+          if (is_merged_out != nullptr) is_merged_out[pos] = merged_q[q] ? 1 : 0;
+        }
+      }
+      running += total;
+    }
     __syncthreads();
   }
   if (threadIdx.x == 0) keep_prefix[T] = running;
@@ -458,8 +505,7 @@ constexpr int SB_MAX_B = 512;                  // sequences whose bounds are cac
 
 struct SmallArgs {
   int prune;                       // 0: keep every token
-  const int32_t* T_dev;            // nullable: device count of the tokens present (<= T)
-  int write_kept;                  // 0: permutation only -- kept_idx / new_cu / is_visual_out stay untouched
+  const int32_t* T_dev;            // PERM_ONLY instantiation: device count of the tokens present (<= T)
   const uint8_t* is_visual;
   const int32_t* cu;
   int B, T, W;
@@ -484,7 +530,9 @@ struct SmallArgs {
 };
 
 // SB_TP tokens per thread, at most KM experts per token (both fix the size of register arrays).
-template <int SB_TP, int KM>
+// PERM_ONLY: every token up to the device count *T_dev is kept (a.prune is 0); only the permutation
+// and the tile lists are produced, kept_idx / new_cu / is_visual_out stay untouched.
+template <int SB_TP, int KM, bool PERM_ONLY>
 __global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallArgs a) {
   __shared__ uint16_t s_kept[SB_MAX_T];
   // phase 1: precede u16[SB_MAX_T] | 2 x sort keys u64[SB_MAX_NW] | 2 x sort keys u32[SB_MAX_NW]
@@ -507,7 +555,7 @@ __global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallA
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int W = a.W, E = a.E, Kmax = a.Kmax, B = a.B;
   int T = a.T;
-  if (a.T_dev != nullptr) {
+  if constexpr (PERM_ONLY) {
     const int Td = *a.T_dev;
     T = Td < T ? (Td > 0 ? Td : 0) : T;
   }
@@ -739,7 +787,7 @@ __global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallA
 
   // ---- outputs
   if (tid <= E) a.expert_offsets[tid] = s_off[tid];
-  for (int b = tid; b <= B && a.write_kept; b += SB_THREADS) {   // new_cu[b] = kept tokens before the sequence start
+  for (int b = tid; b <= B && !PERM_ONLY; b += SB_THREADS) {   // new_cu[b] = kept tokens before the sequence start
     const int c = clampi(cu[b], 0, T);
     int lo = 0, hi = n;
     while (lo < hi) {
@@ -752,7 +800,7 @@ __global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallA
   for (int k = 0; k < SB_TP; ++k) {
     const int p = pos_r[k];
     if (p >= 0) {
-      if (a.write_kept) {
+      if constexpr (!PERM_ONLY) {
         a.kept_idx[p] = k * SB_THREADS + tid;
         if (a.is_visual_out != nullptr) a.is_visual_out[p] = vis_r[k];
       }
@@ -885,7 +933,6 @@ int launch_prune_dispatch_small(const fmoe_ctx* ctx, const fmoe_prune_params* pp
   SmallArgs a;
   a.prune = prune ? 1 : 0;
   a.T_dev = T_dev;
-  a.write_kept = write_kept ? 1 : 0;
   a.is_visual = is_visual;
   a.cu = cu_seqlens;
   a.B = B; a.T = T; a.W = prune ? pp->window : 1;
@@ -904,11 +951,21 @@ int launch_prune_dispatch_small(const fmoe_ctx* ctx, const fmoe_prune_params* pp
   a.tile_count = reinterpret_cast<int32_t*>(base + L.tile_count);
   {
     fmoe_prof_scope prof(ctx, SLOT_DISPATCH, stream);
-    if (T <= 2 * SB_THREADS && ctx->kmax <= 8)
-      hipLaunchKernelGGL((prune_dispatch_small_kernel<2, 8>), dim3(1), dim3(SB_THREADS), 0, stream, a);
-    else
-      hipLaunchKernelGGL((prune_dispatch_small_kernel<SB_MAX_TP, FMOE_MAX_TOPK>), dim3(1), dim3(SB_THREADS),
-                         0, stream, a);
+    const bool fast = T <= 2 * SB_THREADS && ctx->kmax <= 8;
+    if (!write_kept) {
+      if (prune || T_dev == nullptr)
+        return fmoe_fail(FMOE_ERR_INVALID_ARG, "small dispatch: the permutation-only form needs a device token count and no pruning");
+      if (fast)
+        hipLaunchKernelGGL((prune_dispatch_small_kernel<2, 8, true>), dim3(1), dim3(SB_THREADS), 0, stream, a);
+      else
+        hipLaunchKernelGGL((prune_dispatch_small_kernel<SB_MAX_TP, FMOE_MAX_TOPK, true>), dim3(1),
+                           dim3(SB_THREADS), 0, stream, a);
+    } else if (fast) {
+      hipLaunchKernelGGL((prune_dispatch_small_kernel<2, 8, false>), dim3(1), dim3(SB_THREADS), 0, stream, a);
+    } else {
+      hipLaunchKernelGGL((prune_dispatch_small_kernel<SB_MAX_TP, FMOE_MAX_TOPK, false>), dim3(1),
+                         dim3(SB_THREADS), 0, stream, a);
+    }
   }
   FMOE_HIP_CHECK(hipGetLastError());
   return FMOE_OK;
