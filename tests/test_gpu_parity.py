@@ -660,3 +660,52 @@ def test_layer_forward_ablation_switches(seed, kw):
     n = int(host(new_cu)[-1])
     assert np.array_equal(host(kept)[:n], o_kept) and np.array_equal(host(mrg)[:n], o_mrg)
     _check_merged_rows(host(x_m)[:n], o_xm, o_mrg, wl.dtype)
+
+
+# ---------------------------------------------------------------- randomized sweep
+def _random_case(seed):
+    rng = np.random.default_rng(7000 + seed)
+    E = int(rng.choice([3, 5, 8, 16, 33, 64, 100, 128, 256]))
+    k_text = int(rng.integers(1, min(E, 16) + 1))
+    k_visual = int(rng.integers(0, k_text + 1))
+    n_seq = int(rng.integers(1, 6))
+    T_v = [int(v) for v in rng.choice([0, 1, 2, 7, 30, 64, 101, 257], size=n_seq)]
+    T_t = [int(v) for v in rng.choice([0, 1, 3, 9, 20], size=n_seq)]
+    if sum(T_v) + sum(T_t) == 0:
+        T_t[0] = 4
+    n_shared = int(rng.choice([0, 0, 1, 2]))
+    kw = dict(T_v=T_v, T_t=T_t, d=int(rng.choice([16, 40, 64, 136, 256, 320])), E=E,
+              F=int(rng.choice([8, 24, 64, 104])), k_text=k_text, k_visual=k_visual,
+              retention=float(rng.choice([0.1, 0.3, 0.5, 0.77, 0.95, 1.0])), window=int(rng.integers(1, 9)),
+              dtype=str(rng.choice([W.F32, W.BF16])), n_shared=n_shared,
+              F_shared=int(rng.choice([8, 40])) if n_shared else None, bias_std=float(rng.choice([0.0, 1.0, 2.5])),
+              n_components=int(rng.choice([0, 4, 16])), interleave=bool(rng.integers(0, 2)))
+    if k_visual == 0 and n_shared == 0:
+        kw["k_visual"] = 1                                  # K_v = 0 needs shared experts (Sec. 3.1)
+    extra = dict(gamma=float(rng.choice([0.0, 0.0, 0.1, 0.6])), alpha=float(rng.choice([1.0, 0.6, 0.0])),
+                 use_attn=bool(rng.integers(0, 2)), sim_mode=int(rng.integers(0, 2)))
+    return kw, extra
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_randomized_layer_sweep(seed):
+    kw, extra = _random_case(seed)
+    wl = W.small_random(7000 + seed, **kw)
+    rng = np.random.default_rng(9000 + seed)
+    attn = (rng.random(wl.T).astype(np.float32) ** 2) if extra["use_attn"] else None
+    alpha = extra["alpha"] if attn is not None else 1.0
+    over = dict(add_residual=True, gamma=extra["gamma"], alpha=alpha, attn=attn, sim_mode=extra["sim_mode"])
+    o = _oracle(wl, **over)
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    pp = binding.prune_params(retention=wl.retention, window=wl.window, alpha=alpha, gamma=extra["gamma"],
+                              sim_mode=extra["sim_mode"])
+    out, kept, new_cu, vis_out = m.layer_forward(x, vis, cu, pp, attn=dev(attn), add_residual=True, want_mask=True)
+    torch.cuda.synchronize()
+    new_cu = host(new_cu)
+    n = int(new_cu[-1])
+    assert np.array_equal(new_cu, o["new_cu_seqlens"]), (kw, extra)
+    assert np.array_equal(host(kept)[:n], o["kept_idx"]), (kw, extra)
+    assert np.array_equal(host(vis_out)[:n], wl.is_visual[o["kept_idx"]])
+    if n:
+        assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype], (kw, extra)
