@@ -12,6 +12,8 @@
 #define FMOE_MAX_WINDOW 64
 #define FMOE_PERM_BLOCK 256   // kept positions per block in the permutation kernels
 #define FMOE_TILE_M 64        // rows per grouped-GEMM tile (tile list granularity)
+#define FMOE_TILE_RUN 8       // row tiles per run of a group in the tile lists
+#define FMOE_SEG_MIN_TILES 256   // tile entries from which each XCD takes a contiguous segment of the list
 
 // ---- optional per-kernel timing (instrumentation; off by default)
 enum fmoe_kernel_slot {

@@ -365,8 +365,19 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(StreamArgs a) {
   const int rr = item >> 3;
   const int batch = rr / a.cols;
   int nt_launch = rr - batch * a.cols;
-  int ti = batch * 8 + xcd;
-  if (ti >= n_tiles) return;
+  int ti;
+  if (n_tiles >= FMOE_SEG_MIN_TILES) {
+    // long lists: XCD x takes the contiguous eighth [s0, s1) of the list, so that the runs of one
+    // group (whose workgroups share weights and activation rows) stay in one L2
+    const int s0 = (int)(((long long)n_tiles * xcd) >> 3);
+    const int s1 = (int)(((long long)n_tiles * (xcd + 1)) >> 3);
+    if (batch >= s1 - s0) return;
+    ti = s0 + batch;
+  } else {
+    // short lists: entries dealt round-robin, which spreads the few long (shared-group) tiles evenly
+    ti = batch * 8 + xcd;
+    if (ti >= n_tiles) return;
+  }
   fmoe_tile tile = a.tiles[ti];
   const bool shared = tile.group >= a.E;
   // field-by-field select keeps the descriptors in scalar registers (indexing the kernel argument
@@ -385,6 +396,8 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(StreamArgs a) {
   // run per original row tile, i.e. an XCD gets ALL row tiles of ~C/R column tiles, so each weight
   // column block is fetched by one XCD (two at a run boundary) instead of by all of them (weights
   // outweigh the activation rows, which every XCD then reads).
+  // (runs are at most FMOE_TILE_RUN row tiles long; in a long list the whole run sits on this XCD and
+  // the re-deal makes it walk the run column-major, about eight row tiles by eight column tiles at a time)
   if (tile.nrt > 1) {
     const int w = tile.rt * c_eff + nt_launch;
     const int r2 = w % tile.nrt;

@@ -14,7 +14,10 @@
 // descending row count (ties: ascending expert id), so that the short tiles are the ones left to
 // fill the tail of the launch.  A launch gives every entry `cols1` column tiles; the shared group
 // of list 1 may have more (`scols1`): its row tiles are then repeated with a column-tile offset in
-// `col0`.  The row tiles of one group (one replica) are consecutive entries.
+// `col0`.  The row tiles of one group (one replica) are consecutive entries, cut into runs of at most
+// FMOE_TILE_RUN row tiles (rt / nrt number a tile within its run): a run is the unit within which
+// the GEMM kernel re-deals its workgroups column-major, and eight row tiles by eight column tiles
+// is about what one XCD runs at a time.
 // counts[0], counts[1] = number of entries in list 1 / list 2.  Experts whose offsets are malformed
 // (negative, decreasing or past row_cap) are skipped so that no tile can index outside the row
 // buffers.  `scratch` is 513 ints of LDS (8-byte aligned); bm is a power of two.
@@ -60,8 +63,8 @@ __device__ __forceinline__ void fmoe_build_tiles(const int32_t* expert_offsets, 
     fmoe_tile t;
     t.row0 = j * bm;
     t.rows = (n - j * bm < bm) ? (n - j * bm) : bm;
-    t.rt = j;
-    t.nrt = ns;
+    t.rt = j % FMOE_TILE_RUN;
+    t.nrt = (ns - (j - t.rt) < FMOE_TILE_RUN) ? (ns - (j - t.rt)) : FMOE_TILE_RUN;
     t.group = E;
     for (int c = 0; c < rep1; ++c) {   // replica-major: the row tiles of one replica are consecutive
       const int slot = c * ns + j;
@@ -85,8 +88,8 @@ __device__ __forceinline__ void fmoe_build_tiles(const int32_t* expert_offsets, 
       t.row0 = r0 + j * bm;
       t.rows = (cnt - j * bm < bm) ? (cnt - j * bm) : bm;
       t.col0 = 0;
-      t.rt = j;
-      t.nrt = nt;
+      t.rt = j % FMOE_TILE_RUN;
+      t.nrt = (nt - (j - t.rt) < FMOE_TILE_RUN) ? (nt - (j - t.rt)) : FMOE_TILE_RUN;
       if (sh1 + start + j < tile_cap) tiles1[sh1 + start + j] = t;
       if (sh2 + start + j < tile_cap) tiles2[sh2 + start + j] = t;
     }
