@@ -30,6 +30,8 @@
 // The fp32 storage type (a correctness configuration) uses a plain LDS-tiled kernel on the fp32
 // MFMA with the caller's weight layout.
 
+#include <type_traits>
+
 #include "common.h"
 #include "tiles.h"
 
@@ -293,24 +295,44 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
       asm volatile("" ::: "memory");
     }
   }
-  for (; t < NT; t += UNROLL) {        // tail: the number of newer loads shrinks as issuing stops
-#pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-      const int tt = t + u;
-      if (tt < NT) {
-        int newer = 0;   // loads issued in the steps after the one that fetched tile tt's activations
-#pragma unroll
-        for (int q = 1; q < A_AHEAD; ++q) {
-          const int st = tt - A_AHEAD + q;   // issuing step
-          newer += (st + A_AHEAD < NT ? NAB : 0) + (st + B_AHEAD < NT ? 4 : 0);
-        }
-        wait_vm_upto(newer);
-        block_barrier();
-        if (tt + A_AHEAD < NT) loadA((u + A_AHEAD) % A_STAGES, tt + A_AHEAD);
-        if (tt + B_AHEAD < NT) loadB((u + B_AHEAD) % B_SLOTS, tt + B_AHEAD);
-        step(u % B_SLOTS, u % A_STAGES, false, 0, 0, 0, 0);
+  // Tail: 3..6 steps are left after the steady loop (1..6 when it did not run).  Every count gets its
+  // own straight-line code, so that which steps still issue loads, and how many loads are newer than
+  // the tile a step waits for, are compile-time facts as in the steady state (a loop with run-time
+  // conditions around the loads makes the compiler wait for all of them).
+  auto tail_step = [&](auto rem_c, auto j_c) {
+    constexpr int REM = decltype(rem_c)::value, J = decltype(j_c)::value;
+    constexpr int newer = [] {   // loads of the steps after the one that fetched tile J's activations
+      int n = 0;
+      for (int q = 1; q < A_AHEAD; ++q) {
+        const int st = J - A_AHEAD + q;   // issuing step, relative to the first tail step
+        n += (st + A_AHEAD < REM ? NAB : 0) + (st + B_AHEAD < REM ? 4 : 0);
       }
-    }
+      return n;
+    }();
+    FMOE_WAIT_VM(newer);
+    block_barrier();
+    constexpr bool more = J + A_AHEAD < REM;   // the rings are equally deep: all of a step's loads or none
+    step(J % B_SLOTS, J % A_STAGES, more, (J + B_AHEAD) % B_SLOTS, (J + A_AHEAD) % A_STAGES,
+         t + J + A_AHEAD, t + J + B_AHEAD);
+  };
+  auto tail = [&](auto rem_c) {
+    constexpr int REM = decltype(rem_c)::value;
+    tail_step(rem_c, std::integral_constant<int, 0>{});
+    if constexpr (REM > 1) tail_step(rem_c, std::integral_constant<int, 1>{});
+    if constexpr (REM > 2) tail_step(rem_c, std::integral_constant<int, 2>{});
+    if constexpr (REM > 3) tail_step(rem_c, std::integral_constant<int, 3>{});
+    if constexpr (REM > 4) tail_step(rem_c, std::integral_constant<int, 4>{});
+    if constexpr (REM > 5) tail_step(rem_c, std::integral_constant<int, 5>{});
+  };
+  static_assert(A_AHEAD == B_AHEAD && UNROLL + B_AHEAD == 7, "the tail below covers 1..6 left-over steps");
+  switch (NT - t) {   // uniform
+    case 1: tail(std::integral_constant<int, 1>{}); break;
+    case 2: tail(std::integral_constant<int, 2>{}); break;
+    case 3: tail(std::integral_constant<int, 3>{}); break;
+    case 4: tail(std::integral_constant<int, 4>{}); break;
+    case 5: tail(std::integral_constant<int, 5>{}); break;
+    case 6: tail(std::integral_constant<int, 6>{}); break;
+    default: break;   // 0: K is a multiple of the steady loop's stride plus its look-ahead
   }
 
   // epilogue: accumulator register v of lane l holds row 4*(l/16) + v, column l%16 of a 16x16 block.
@@ -354,7 +376,7 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
 }
 
 template <bool SWIGLU>
-__global__ __launch_bounds__(256) void ffn_stream_kernel(StreamArgs a) {
+__global__ __launch_bounds__(256, 2) void ffn_stream_kernel(StreamArgs a) {
   __shared__ __align__(16) bf16_t As[A_STAGES * SBM * SBK];
 
   // One work item per block: item -> (batch of 8 row tiles, column tile, tile within the batch =
