@@ -765,7 +765,6 @@ int run_ffn_f32(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int
                 const fmoe_ffn_geom& geo, hipStream_t stream) {
   const fmoe_config& c = ctx->cfg;
   const int d = c.d_model, E = c.n_experts, F = c.d_ffn;
-  const bool has_shared = c.n_shared > 0;
   const int Fs = c.d_ffn_shared, Ft = c.n_shared * Fs;
   int32_t* tile_count = reinterpret_cast<int32_t*>(base + L.tile_count);
   GemmArgs g1{}, g2{};
