@@ -30,7 +30,7 @@ VALU_F32_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the dominant kernel on workload c2 from two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB; the factors are what a 256 MiB device copy reads on the
 # same counters) -- profiles/ffn_stream_c2_hbm_traffic.md.  Other workloads: not measured.
-MEASURED_TRAFFIC_BYTES = {"c2": int((85963.6 * 2.0 + 7616.0) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"c2": int((86897.9 * 2.0 + 7616.0) * 1024)}
 
 
 def main():
