@@ -139,7 +139,7 @@ def main():
                    + n_kept * d * (1 if Ns else 0)) * es,
             flops=2.0 * M * d * F + 2.0 * n_kept * d * Fs * Ns,
             peak_tflops=MFMA_BF16_PEAK_TFLOPS if is_bf16 else MFMA_F32_PEAK_TFLOPS),
-        "combine_kernel": dict(bytes=M * d * es + (n_kept * d * es if Ns else 0) + n_kept * d * es
+        "combine_kernel": dict(bytes=M * d * es + Ns * n_kept * d * es + n_kept * d * es
                                + n_kept * Kmax * 8, flops=2.0 * M * d, peak_tflops=VALU_F32_PEAK_TFLOPS),
         "window_score_kernel": dict(bytes=n_vis * E * 4 + (n_vis // wl.window) * 4, flops=6.0 * n_vis * E,
                                     peak_tflops=VALU_F32_PEAK_TFLOPS),
