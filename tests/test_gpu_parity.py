@@ -709,3 +709,23 @@ def test_randomized_layer_sweep(seed):
     assert np.array_equal(host(vis_out)[:n], wl.is_visual[o["kept_idx"]])
     if n:
         assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype], (kw, extra)
+
+
+@pytest.mark.parametrize("d,F", [(448, 576), (576, 640), (640, 704), (832, 960), (960, 448)])
+def test_expert_ffn_k_loop_lengths(d, F):
+    # bf16 expert GEMMs at reduction lengths of 7..15 k-tiles of 64: every combination of steady-loop
+    # iterations and left-over steps (3, 4, 5, 6) of the streaming kernel's k loop, ragged row counts
+    wl = W.small_random(8000 + d, T_v=[150, 40], T_t=[30, 7], d=d, E=12, F=F, k_text=4, k_visual=2,
+                        retention=0.5, window=3, dtype=W.BF16, n_shared=1, F_shared=F - 64, bias_std=1.5)
+    o = _oracle(wl, add_residual=True)
+    n = len(o["kept_idx"])
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    out, kept, new_cu, _ = m.layer_forward(x, vis, cu, binding.prune_params(retention=0.5, window=3),
+                                           add_residual=True)
+    assert np.array_equal(host(kept)[:n], o["kept_idx"])
+    assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[W.BF16]
+    y, ysh = m.expert_ffn(x, dev(o["kept_idx"]), n, dev(o["expert_offsets"]), dev(o["perm_src"]))
+    M = int(o["expert_offsets"][-1])
+    assert max_rel_err(host(y)[:M], o["y"]) <= TOL[W.BF16]
+    assert max_rel_err(host(ysh).astype(np.float64).sum(0)[:n], o["y_shared"]) <= TOL[W.BF16]
