@@ -285,6 +285,9 @@ __global__ __launch_bounds__(1024) void compact_kernel(
     const int32_t* __restrict__ merged_before, uint8_t* __restrict__ is_merged_out) {
   // gamma > 0 (window merging): a merged window keeps exactly its first token; the others follow the
   // drop rule with the merged windows taken out of the walk and the budget merging left.
+  // win_merged == nullptr (no attention term: drop order and merge order are the same order): which
+  // windows merge and how many merged windows precede a window follow in closed form from the
+  // window's place rank_c in that order and the place of the sequence's last window.
   // CQ chunks of 1024 tokens per round.  A token's decision is a chain of dependent loads (its visual
   // ordinal -> its window's counters); the round issues each link of the chain for all its chunks
   // before using any of them, so that the memory latencies overlap, and the sequence bounds are
@@ -302,6 +305,7 @@ __global__ __launch_bounds__(1024) void compact_kernel(
   const int32_t* cuc = cached ? s_cu : cu;   // clamping a clamped bound changes nothing
   const int32_t* nvc = cached ? s_nv : seq_nv;
   const bool merging = gamma > 0.0f;
+  const bool closed = merging && win_merged == nullptr;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int running = 0;
   for (int base = 0; base < T; base += CQ * 1024) {
@@ -323,10 +327,14 @@ __global__ __launch_bounds__(1024) void compact_kernel(
         pc_q[q] = precede[slot];
         if (merging) {
           const int n = (nv_q[q] + W - 1) / W;
-          wm_q[q] = win_merged[slot];
-          mb_q[q] = merged_before[slot];
           rl_q[q] = rank_c[s_q[q] + n - 1];
-          lm_q[q] = win_merged[s_q[q] + n - 1];
+          if (closed) {
+            wm_q[q] = rank_c[slot];   // the window's place; turned into the merged flag below
+          } else {
+            wm_q[q] = win_merged[slot];
+            mb_q[q] = merged_before[slot];
+            lm_q[q] = win_merged[s_q[q] + n - 1];
+          }
         }
       }
     }
@@ -340,14 +348,22 @@ __global__ __launch_bounds__(1024) void compact_kernel(
         const int in_win = ord % W;
         if (!merging) {
           keep = in_win < window_keep_lead(ord, nv, W, retention, pc_q[q]);
-        } else if (wm_q[q]) {
-          keep = merged_tok = in_win == 0;
         } else {
           const int n = (nv + W - 1) / W;
           const bool short_last = nv - (n - 1) * W < W;
           const int L = short_last ? rl_q[q] : n;
           const fmoe_merge_plan p = merge_plan(nv, W, retention, gamma, L);
-          keep = in_win < window_keep_lead_merge(ord, nv, W, pc_q[q], mb_q[q], lm_q[q] != 0, p.u_rem);
+          int is_m = wm_q[q], mb = mb_q[q], last_m = lm_q[q];
+          if (closed) {
+            const int r = wm_q[q];                                   // place of this window
+            const int k = r - ((short_last && L < r) ? 1 : 0);       // full-size windows ahead of it
+            const bool is_last = short_last && (ord / W == n - 1);
+            is_m = is_last ? p.last_m : (k < p.q_full ? 1 : 0);
+            last_m = short_last ? p.last_m : (rl_q[q] < p.q_full ? 1 : 0);
+            mb = (k < p.q_full ? k : p.q_full) + ((short_last && p.last_m && L < r) ? 1 : 0);
+          }
+          if (is_m) keep = merged_tok = in_win == 0;
+          else keep = in_win < window_keep_lead_merge(ord, nv, W, pc_q[q], mb, last_m != 0, p.u_rem);
         }
       }
       keep_q[q] = keep;
@@ -864,7 +880,8 @@ int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* 
                        pp->alpha, seq_nv, win_s, win_a, drop_from, scores_out, rank_c,
                        static_cast<const int32_t*>(nullptr));
   }
-  if (merging) {   // which windows merge, then how many merged windows precede each window in drop order
+  const bool closed_form = merging && attn == nullptr;   // one order: the compaction derives the merged set
+  if (merging && !closed_form) {   // which windows merge, then how many merged windows precede each window in drop order
     hipLaunchKernelGGL(merge_decide_kernel, dim3((T + 255) / 256), dim3(256), 0, stream, cu_seqlens, B, T,
                        pp->window, pp->retention, pp->gamma, seq_nv, rank_c, win_merged, merged_before);
     hipLaunchKernelGGL(select_kernel, sel_grid, dim3(256), 0, stream, cu_seqlens, B, T, pp->window,
@@ -875,7 +892,8 @@ int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* 
     fmoe_prof_scope prof(ctx, SLOT_COMPACT, stream);
     hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, stream, is_visual, cu_seqlens, B, T,
                        pp->window, pp->retention, vis_ord, seq_nv, drop_from, keep_prefix, kept_idx,
-                       new_cu_seqlens, is_visual_out, pp->gamma, rank_c, win_merged, merged_before,
+                       new_cu_seqlens, is_visual_out, pp->gamma, rank_c,
+                       closed_form ? static_cast<int32_t*>(nullptr) : win_merged, merged_before,
                        merging ? is_merged : static_cast<uint8_t*>(nullptr));
   }
   if (merging) {
