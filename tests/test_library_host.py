@@ -120,3 +120,37 @@ def test_stage_bookkeeping_matches_the_oracles_counts():
         assert int(new_cu[-1]) == binding.kept_count(lens, nt, 1.0)
         vis, cu = vis[kept], new_cu
     assert lens[2] == 0 and lens[1] >= 1                      # empty stays empty; N_v > 0 keeps >= 1
+
+
+def test_switches_and_diagnostics_validate_their_arguments(lib):
+    """Host-side checks of the ablation switches and the diagnostics entry points: bad values are
+    refused with an error code before anything is enqueued (no GPU needed)."""
+    cfg = binding.FmoeConfig(64, 8, 32, 0, 0, 2, 1, 1, binding.FMOE_F32)
+    ctx = C.c_void_p()
+    assert lib.fmoe_create(C.byref(ctx), C.byref(cfg), 0) == 0
+    # selection strategy: 0..2, k_base within [0, min(E, 16)]
+    assert lib.fmoe_set_selection(ctx, binding.MINK, 4, 7) == 0
+    assert lib.fmoe_set_selection(ctx, 3, 4, 0) == -1
+    assert lib.fmoe_set_selection(ctx, binding.RANDOMK, 9, 0) == -1          # E = 8
+    assert lib.fmoe_set_selection(ctx, binding.RANDOMK, -1, 0) == -1
+    assert lib.fmoe_set_selection(None, 0, 0, 0) == -2
+    assert lib.fmoe_set_selection(ctx, binding.TOPK, 0, 0) == 0
+    # merge method: 0 (MLERP) or 1 (mean)
+    bad = binding.prune_params(retention=0.5, window=3, gamma=0.1, merge_mode=2)
+    assert lib.fmoe_prune(ctx, C.byref(bad), None, None, None, 1, 4, None, None, None, None, None, None, None,
+                          None, 0, None) == -1
+    assert b"merge_mode" in lib.fmoe_last_error()
+    # diagnostics
+    dummy = C.c_void_p(0x1000)
+    assert lib.fmoe_gate_cosine(ctx, dummy, 4, 8, 9, dummy, None) == -1       # m > K
+    assert lib.fmoe_gate_cosine(ctx, dummy, 4, 0, 0, dummy, None) == -1       # K < 1
+    assert lib.fmoe_gate_cosine(ctx, None, 4, 8, 2, dummy, None) == -2
+    assert lib.fmoe_gate_cosine(ctx, None, 0, 8, 2, None, None) == 0          # nothing to do
+    assert lib.fmoe_adjacent_similarity(ctx, dummy, dummy, dummy, -1, 4, dummy, dummy, dummy, None) == -1
+    assert lib.fmoe_adjacent_similarity(ctx, dummy, dummy, dummy, 0, 4, dummy, dummy, dummy, None) == -1
+    assert lib.fmoe_adjacent_similarity(ctx, dummy, dummy, None, 1, 4, dummy, dummy, dummy, None) == -2
+    assert lib.fmoe_magnitude_stability(ctx, dummy, -1, None, dummy, None, dummy, dummy, dummy, None) == -1
+    assert lib.fmoe_magnitude_stability(ctx, dummy, 4, None, None, None, dummy, dummy, dummy, None) == -2
+    assert lib.fmoe_row_cosine(ctx, dummy, None, 4, None, dummy, None) == -2
+    assert lib.fmoe_row_cosine(ctx, None, None, 0, None, None, None) == 0
+    lib.fmoe_destroy(ctx)
