@@ -30,7 +30,7 @@ VALU_F32_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the dominant kernel on workload c2 from two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB; the factors are what a 256 MiB device copy reads on the
 # same counters) -- profiles/ffn_stream_c2_hbm_traffic.md.  Other workloads: not measured.
-MEASURED_TRAFFIC_BYTES = {"c2": int((86897.9 * 2.0 + 7616.0) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"c2": int((84611.9 * 2.0 + 7616.0) * 1024)}
 
 
 def main():
@@ -44,6 +44,16 @@ def main():
                          "c5_layer_full: the same layer with top-6 for every token and no pruning)")
     ap.add_argument("--gamma", type=float, default=0.0,
                     help="merge rate of Sec. 3.2.3 (context runs; the metric is quoted at 0, i.e. without merging)")
+    ap.add_argument("--weight-copies", type=int, default=None,
+                    help="cycle the steps over this many copies of the layer's weights, each in device memory of "
+                         "its own (same values, same result).  Default 4 for workload c2, whose 164 MB of touched "
+                         "weights would otherwise partly stay in the 256 MB memory-side cache from one step to "
+                         "the next, which no layer of a real model's forward pass enjoys; 1 elsewhere (those "
+                         "layers exceed that cache on their own)")
+    ap.add_argument("--also-same-copy", action="store_true",
+                    help="after the timed region, time the same number of steps on one copy of the weights only "
+                         "and add the result as 'same_weights_every_step' (off by default: a kernel trace of the "
+                         "run would otherwise average launches with and without cache-resident weights)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=30)
     ap.add_argument("--copy-calib", action="store_true",
@@ -76,22 +86,35 @@ def main():
         r = torch.from_numpy(np.ascontiguousarray(a)).cuda()
         return r.to(t).contiguous() if t is not None else r
 
+    def make_ctx(w):
+        c = binding.FMoE(d_model=wl.d, n_experts=wl.E, d_ffn=wl.F, n_shared=wl.n_shared,
+                         d_ffn_shared=wl.F_shared if wl.n_shared else 0, k_text=wl.k_text,
+                         k_visual=wl.k_visual, dtype=wl.dtype)
+        c.set_weights(dev(w.router_w, td), dev(w.router_bias), dev(w.w_gate, td), dev(w.w_up, td),
+                      dev(w.w_down, td), dev(w.ws_gate, td), dev(w.ws_up, td), dev(w.ws_down, td))
+        return c
+
+    # every copy holds the same layer: the steps differ only in where their weights live
+    NL = args.weight_copies if args.weight_copies is not None else (4 if args.workload == "c2" else 1)
+    NL = max(1, min(NL, 64))
     lw = wl.weights
-    m = binding.FMoE(d_model=wl.d, n_experts=wl.E, d_ffn=wl.F, n_shared=wl.n_shared,
-                     d_ffn_shared=wl.F_shared if wl.n_shared else 0, k_text=wl.k_text,
-                     k_visual=wl.k_visual, dtype=wl.dtype)
-    m.set_weights(dev(lw.router_w, td), dev(lw.router_bias), dev(lw.w_gate, td), dev(lw.w_up, td),
-                  dev(lw.w_down, td), dev(lw.ws_gate, td), dev(lw.ws_up, td), dev(lw.ws_down, td))
+    ctxs = [make_ctx(lw) for _ in range(NL)]
+    m = ctxs[0]
     x, vis, cu = dev(wl.x, td), dev(wl.is_visual), dev(wl.cu_seqlens)
     pp = binding.prune_params(retention=wl.retention, window=wl.window, gamma=args.gamma)
     T, B = wl.T, wl.B
     out = torch.empty((T, wl.d), dtype=td, device="cuda")
     kept = torch.empty(T, dtype=torch.int32, device="cuda")
     new_cu = torch.empty(B + 1, dtype=torch.int32, device="cuda")
-    m.workspace(T, B)
+    for c in ctxs:
+        c.workspace(T, B)
+    calls = [0]
 
     def step():
-        m.layer_forward(x, vis, cu, pp, out=out, kept_idx=kept, new_cu=new_cu)
+        c = ctxs[calls[0] % NL]
+        calls[0] += 1
+        c.layer_forward(x, vis, cu, pp, out=out, kept_idx=kept, new_cu=new_cu)
+        return c
 
     for _ in range(args.warmup):
         step()
@@ -103,16 +126,29 @@ def main():
     ev1.record()
     torch.cuda.synchronize()
     ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    same_layer_ms = None
+    if NL > 1 and args.also_same_copy:   # for comparison: the same copy of the weights every step
+        for _ in range(args.warmup):
+            m.layer_forward(x, vis, cu, pp, out=out, kept_idx=kept, new_cu=new_cu)
+        ev0.record()
+        for _ in range(args.steps):
+            m.layer_forward(x, vis, cu, pp, out=out, kept_idx=kept, new_cu=new_cu)
+        ev1.record()
+        torch.cuda.synchronize()
+        same_layer_ms = ev0.elapsed_time(ev1) / args.steps
 
     # ---- instrumentation pass: HIP events around every kernel, on the launch stream
-    m.profile_enable(True)
+    for c in ctxs:
+        c.profile_enable(True)
     acc = {}
     nprof = max(1, min(args.profile_steps, args.steps))
+    nprof = (nprof + NL - 1) // NL * NL          # every copy the same number of times
     for _ in range(nprof):
-        step()
-        for k, v in m.profile_read().items():
+        c = step()
+        for k, v in c.profile_read().items():
             acc[k] = acc.get(k, 0.0) + v
-    m.profile_enable(False)
+    for c in ctxs:
+        c.profile_enable(False)
     kms = {k: v / nprof for k, v in acc.items()}
 
     # ---- algorithmic work per launch, from the shapes and the routing result of this input
@@ -199,9 +235,11 @@ def main():
         "config": {"workload": wl.name, "tokens": T, "visual": n_vis, "d_model": d, "experts": E,
                    "d_ffn": F, "shared_experts": Ns, "k_text": wl.k_text, "k_visual": wl.k_visual,
                    "retention": wl.retention, "window": wl.window, "kept_tokens": n_kept,
-                   "routed_rows": M, "experts_touched": touched,
+                   "routed_rows": M, "experts_touched": touched, "weight_copies": NL,
                    **({"gamma": args.gamma} if args.gamma > 0 else {})},
         "roofline": roofline, "cpu_baseline": cpu,
+        **({"same_weights_every_step": {"ms_per_step": round(same_layer_ms, 5),
+                                      "value": round(T / (same_layer_ms * 1e-3), 1)}} if same_layer_ms else {}),
         "kernel_sum_us": round(sum(kms.values()) * 1e3, 2), "kernels": kernels,
     }
     print(json.dumps(line), flush=True)
