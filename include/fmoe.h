@@ -72,6 +72,28 @@ typedef struct {
                          1 = plain mean (the alternative of the merge-method ablation, Sec. 4)  */
 } fmoe_prune_params;
 
+/* Model description for the theoretical FLOPs ratios of App. E (batch size 1, vision tokens only, as in
+ * the appendix).  Layers are indexed from 0; the first n_dense layers carry a dense MLP of intermediate
+ * size S instead of the experts (DeepSeek-VL2: 1, InternVL3.5: 0).  K and K_v count every active expert
+ * of a token, shared ones included (the printed DeepSeek-VL2 savings come out with K = 6 + 2 and
+ * K_v = 2 + 2).  Pruning after layer prune_layers[s] multiplies the vision length by beta, so layer i
+ * sees L_v * beta^(number of prune layers below i); lengths stay real numbers, as in the appendix. */
+typedef struct {
+  int32_t n_layers;        /* transformer layers                                                  */
+  int32_t n_dense;         /* leading layers with a dense MLP instead of the MoE FFN              */
+  double H;                /* hidden size                                                         */
+  double S;                /* intermediate size of the dense MLP (unused when n_dense = 0)        */
+  double S_m;              /* intermediate size of one expert                                     */
+  double E;                /* routed experts (the router term 2*L*H*E)                            */
+  double K;                /* active experts per token                                            */
+  double K_v;              /* active experts per vision token in layers >= l_v                    */
+  int32_t l_v;             /* first layer with reduced activation, 0 .. n_layers (n_layers: none) */
+  int32_t n_prune;         /* pruning stages, 0 .. 8                                              */
+  int32_t prune_layers[8]; /* ascending layer indices; the stage acts on the layers after it      */
+  double beta;             /* per-stage retention in (0,1]                                        */
+  double L_v;              /* vision tokens before pruning                                        */
+} fmoe_flops_model;
+
 typedef struct fmoe_ctx fmoe_ctx;
 
 /* Library version string, static storage. */
@@ -225,7 +247,7 @@ int fmoe_profile_read(fmoe_ctx* ctx, float* ms);
  * mean [2] / count [2] (out): average and number of the pairs, index 0 text, 1 vision (mean 0
  * without pairs).
  *
- * fmoe_magnitude_stability -- magnitude stability of expert outputs (App. B): row_norm[r] =
+ * fmoe_magnitude_stability -- magnitude stability of expert outputs (App. C.1): row_norm[r] =
  * Euclidean norm of row r of y [M, d_model] (the routed experts' outputs before the gate-weighted
  * sum, as fmoe_expert_ffn writes them; context dtype), for the first M rows or *M_dev of them when
  * M_dev is not NULL (a device count such as expert_offsets + E).  The modality of row r is that of
@@ -252,6 +274,17 @@ int fmoe_row_cosine(fmoe_ctx* ctx, const void* a, const void* b, int32_t n, cons
                     void* stream);
 int fmoe_gate_cosine(fmoe_ctx* ctx, const float* gates, int32_t T, int32_t K, int32_t m, float* out,
                      void* stream);
+
+/* ---- theoretical FLOPs (App. E) [host arithmetic only: no device, no context, no stream] ----------
+ * Per-layer cost on x tokens: attention 4*x^2*H + 8*x*H^2, plus the MoE FFN 2*x*H*E + 6*x*H*S_m*k
+ * (k = K, or K_v where activation is reduced) or, in a dense layer, the MLP 6*x*H*S.
+ * ratios[0] = R_prune (token pruning only), ratios[1] = R_act (reduced activation from layer l_v on,
+ * no pruning), ratios[2] = R_comb (both): total FLOPs over all layers divided by the unmodified model's;
+ * the saving the paper's tables print is 1 - R.  The tables' l_v counts MoE layers from one: their
+ * (l_v, K_v) entries are reproduced with l_v = table value - 1 + n_dense here.
+ * FMOE_ERR_NULL_PTR for a NULL argument, FMOE_ERR_INVALID_ARG for values outside the ranges above
+ * (non-positive sizes, beta outside (0,1], prune layers not ascending or outside the model). */
+int fmoe_flops_ratios(const fmoe_flops_model* model, double* ratios /* [3], host, out */);
 
 #ifdef __cplusplus
 }

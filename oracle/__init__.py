@@ -2,7 +2,8 @@
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by bench.py's
 cpu_baseline leg.  The product package never imports this module.  Only argument marshalling
-lives here; the arithmetic is in the C++ file.
+lives here; the arithmetic is in the C++ file (the two host formulas of the appendices, the merge-rate
+bound of App. D and the FLOPs ratios of App. E, are written out below).
 """
 from __future__ import annotations
 
@@ -145,6 +146,43 @@ def gamma_hat(retain_ratio, window, stages=3):
     (1/beta - 1)/(W - 1) with the per-stage retain ratio beta = r^(1/stages)."""
     beta = float(retain_ratio) ** (1.0 / stages)
     return (1.0 / beta - 1.0) / (window - 1)
+
+
+def flops_layer(x, H, E, S_m, K):
+    """App. E, baseline FLOPs with B = 1: C(x), one MoE transformer layer on a subsequence of x
+    tokens = attention 4x^2 H + 8xH^2 plus MoE FFN 2xHE + 6xH S_m K."""
+    x, H, E, S_m, K = float(x), float(H), float(E), float(S_m), float(K)
+    return 4.0 * x * x * H + 8.0 * x * H * H + 2.0 * x * H * E + 6.0 * x * H * S_m * K
+
+
+def flops_ratios(stage_layers, *, H, E, S_m, K, K_v, l_v, beta, L_v, n_dense=0, S=0.0):
+    """App. E's closed forms, stage by stage.  `stage_layers` = the number of MoE layers N_s that run at
+    vision length L_v, beta L_v, beta^2 L_v, ... (InternVL3.5: 6, 3, 4, 35; DeepSeek-VL2: 2, 3, 3, 21
+    after its one dense layer).  C'(x) is C(x) with K_v in place of K; Delta_s = C'_s - C_s; m_s = the
+    MoE layers of stage s whose index is l_v or more.
+        R_prune = (D + sum_s N_s C_s) / (D + N C_0)
+        R_act   = (D + (N - M) C_0 + M C'_0) / (D + N C_0),  M = sum_s m_s
+        R_comb  = (D + sum_s [N_s C_s + m_s Delta_s]) / (D + N C_0)
+    with N = sum_s N_s and D = the n_dense leading dense layers at full length, each its attention plus
+    the MLP 6 L_v H S (the appendix prints the MLP term alone; the savings it tabulates for DeepSeek-VL2
+    need the dense layer's attention in D as well).  Returns (R_prune, R_act, R_comb)."""
+    N = sum(stage_layers)
+    c0 = flops_layer(L_v, H, E, S_m, K)
+    D = n_dense * (4.0 * L_v * L_v * H + 8.0 * L_v * H * H + 6.0 * L_v * H * S)
+    den = D + N * c0
+    num_prune = num_comb = D
+    first = n_dense   # index of the stage's first layer
+    M = 0
+    for s, n_s in enumerate(stage_layers):
+        x = L_v * beta ** s
+        c_s, cp_s = flops_layer(x, H, E, S_m, K), flops_layer(x, H, E, S_m, K_v)
+        m_s = sum(1 for i in range(first, first + n_s) if i >= l_v)
+        num_prune += n_s * c_s
+        num_comb += n_s * c_s + m_s * (cp_s - c_s)
+        M += m_s
+        first += n_s
+    num_act = D + (N - M) * c0 + M * flops_layer(L_v, H, E, S_m, K_v)
+    return num_prune / den, num_act / den, num_comb / den
 
 
 def prune(probs, is_visual, cu_seqlens, retention, window, alpha=1.0, gamma=0.0, sim_mode=0,
@@ -325,7 +363,7 @@ def adjacent_similarity(probs, is_visual, cu_seqlens):
 
 
 def magnitude_stability(y, row_is_visual):
-    """App. B.  Returns row_norm [M] f32 and stats [2,4] f64 = (mu, sigma, CV, V) for text, vision."""
+    """App. C.1.  Returns row_norm [M] f32 and stats [2,4] f64 = (mu, sigma, CV, V) for text, vision."""
     y, vis = _f32(y), _u8(row_is_visual)
     M, d = y.shape
     norms = np.empty(max(M, 1), np.float32)

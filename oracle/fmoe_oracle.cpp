@@ -28,9 +28,9 @@
 //    result = p * 2^n, and exactly 0 when n < -125.
 //  * '/' and sqrt are the correctly rounded IEEE operations.
 //
-// parity unpinned: nothing in the paper prints a numeric worked example of the layer, so no
-// function here is pinned to paper-printed values; the pins are closed forms, invariants,
-// special cases and brute force (see tests/test_oracle_*.py).
+// Pins: the paper prints no numeric worked example of the layer, so the functions here are pinned
+// by closed forms, invariants, special cases that reduce to textbook routines and brute force on
+// small inputs (tests/test_oracle_pins.py); none is left unpinned.
 //
 // Build: g++ -O2 -ffp-contract=off -mfma -fopenmp -shared -fPIC (see oracle/build.py).
 
@@ -693,7 +693,7 @@ int orc_adjacent_similarity(const float* probs, const uint8_t* is_visual, const 
   return 0;
 }
 
-// App. B: magnitude stability of expert outputs.  l = Euclidean norm of every expert-output row
+// App. C.1: magnitude stability of expert outputs.  l = Euclidean norm of every expert-output row
 // (before the gate-weighted fusion); per modality mu, sigma (population), CV = sigma/mu and
 // V = 1/(1+CV).  row_is_visual [M]; row_norm [M] out (nullable); stats [2][4] = {mu, sigma, CV, V}
 // for text (0) and vision (1); a modality without rows, or with mu = 0, reports CV = 0, V = 1.

@@ -23,13 +23,20 @@ EXPORTS = ["fmoe_version", "fmoe_last_error", "fmoe_create", "fmoe_destroy", "fm
            "fmoe_set_weights", "fmoe_workspace_bytes", "fmoe_route", "fmoe_prune", "fmoe_permute",
            "fmoe_expert_ffn", "fmoe_combine", "fmoe_layer_forward", "fmoe_profile_enable",
            "fmoe_profile_slots", "fmoe_profile_name", "fmoe_profile_read", "fmoe_adjacent_similarity",
-           "fmoe_magnitude_stability", "fmoe_row_cosine", "fmoe_gate_cosine"]
+           "fmoe_magnitude_stability", "fmoe_row_cosine", "fmoe_gate_cosine", "fmoe_flops_ratios"]
 
 
 class FmoeConfig(C.Structure):
     _fields_ = [("d_model", C.c_int32), ("n_experts", C.c_int32), ("d_ffn", C.c_int32),
                 ("n_shared", C.c_int32), ("d_ffn_shared", C.c_int32), ("k_text", C.c_int32),
                 ("k_visual", C.c_int32), ("renormalize", C.c_int32), ("dtype", C.c_int32)]
+
+
+class FmoeFlopsModel(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_dense", C.c_int32), ("H", C.c_double), ("S", C.c_double),
+                ("S_m", C.c_double), ("E", C.c_double), ("K", C.c_double), ("K_v", C.c_double),
+                ("l_v", C.c_int32), ("n_prune", C.c_int32), ("prune_layers", C.c_int32 * 8),
+                ("beta", C.c_double), ("L_v", C.c_double)]
 
 
 class FmoePruneParams(C.Structure):
@@ -79,6 +86,7 @@ def load():
     lib.fmoe_magnitude_stability.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.fmoe_row_cosine.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     lib.fmoe_gate_cosine.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+    lib.fmoe_flops_ratios.argtypes = [C.POINTER(FmoeFlopsModel), C.POINTER(C.c_double)]
     lib.fmoe_profile_enable.argtypes = [vp, C.c_int]
     lib.fmoe_profile_slots.argtypes = []
     lib.fmoe_profile_name.argtypes = [C.c_int]
@@ -298,6 +306,21 @@ class FMoE:
         out = self._f32(max(T, 1))
         _check(self.lib.fmoe_gate_cosine(self._ctx, _ptr(gates), T, K, int(m), _ptr(out), _stream()))
         return out[:T]
+
+
+def flops_ratios(*, n_layers, H, S_m, E, K, L_v, K_v=None, l_v=None, prune_layers=(), beta=1.0, n_dense=0, S=0.0):
+    """(R_prune, R_act, R_comb) of App. E from fmoe_flops_ratios: the FLOPs left with token pruning, with
+    reduced expert activation from layer l_v on, and with both, as fractions of the unmodified model's."""
+    prune_layers = [int(p) for p in prune_layers]
+    if len(prune_layers) > 8:
+        raise ValueError("at most 8 pruning stages")
+    m = FmoeFlopsModel(n_layers=int(n_layers), n_dense=int(n_dense), H=float(H), S=float(S), S_m=float(S_m),
+                       E=float(E), K=float(K), K_v=float(K if K_v is None else K_v),
+                       l_v=int(n_layers if l_v is None else l_v), n_prune=len(prune_layers),
+                       prune_layers=(C.c_int32 * 8)(*prune_layers), beta=float(beta), L_v=float(L_v))
+    out = (C.c_double * 3)()
+    _check(load().fmoe_flops_ratios(C.byref(m), out))
+    return out[0], out[1], out[2]
 
 
 def kept_visual_lens(visual_lens, retention):

@@ -498,6 +498,48 @@ int fmoe_gate_cosine(fmoe_ctx* ctx, const float* gates, int32_t T, int32_t K, in
   return launch_gate_cosine(gates, T, K, m, out, static_cast<hipStream_t>(stream));
 }
 
+int fmoe_flops_ratios(const fmoe_flops_model* m, double* ratios) {
+  if (!m || !ratios) return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_flops_ratios: model / ratios is NULL");
+  if (m->n_layers < 1 || m->n_dense < 0 || m->n_dense > m->n_layers)
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_flops_ratios: need n_layers >= 1 and 0 <= n_dense <= n_layers (%d, %d)",
+                     m->n_layers, m->n_dense);
+  if (!(m->H > 0.0) || !(m->S_m > 0.0) || !(m->E > 0.0) || !(m->K > 0.0) || !(m->K_v >= 0.0) || !(m->L_v > 0.0) ||
+      (m->n_dense > 0 && !(m->S > 0.0)))
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_flops_ratios: H, S_m, E, K, L_v (and S with dense layers) must be positive, K_v >= 0");
+  if (!(m->beta > 0.0 && m->beta <= 1.0))
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_flops_ratios: beta %g is not in (0,1]", m->beta);
+  if (m->l_v < 0 || m->l_v > m->n_layers)
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_flops_ratios: l_v %d is not in 0..%d", m->l_v, m->n_layers);
+  if (m->n_prune < 0 || m->n_prune > 8)
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_flops_ratios: n_prune %d is not in 0..8", m->n_prune);
+  for (int s = 0; s < m->n_prune; ++s)
+    if (m->prune_layers[s] < 0 || m->prune_layers[s] >= m->n_layers || (s > 0 && m->prune_layers[s] <= m->prune_layers[s - 1]))
+      return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_flops_ratios: prune layers must ascend inside 0..%d", m->n_layers - 1);
+  // one pass over the layers, each priced at the vision length and the expert count in force there
+  const double H = m->H;
+  auto attention = [&](double x) { return 4.0 * x * x * H + 8.0 * x * H * H; };
+  auto ffn = [&](int layer, double x, double k) {
+    return layer < m->n_dense ? 6.0 * x * H * m->S : 2.0 * x * H * m->E + 6.0 * x * H * m->S_m * k;
+  };
+  double base = 0.0, pruned = 0.0, reduced = 0.0, both = 0.0, x = m->L_v;
+  int stage = 0;
+  for (int i = 0; i < m->n_layers; ++i) {
+    const double k = i >= m->l_v ? m->K_v : m->K;
+    base += attention(m->L_v) + ffn(i, m->L_v, m->K);
+    pruned += attention(x) + ffn(i, x, m->K);
+    reduced += attention(m->L_v) + ffn(i, m->L_v, k);
+    both += attention(x) + ffn(i, x, k);
+    if (stage < m->n_prune && m->prune_layers[stage] == i) {   // acts on the layers after this one
+      x *= m->beta;
+      ++stage;
+    }
+  }
+  ratios[0] = pruned / base;
+  ratios[1] = reduced / base;
+  ratios[2] = both / base;
+  return FMOE_OK;
+}
+
 int fmoe_profile_slots(void) { return SLOT_COUNT; }
 
 const char* fmoe_profile_name(int slot) {

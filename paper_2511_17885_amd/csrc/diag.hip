@@ -1,6 +1,6 @@
 // The paper's analysis statistics as device kernels (diagnostics: they read the layer's tensors and
 // feed none of its decisions): adjacent-token routing similarity (Fig. 1; Eq.8 on a two-token
-// window), magnitude stability of expert outputs (App. B), the measured cosine between two layer
+// window), magnitude stability of expert outputs (App. C.1), the measured cosine between two layer
 // outputs and the closed-form angle of App. C.  fp32 arithmetic inside a row, fp64 for the sums over
 // tokens; every reduction has a fixed order, so results are reproducible run to run.
 

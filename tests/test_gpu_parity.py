@@ -574,7 +574,7 @@ def test_magnitude_stability_and_output_angle(seed, kw):
     n, M = len(o["kept_idx"]), int(o["expert_offsets"][-1])
     m = make_layer(wl)
     x, vis, cu = inputs(wl)
-    # App. B on the routed experts' outputs of the layer (the oracle's rows, rounded to the dtype)
+    # App. C.1 on the routed experts' outputs of the layer (the oracle's rows, rounded to the dtype)
     y_rows = dev(np.asarray(o["y"], np.float32), torch_dtype(wl))
     row_vis = wl.is_visual[o["kept_idx"][o["perm_src"]]]
     o_norm, o_stats = oracle.magnitude_stability(host(y_rows), row_vis)

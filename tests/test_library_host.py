@@ -154,3 +154,47 @@ def test_switches_and_diagnostics_validate_their_arguments(lib):
     assert lib.fmoe_row_cosine(ctx, dummy, None, 4, None, dummy, None) == -2
     assert lib.fmoe_row_cosine(ctx, None, None, 0, None, None, None) == 0
     lib.fmoe_destroy(ctx)
+
+
+def test_flops_ratios_layer_loop_matches_the_closed_forms_and_the_printed_savings(lib):
+    """fmoe_flops_ratios prices the model layer by layer; the oracle evaluates App. E's stage formulas."""
+    import numpy as np
+    import oracle
+    from test_oracle_pins import FLOPS_MODELS, flops_table_rows
+    for model, keep, beta, lv, kv, saving in flops_table_rows():
+        m = dict(FLOPS_MODELS[model])
+        shared, stages = m.pop("shared"), m.pop("stage_layers")
+        n_layers = m["n_dense"] + sum(stages)
+        prune_layers = (np.cumsum(stages[:-1]) + m["n_dense"] - 1).tolist()
+        assert prune_layers == ([5, 8, 12] if model == "internvl35" else [2, 5, 8])
+        l_v = n_layers if lv is None else lv - 1 + m["n_dense"]
+        K_v = m["K"] if kv is None else kv + shared
+        got = binding.flops_ratios(n_layers=n_layers, prune_layers=prune_layers, beta=beta, l_v=l_v, K_v=K_v, **m)
+        assert round(100.0 * (1.0 - got[2]), 2) == saving
+    rng = np.random.default_rng(11)
+    for _ in range(50):
+        n_dense = int(rng.integers(0, 3))
+        stages = tuple(int(v) for v in rng.integers(1, 9, size=int(rng.integers(1, 6))))
+        n_layers = n_dense + sum(stages)
+        kw = dict(H=float(rng.integers(64, 8192)), E=float(rng.integers(4, 256)), S_m=float(rng.integers(64, 4096)),
+                  K=float(rng.integers(2, 12)), L_v=float(rng.integers(16, 20000)), n_dense=n_dense,
+                  S=float(rng.integers(256, 20000)))
+        K_v = float(rng.integers(0, int(kw["K"]) + 1))
+        l_v = int(rng.integers(0, n_layers + 1))
+        beta = float(rng.uniform(0.3, 1.0))
+        prune_layers = (np.cumsum(stages[:-1]) + n_dense - 1).tolist()
+        got = binding.flops_ratios(n_layers=n_layers, prune_layers=prune_layers, beta=beta, l_v=l_v, K_v=K_v, **kw)
+        want = oracle.flops_ratios(stages, K_v=K_v, l_v=l_v, beta=beta, **kw)
+        assert np.allclose(got, want, rtol=1e-12, atol=0.0), (stages, n_dense, l_v, got, want)
+
+
+def test_flops_ratios_validate_their_arguments(lib):
+    ok = dict(n_layers=12, H=512, S_m=256, E=16, K=4, L_v=100, prune_layers=(2, 5), beta=0.8, l_v=3, K_v=2)
+    assert all(0.0 < v <= 1.0 for v in binding.flops_ratios(**ok))
+    for bad in (dict(n_layers=0), dict(H=0), dict(beta=0.0), dict(beta=1.5), dict(l_v=13), dict(prune_layers=(5, 2)),
+                dict(prune_layers=(12,)), dict(n_dense=1, S=0.0), dict(K_v=-1), dict(L_v=0)):
+        with pytest.raises(binding.FmoeError) as e:
+            binding.flops_ratios(**{**ok, **bad})
+        assert e.value.code == -1, bad   # FMOE_ERR_INVALID_ARG
+    m = binding.FmoeFlopsModel()
+    assert lib.fmoe_flops_ratios(None, (C.c_double * 3)()) == lib.fmoe_flops_ratios(C.byref(m), None) != 0

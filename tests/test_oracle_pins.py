@@ -2,6 +2,7 @@
 (a closed form, an invariant, a textbook routine, brute force in numpy/python on tiny inputs).
 Citations are to the paper's sections / equations (Sec. 3 equations counted in order)."""
 import math
+import os
 
 import numpy as np
 import pytest
@@ -648,7 +649,7 @@ def test_adjacent_similarity_equals_exact_window_similarity_of_two_token_windows
 
 
 def test_magnitude_stability_closed_forms():
-    # App. B: V = 1/(1+CV); norms {1,3} in equal numbers: mu 2, sigma 1, CV 1/2, V 2/3
+    # App. C.1: V = 1/(1+CV); norms {1,3} in equal numbers: mu 2, sigma 1, CV 1/2, V 2/3
     y = np.zeros((6, 4), np.float32)
     y[0, 0], y[1, 1] = 1.0, -1.0
     y[2, :2], y[3, 2] = [0.0, 3.0], 3.0
@@ -774,3 +775,73 @@ def test_merge_mean_mode_is_the_numpy_mean():
         scale = np.linalg.norm(rows, axis=1).max() / np.linalg.norm(rows.mean(0))
         assert np.abs(xm2[p] - rows.mean(0) * scale).max() <= 1e-5
     assert np.array_equal(xm[is_m == 0], xm2[is_m == 0])
+
+
+# ---------------------------------------------------------------- App. E: theoretical FLOPs ratios
+# Readings the printed savings fix (the paper states neither the dimensions nor the length behind them):
+# the public dimensions of the two models, 2048 vision tokens, K counting the shared experts, the rounded
+# per-stage beta of App. D, and the tables' l_v as the ordinal of the MoE layer counted from one.
+FLOPS_MODELS = {
+    "internvl35": dict(stage_layers=(6, 3, 4, 35), H=2048, E=128, S_m=768, K=8, L_v=2048, n_dense=0, S=0.0,
+                       shared=0),
+    "deepseek_vl2": dict(stage_layers=(2, 3, 3, 21), H=2560, E=72, S_m=1536, K=8, L_v=2048, n_dense=1,
+                         S=12288, shared=2),
+}
+
+
+def flops_table_rows():
+    path = os.path.join(os.path.dirname(__file__), "golden", "flops_savings.txt")
+    rows = []
+    for ln in open(path):
+        if ln.startswith("#") or not ln.strip():
+            continue
+        model, keep, beta, lv, kv, saving, _src = ln.split()
+        rows.append((model, float(keep), float(beta), None if lv == "-" else int(lv),
+                     None if kv == "-" else int(kv), float(saving)))
+    return rows
+
+
+def test_flops_ratios_reproduce_every_saving_the_paper_prints():
+    rows = flops_table_rows()
+    assert len(rows) == 12
+    for model, keep, beta, lv, kv, saving in rows:
+        m = dict(FLOPS_MODELS[model])
+        shared = m.pop("shared")
+        stages = m.pop("stage_layers")
+        n_layers = m["n_dense"] + sum(stages)
+        if lv is None:   # pruning only
+            r_prune, r_act, r_comb = oracle.flops_ratios(stages, K_v=m["K"], l_v=n_layers, beta=beta, **m)
+            assert r_act == 1.0 and r_comb == r_prune
+            got = 100.0 * (1.0 - r_prune)
+        else:
+            l_v = lv - 1 + m["n_dense"]
+            got = 100.0 * (1.0 - oracle.flops_ratios(stages, K_v=kv + shared, l_v=l_v, beta=beta, **m)[2])
+        assert round(got, 2) == saving, (model, keep, lv, kv, got, saving)
+
+
+def test_flops_ratios_special_cases_and_limits():
+    kw = dict(H=1024, E=64, S_m=512, K=6, L_v=1000.0)
+    st = (4, 3, 5, 12)
+    # nothing switched on: every ratio is one
+    assert oracle.flops_ratios(st, K_v=6, l_v=0, beta=1.0, **kw) == (1.0, 1.0, 1.0)
+    # one switch at a time: the combined ratio is the other switch's ratio
+    rp, ra, rc = oracle.flops_ratios(st, K_v=6, l_v=3, beta=0.8, **kw)
+    assert ra == 1.0 and rc == rp
+    rp, ra, rc = oracle.flops_ratios(st, K_v=2, l_v=3, beta=1.0, **kw)
+    assert rp == 1.0 and rc == ra
+    # C(x) by hand at small integers: 4*9*2 + 8*3*4 + 2*3*2*5 + 6*3*2*7*3
+    assert oracle.flops_layer(3, 2, 5, 7, 3) == 72 + 96 + 60 + 756
+    # activation only, written out: (l_v C + (N - l_v) C') / (N C)
+    N = sum(st)
+    c, cp = oracle.flops_layer(1000, 1024, 64, 512, 6), oracle.flops_layer(1000, 1024, 64, 512, 2)
+    assert np.isclose(ra, (3 * c + (N - 3) * cp) / (N * c), rtol=1e-14)
+    # a very wide model is linear in the length, a very long sequence quadratic (attention only)
+    beta = 0.7
+    wide = oracle.flops_ratios(st, H=1e12, E=64, S_m=512, K=6, K_v=6, l_v=N, beta=beta, L_v=10.0)[0]
+    assert np.isclose(wide, sum(n * beta ** s for s, n in enumerate(st)) / N, rtol=1e-9)
+    long_ = oracle.flops_ratios(st, H=8, E=1, S_m=1, K=1, K_v=1, l_v=N, beta=beta, L_v=1e12)[0]
+    assert np.isclose(long_, sum(n * beta ** (2 * s) for s, n in enumerate(st)) / N, rtol=1e-9)
+    # a dense first layer is never pruned or reduced: it only dilutes the savings
+    with_dense = oracle.flops_ratios(st, K_v=2, l_v=0, beta=0.8, n_dense=1, S=4096, **kw)
+    without = oracle.flops_ratios(st, K_v=2, l_v=0, beta=0.8, **kw)
+    assert all(a > b for a, b in zip(with_dense, without))
