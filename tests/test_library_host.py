@@ -198,3 +198,13 @@ def test_flops_ratios_validate_their_arguments(lib):
         assert e.value.code == -1, bad   # FMOE_ERR_INVALID_ARG
     m = binding.FmoeFlopsModel()
     assert lib.fmoe_flops_ratios(None, (C.c_double * 3)()) == lib.fmoe_flops_ratios(C.byref(m), None) != 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU's throughput; asked for more it says so and exits before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
