@@ -377,6 +377,43 @@ def test_layer_forward_merge_rejects_router_only_mode():
         m.layer_forward(x, vis, cu, binding.prune_params(retention=0.5, window=3, gamma=0.1, prune_mode=2))
 
 
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+@pytest.mark.parametrize("B", [0, 3])
+def test_empty_batch(dtype, B):
+    """No tokens at all (no sequences, or sequences that are all empty): every entry point returns without
+    work, the fused layer reports zero kept tokens per sequence, and a normal batch run right after on the
+    same context is unaffected."""
+    wl = _wl(108 if dtype == W.BF16 else 101, SMALL[8 if dtype == W.BF16 else 1].values[1])
+    m = make_layer(wl)
+    td = torch_dtype(wl)
+    x0 = torch.empty((0, wl.d), dtype=td, device="cuda")
+    vis0 = torch.empty(0, dtype=torch.uint8, device="cuda")
+    cu0 = torch.zeros(B + 1, dtype=torch.int32, device="cuda")
+    for pp in (None, binding.prune_params(retention=0.5, window=3),
+               binding.prune_params(retention=0.5, window=3, gamma=0.1)):
+        new_cu = torch.full((B + 1,), 7, dtype=torch.int32, device="cuda")
+        m.layer_forward(x0, vis0, cu0, pp, new_cu=new_cu)
+        torch.cuda.synchronize()
+        assert not host(new_cu).any()
+    probs, idx, gate = m.route(x0, vis0)
+    assert probs.shape[0] == 0 and idx.shape[0] == 0
+    kept, new_cu, _ = m.prune(binding.prune_params(retention=0.5, window=3), probs, vis0, cu0)
+    offs, perm, inv = m.permute(idx.contiguous(), None, 0)
+    torch.cuda.synchronize()
+    assert not host(new_cu).any() and not host(offs).any()
+    y, ysh = m.expert_ffn(x0, None, 0, offs, perm)
+    m.combine(y, ysh, inv, gate.contiguous(), None, 0)
+    torch.cuda.synchronize()
+    # the context still works
+    x, vis, cu = inputs(wl)
+    out, kept, new_cu, _ = m.layer_forward(x, vis, cu, binding.prune_params(retention=wl.retention, window=wl.window))
+    torch.cuda.synchronize()
+    o = _oracle(wl)
+    n = int(host(new_cu)[-1])
+    assert np.array_equal(host(kept)[:n], o["kept_idx"])
+    assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
+
+
 # ---------------------------------------------------------------- the benchmark configurations
 def _check_config(wl, sample=None, seed=0):
     """Decisions on every token; outputs on every kept token, or on a sample of them evaluated
