@@ -748,6 +748,30 @@ def test_randomized_layer_sweep(seed):
         assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype], (kw, extra)
 
 
+@pytest.mark.parametrize("T_v,T_t,window", [
+    ([4096], [0], 4),        # 4096 tokens, 1024 windows: the largest batch of the single-workgroup dispatch kernel
+    ([4095], [1], 4),        # 1024 windows, the last one short
+    ([4092], [4], 3),        # 1364 windows in one sequence: the general kernels, although T = 4096
+    ([4096], [1], 4),        # one token more than the single-workgroup kernel takes
+    ([1024, 1024, 1024, 1020], [1, 1, 1, 1], 1),   # W = 1: every visual token is a window of its own
+])
+def test_layer_forward_at_the_small_batch_limits(T_v, T_t, window):
+    """Both sides of the size limits that decide between the single-workgroup prune/dispatch kernel and the
+    general kernel chain give the oracle's kept set, permutation and outputs."""
+    wl = W.small_random(4242, T_v=T_v, T_t=T_t, d=64, E=16, F=32, k_text=3, k_visual=2, retention=0.6,
+                        window=window, dtype=W.F32, bias_std=1.0, n_components=24)
+    o = _oracle(wl)
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    out, kept, new_cu, _ = m.layer_forward(x, vis, cu, binding.prune_params(retention=wl.retention, window=window))
+    torch.cuda.synchronize()
+    new_cu = host(new_cu)
+    n = int(new_cu[-1])
+    assert np.array_equal(new_cu, o["new_cu_seqlens"])
+    assert np.array_equal(host(kept)[:n], o["kept_idx"])
+    assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
+
+
 @pytest.mark.parametrize("d,F", [(448, 576), (576, 640), (640, 704), (832, 960), (960, 448)])
 def test_expert_ffn_k_loop_lengths(d, F):
     # bf16 expert GEMMs at reduction lengths of 7..15 k-tiles of 64: every combination of steady-loop
