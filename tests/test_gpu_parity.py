@@ -772,6 +772,25 @@ def test_layer_forward_at_the_small_batch_limits(T_v, T_t, window):
     assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
 
 
+def test_layer_forward_general_chain_at_the_widest_routing():
+    """The largest expert count and top-k the library takes (256 experts, 16 per text token), shared experts,
+    bf16, several ragged sequences and more tokens than the single-workgroup kernel handles."""
+    wl = W.small_random(5151, T_v=[2500, 1, 1800, 700], T_t=[40, 3, 0, 77], d=96, E=256, F=40, k_text=16, k_visual=7,
+                        retention=0.4, window=5, dtype=W.BF16, n_shared=2, F_shared=24, bias_std=1.0, n_components=40)
+    assert wl.T > 4096
+    o = _oracle(wl, add_residual=True)
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    out, kept, new_cu, _ = m.layer_forward(x, vis, cu, binding.prune_params(retention=wl.retention, window=wl.window),
+                                           add_residual=True)
+    torch.cuda.synchronize()
+    new_cu = host(new_cu)
+    n = int(new_cu[-1])
+    assert np.array_equal(new_cu, o["new_cu_seqlens"])
+    assert np.array_equal(host(kept)[:n], o["kept_idx"])
+    assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
+
+
 @pytest.mark.parametrize("d,F", [(448, 576), (576, 640), (640, 704), (832, 960), (960, 448)])
 def test_expert_ffn_k_loop_lengths(d, F):
     # bf16 expert GEMMs at reduction lengths of 7..15 k-tiles of 64: every combination of steady-loop
