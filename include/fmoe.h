@@ -15,7 +15,9 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *    enqueued asynchronously on it; no call synchronises with the host and no hot call
  *    (route / prune / permute / expert_ffn / combine / layer_forward) allocates memory.
- *    Scratch comes from a caller-provided workspace sized by fmoe_workspace_bytes().
+ *    Scratch comes from a caller-provided workspace sized by fmoe_workspace_bytes().  A hot call
+ *    is a sequence of kernel launches and nothing else (no memset, no copy), so it can be
+ *    captured into a HIP graph on `stream` and replayed.
  *  - Data-dependent counts (tokens kept, rows per expert) stay on the device:
  *    new_cu_seqlens[B] holds the number of kept tokens T'; expert_offsets[E] holds the number
  *    of routed rows M.

@@ -414,6 +414,37 @@ def test_empty_batch(dtype, B):
     assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
 
 
+@pytest.mark.parametrize("gamma", [0.0, 0.3])
+def test_layer_forward_replays_from_a_captured_graph(gamma):
+    """The fused layer is kernel launches only (no allocation, no host synchronisation, no memset), so a
+    caller can capture it into a graph.  Every replay, with eager work and synchronisations of the
+    program in between, must give the eager call's result bit for bit."""
+    wl = _wl(108, SMALL[8].values[1])
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    pp = binding.prune_params(retention=wl.retention, window=wl.window, gamma=gamma)
+    out_e, kept_e, cu_e, _ = m.layer_forward(x, vis, cu, pp, add_residual=True)   # also sizes the workspace
+    torch.cuda.synchronize()
+    n = int(host(cu_e)[-1])
+    ref_out, ref_kept, ref_cu = host(out_e)[:n].copy(), host(kept_e)[:n].copy(), host(cu_e).copy()
+    out_g, kept_g, cu_g = torch.empty_like(out_e), torch.empty_like(kept_e), torch.empty_like(cu_e)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        m.layer_forward(x, vis, cu, pp, add_residual=True, out=out_g, kept_idx=kept_g, new_cu=cu_g)
+    for rep in range(4):
+        out_g.fill_(float("nan"))
+        kept_g.fill_(-1)
+        cu_g.fill_(-1)
+        junk = (x.float() * (rep + 1)).sum()   # eager work of the program between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.isfinite(float(junk))
+        assert np.array_equal(host(cu_g), ref_cu), rep
+        assert np.array_equal(host(kept_g)[:n], ref_kept), rep
+        assert np.array_equal(host(out_g)[:n], ref_out), rep
+
+
 # ---------------------------------------------------------------- the benchmark configurations
 def _check_config(wl, sample=None, seed=0):
     """Decisions on every token; outputs on every kept token, or on a sample of them evaluated
