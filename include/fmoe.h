@@ -129,9 +129,18 @@ int fmoe_set_selection(fmoe_ctx* ctx, int32_t strategy, int32_t k_base, uint64_t
  * before the softmax); w_gate, w_up [E,S_m,H]; w_down [E,H,S_m]; ws_gate, ws_up
  * [N_s,S_s,H]; ws_down [N_s,H,S_s] (NULL iff N_s == 0).  An expert is the three-matrix gated
  * FFN  y = W_down (silu(W_gate x) * (W_up x))  without biases (flop model of App. E).
- * The router matrix is copied once into a private fp32 buffer laid out for the router kernel
- * (E*H*4 bytes rounded up to 16x16 blocks; the only device allocation the library makes, on
- * the first call, freed by fmoe_destroy); the other weights are used in place. */
+ * Device allocations (the only ones the library makes; made on the first call, reused by later calls
+ * on the same context, freed by fmoe_destroy):
+ *  - a private fp32 copy of the router matrix in the router kernel's operand order (E*H*4 bytes
+ *    rounded up to 16x16 blocks and whole 128-wide k chunks);
+ *  - bf16 contexts only: private copies of all expert weights (routed and shared) in matrix-core
+ *    operand order, the same total size as the originals up to zero padding of the reduction
+ *    length to 64 and of the output columns to 64 (gate/up) / 128 (down).  The expert GEMMs of a
+ *    bf16 context read ONLY these copies: the caller's expert tensors may be freed or changed after
+ *    the call returns and the stream has drained, and a later change to them has no effect until
+ *    fmoe_set_weights is called again.  A bf16 layer therefore holds its expert weights twice while
+ *    the caller keeps the originals.
+ * fp32 contexts keep borrowing w_gate .. ws_down until the next call or fmoe_destroy. */
 int fmoe_set_weights(fmoe_ctx* ctx, const void* router_w, const float* router_bias,
                      const void* w_gate, const void* w_up, const void* w_down,
                      const void* ws_gate, const void* ws_up, const void* ws_down, void* stream);
@@ -151,7 +160,9 @@ int fmoe_route(fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int32_t T
                int32_t* topk_idx, float* topk_gate, void* stream);
 
 /* Sec. 3.2: window redundancy scores, budget, drop, compaction -- per sequence.
- * probs [T,E] fp32 from fmoe_route; cu_seqlens [B+1] int32 (cu[0] = 0, cu[B] = T).
+ * probs [T,E] fp32 from fmoe_route; cu_seqlens [B+1] int32 (cu[0] = 0, cu[B] = T; T > 0 with
+ * B == 0 is FMOE_ERR_INVALID_ARG; should cu[B] be below T on the device, the tokens past it are in
+ * no sequence: they are never pruned and lie beyond new_cu_seqlens[B]).
  * attn_importance [T] fp32 or NULL: per-token attention importance (Eq.7); when given, windows
  * are dropped in the order (normalised window attention ascending, score descending, index
  * ascending), otherwise (score descending, index ascending).
@@ -220,12 +231,69 @@ int fmoe_combine(fmoe_ctx* ctx, const void* y, const void* y_shared, const int32
  * therefore run the experts on the kept tokens only.
  * Window merging (params->gamma > 0; prune_mode 1 only, FMOE_ERR_UNSUPPORTED otherwise): the rows of
  * x are merged (fmoe_prune's x_merged), every kept token is routed again on the merged input, the
- * experts run on it and add_residual adds the merged rows. */
+ * experts run on it and add_residual adds the merged rows.
+ * bf16: x (T*H*2 bytes) and the hidden buffers (T*Kmax*S_m*2, T*N_s*S_s*2 bytes) must each stay
+ * below 4 GiB, else FMOE_ERR_UNSUPPORTED (32-bit row offsets in the expert GEMMs).  T > 0 with
+ * B == 0 is FMOE_ERR_INVALID_ARG. */
 int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const void* x,
                        const uint8_t* is_visual, const int32_t* cu_seqlens, int32_t B, int32_t T,
                        const float* attn_importance, int add_residual, void* out,
                        int32_t* kept_idx, int32_t* new_cu_seqlens, uint8_t* is_visual_out,
                        void* ws, size_t ws_bytes, void* stream);
+
+/* ---- the layer stack: per-layer expert activation (Sec. 3.1) and pruning stages (Sec. 3.2, App. D) ----
+ *
+ * fmoe_kept_counts [host arithmetic only] -- the token budget of Sec. 3.2.3 per sequence: a pruning
+ * stage with retention r keeps eta_b = floor(r*N_v,b + 1/2) visual tokens of sequence b, clamped to
+ * [min(1,N_v,b), N_v,b] (r is taken at fp32 precision and the product in fp64, exactly as the kernels
+ * do), and every text token.  visual_lens [B] host in, kept_visual_lens [B] host out (may alias).
+ * Because the rule keeps an exact count, a caller can size every later call without reading the device.
+ * FMOE_ERR_INVALID_ARG for r outside (0,1], B < 0 or a negative length.
+ *
+ * fmoe_stage_retention [host arithmetic only] -- App. D: a cumulative retain ratio r reached in
+ * `stages` pruning stages of equal per-stage ratio beta = r^(1/stages); *beta is the fp32 value the
+ * stages are run with.  FMOE_ERR_INVALID_ARG for r outside (0,1] or stages < 1. */
+int fmoe_kept_counts(const int32_t* visual_lens, int32_t B, float retention, int32_t* kept_visual_lens);
+int fmoe_stage_retention(float retention, int32_t stages, float* beta);
+
+/* What one layer of a stack does: its experts per token (Sec. 3.1: K for every token below layer
+ * l_v, K_v for visual tokens from l_v on) and its pruning stage, if any (prune.prune_mode == 0 or
+ * prune.retention == 1: none). */
+typedef struct {
+  int32_t k_text, k_visual;
+  fmoe_prune_params prune;
+} fmoe_layer_plan;
+
+/* Fill plan[n_layers] [host]: k = (K, K) in layers below l_v and (K, K_v) from l_v on (l_v = n_layers:
+ * never reduced); a pruning stage in each of the n_stages layers prune_layers[] (ascending, 0-based; the
+ * stage acts inside that layer, after its routing, so the layers after it see the shorter sequence),
+ * each with the fields of *stage except retention, which becomes the per-stage ratio
+ * fmoe_stage_retention(stage->retention, n_stages).  stage may be NULL iff n_stages == 0. */
+int fmoe_stack_plan(int32_t n_layers, int32_t K, int32_t K_v, int32_t l_v, const int32_t* prune_layers,
+                    int32_t n_stages, const fmoe_prune_params* stage, fmoe_layer_plan* plan);
+
+/* Workspace bytes of fmoe_stack_forward for a batch of up to max_tokens tokens in max_seqs sequences
+ * (two activation buffers, masks, index lists, plus the largest per-layer workspace of the plan). [host] */
+size_t fmoe_stack_workspace_bytes(fmoe_ctx* const* layers, const fmoe_layer_plan* plan, int32_t n_layers,
+                                  int32_t max_tokens, int32_t max_seqs);
+
+/* x <- x + MoE_l(x) for l = 0 .. n_layers-1, every layer one fmoe_layer_forward with add_residual on
+ * the context layers[l] (all of one d_model, dtype and device; weights set), its top-k switched to
+ * plan[l] with fmoe_set_topk and plan[l].prune as its pruning stage.  Kernel launches only: the token
+ * count handed to the layers after a stage comes from fmoe_kept_counts on visual_lens / text_lens
+ * [B] [host], the per-sequence token counts of the input batch (their sum must be T).
+ * attn [n_layers] [host array of device pointers] or NULL: attn[l] = attention importance [T_l] for the
+ * stage of layer l (Eq.7), NULL entries = none.
+ * out [T capacity, d_model]: the first *n_out rows are the stack's output; kept_idx [T capacity]: for
+ * each output row the index of its token in the input batch (identity without pruning);
+ * new_cu_seqlens [B+1]; is_visual_out [T capacity] or NULL; n_out [host] or NULL: rows of out, known
+ * on the host from the budget rule.  x is not modified.  The contexts' k_text / k_visual are left at
+ * the last layer's plan. */
+int fmoe_stack_forward(fmoe_ctx* const* layers, const fmoe_layer_plan* plan, int32_t n_layers,
+                       const void* x, const uint8_t* is_visual, const int32_t* cu_seqlens,
+                       const int32_t* visual_lens, const int32_t* text_lens, int32_t B, int32_t T,
+                       const float* const* attn, void* out, int32_t* kept_idx, int32_t* new_cu_seqlens,
+                       uint8_t* is_visual_out, int32_t* n_out, void* ws, size_t ws_bytes, void* stream);
 
 /* Instrumentation (not part of the paper's path): per-kernel GPU time of the most recent hot
  * call.  fmoe_profile_enable(ctx,1) creates one HIP event pair per kernel slot and makes every

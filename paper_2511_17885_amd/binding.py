@@ -7,7 +7,6 @@ been built, loading raises.
 from __future__ import annotations
 
 import ctypes as C
-import math
 import os
 from typing import Optional
 
@@ -23,7 +22,9 @@ EXPORTS = ["fmoe_version", "fmoe_last_error", "fmoe_create", "fmoe_destroy", "fm
            "fmoe_set_weights", "fmoe_workspace_bytes", "fmoe_route", "fmoe_prune", "fmoe_permute",
            "fmoe_expert_ffn", "fmoe_combine", "fmoe_layer_forward", "fmoe_profile_enable",
            "fmoe_profile_slots", "fmoe_profile_name", "fmoe_profile_read", "fmoe_adjacent_similarity",
-           "fmoe_magnitude_stability", "fmoe_row_cosine", "fmoe_gate_cosine", "fmoe_flops_ratios"]
+           "fmoe_magnitude_stability", "fmoe_row_cosine", "fmoe_gate_cosine", "fmoe_flops_ratios",
+           "fmoe_kept_counts", "fmoe_stage_retention", "fmoe_stack_plan", "fmoe_stack_workspace_bytes",
+           "fmoe_stack_forward"]
 
 
 class FmoeConfig(C.Structure):
@@ -43,6 +44,10 @@ class FmoePruneParams(C.Structure):
     _fields_ = [("retention", C.c_float), ("window", C.c_int32), ("alpha", C.c_float),
                 ("gamma", C.c_float), ("sim_mode", C.c_int32), ("prune_mode", C.c_int32),
                 ("merge_mode", C.c_int32)]
+
+
+class FmoeLayerPlan(C.Structure):
+    _fields_ = [("k_text", C.c_int32), ("k_visual", C.c_int32), ("prune", FmoePruneParams)]
 
 
 class FmoeError(RuntimeError):
@@ -87,6 +92,15 @@ def load():
     lib.fmoe_row_cosine.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     lib.fmoe_gate_cosine.argtypes = [vp, vp, i32, i32, i32, vp, vp]
     lib.fmoe_flops_ratios.argtypes = [C.POINTER(FmoeFlopsModel), C.POINTER(C.c_double)]
+    i32p = C.POINTER(C.c_int32)
+    lib.fmoe_kept_counts.argtypes = [i32p, i32, C.c_float, i32p]
+    lib.fmoe_stage_retention.argtypes = [C.c_float, i32, C.POINTER(C.c_float)]
+    lib.fmoe_stack_plan.argtypes = [i32, i32, i32, i32, i32p, i32, C.POINTER(FmoePruneParams),
+                                    C.POINTER(FmoeLayerPlan)]
+    lib.fmoe_stack_workspace_bytes.argtypes = [C.POINTER(vp), C.POINTER(FmoeLayerPlan), i32, i32, i32]
+    lib.fmoe_stack_workspace_bytes.restype = sz
+    lib.fmoe_stack_forward.argtypes = [C.POINTER(vp), C.POINTER(FmoeLayerPlan), i32, vp, vp, vp, i32p, i32p,
+                                       i32, i32, C.POINTER(vp), vp, vp, vp, vp, i32p, vp, sz, vp]
     lib.fmoe_profile_enable.argtypes = [vp, C.c_int]
     lib.fmoe_profile_slots.argtypes = []
     lib.fmoe_profile_name.argtypes = [C.c_int]
@@ -94,7 +108,7 @@ def load():
     lib.fmoe_profile_read.argtypes = [vp, C.POINTER(C.c_float)]
     for name in EXPORTS:
         if name not in ("fmoe_version", "fmoe_last_error", "fmoe_destroy", "fmoe_workspace_bytes",
-                        "fmoe_profile_name"):
+                        "fmoe_profile_name", "fmoe_stack_workspace_bytes"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -324,69 +338,86 @@ def flops_ratios(*, n_layers, H, S_m, E, K, L_v, K_v=None, l_v=None, prune_layer
 
 
 def kept_visual_lens(visual_lens, retention):
-    """Per-sequence visual token counts after one pruning stage, on the host: eta_b = floor(r*N_v + 1/2)
-    clamped to [min(1,N_v), N_v] (Sec. 3.2.3).  `retention` is taken at fp32 precision, as the library
-    receives it.  Pure integer bookkeeping that lets a caller size the next layer's call without
-    reading the device."""
-    r = C.c_float(float(retention)).value
-    out = []
-    for nv in visual_lens:
-        eta = int(math.floor(r * nv + 0.5))
-        out.append(min(max(eta, min(1, nv)), nv))
-    return out
+    """Per-sequence visual token counts after one pruning stage (fmoe_kept_counts: the budget rule of
+    Sec. 3.2.3 on the host), which lets a caller size the next layer's call without reading the device."""
+    n = len(visual_lens)
+    src = (C.c_int32 * max(n, 1))(*[int(v) for v in visual_lens])
+    dst = (C.c_int32 * max(n, 1))()
+    _check(load().fmoe_kept_counts(src, n, float(retention), dst))
+    return [int(dst[b]) for b in range(n)]
 
 
 def kept_count(visual_lens, text_lens, retention):
-    """T' of a pruned batch, on the host: every sequence keeps eta_b visual tokens (kept_visual_lens)
-    and all its text tokens."""
+    """T' of a pruned batch, on the host: every sequence keeps its budget of visual tokens
+    (kept_visual_lens) and all its text tokens."""
     return sum(kept_visual_lens(visual_lens, retention)) + sum(text_lens)
 
 
-def stage_schedule(retention, prune_layers, **prune_kw):
-    """App. D: a cumulative retain ratio r reached in len(prune_layers) stages of equal per-stage ratio
-    beta = r^(1/stages).  Returns {layer: prune params with retention = beta}; the other fields
-    (window, alpha, gamma, sim_mode, prune_mode) are shared by the stages."""
-    stages = len(prune_layers)
-    beta = float(retention) ** (1.0 / stages) if stages else 1.0
-    return {int(l): prune_params(retention=beta, **prune_kw) for l in prune_layers}
+def stage_retention(retention, stages):
+    """App. D (fmoe_stage_retention): the per-stage ratio beta of `stages` equal stages reaching `retention`."""
+    beta = C.c_float()
+    _check(load().fmoe_stage_retention(float(retention), int(stages), C.byref(beta)))
+    return beta.value
+
+
+def stage_schedule(retention, prune_layers, window=1, alpha=1.0, gamma=0.0, sim_mode=0, prune_mode=1,
+                   merge_mode=0):
+    """{layer: prune params} of a multi-stage schedule: every listed layer runs a stage with the
+    per-stage ratio of App. D; the other fields are shared by the stages."""
+    beta = stage_retention(retention, len(prune_layers)) if len(prune_layers) else 1.0
+    return {int(l): prune_params(beta, window, alpha, gamma, sim_mode, prune_mode, merge_mode)
+            for l in prune_layers}
 
 
 class FMoEStack:
     """A stack of MoE layers with x <- x + MoE_l(x), per-layer (k_text, k_visual) (Sec. 3.1: reduced
-    activation from layer l_v on) and pruning stages at chosen layers (Sec. 3.2; App. D: several stages
-    of equal per-stage ratio).  Host-side sequencing only: every layer is one fmoe_layer_forward
-    enqueue; the token count handed to the layers after a pruning stage comes from
-    `kept_visual_lens`, so nothing is read back from the device."""
+    activation from layer l_v on) and pruning stages at chosen layers (Sec. 3.2; App. D).  One
+    fmoe_stack_forward call: the sequencing, the budget bookkeeping and the index composition all
+    happen inside the library."""
 
     def __init__(self, layers, k_schedule, prune_after_layer=None, params=None, prune_schedule=None):
         self.layers = list(layers)
-        self.k_schedule = [tuple(k) for k in k_schedule]
-        self.prune_schedule = dict(prune_schedule or {})
+        sched = dict(prune_schedule or {})
         if prune_after_layer is not None and params is not None:
-            self.prune_schedule[int(prune_after_layer)] = params
-        assert len(self.layers) == len(self.k_schedule)
+            sched[int(prune_after_layer)] = params
+        assert len(self.layers) == len(k_schedule)
+        n = len(self.layers)
+        self.plan = (FmoeLayerPlan * n)()
+        for l, (kt, kv) in enumerate(k_schedule):
+            self.plan[l].k_text, self.plan[l].k_visual = int(kt), int(kv)
+            self.plan[l].prune = sched.get(l, prune_params(retention=1.0, window=1, prune_mode=0))
+        self._ctxs = (C.c_void_p * n)(*[m._ctx.value for m in self.layers])
+        self._ws = None
 
-    def forward(self, x, is_visual, cu_seqlens, visual_lens, text_lens, attn=None):
+    def workspace_bytes(self, max_tokens, max_seqs):
+        return int(load().fmoe_stack_workspace_bytes(self._ctxs, self.plan, len(self.layers), max_tokens, max_seqs))
+
+    def forward(self, x, is_visual, cu_seqlens, visual_lens, text_lens, attn=None, out=None, kept_idx=None,
+                new_cu=None):
         """visual_lens / text_lens: per-sequence token counts on the host.  attn: {layer: importance
         [T at that layer]} for stages that use the attention term.  Returns (x_out [T', d], kept_idx
-        [T'] indices into the input batch or None, new_cu_seqlens)."""
-        T = x.shape[0]
-        kept_total = None
-        visual_lens = list(visual_lens)
-        for l, layer in enumerate(self.layers):
-            layer.set_topk(*self.k_schedule[l])
-            params = self.prune_schedule.get(l)
-            if params is not None:
-                a = attn.get(l) if attn else None
-                out, kept, new_cu, vis_out = layer.layer_forward(x, is_visual, cu_seqlens, params, attn=a,
-                                                                 add_residual=True, want_mask=True)
-                if params.prune_mode != 0 and params.retention < 1.0:
-                    visual_lens = kept_visual_lens(visual_lens, params.retention)
-                T = sum(visual_lens) + sum(text_lens)
-                x, is_visual, cu_seqlens = out[:T], vis_out[:T], new_cu
-                # index bookkeeping across stages: positions in the input batch of what is still there
-                kept_total = kept[:T] if kept_total is None else kept_total[kept[:T].long()]
-            else:
-                out, _, _, _ = layer.layer_forward(x, is_visual, cu_seqlens, None, add_residual=True)
-                x = out[:T]
-        return x, kept_total, cu_seqlens
+        [T'] indices into the input batch, new_cu_seqlens)."""
+        m0 = self.layers[0]
+        T, B, n = x.shape[0], cu_seqlens.shape[0] - 1, len(self.layers)
+        need = self.workspace_bytes(T, B)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=m0.device)
+        if out is None:
+            out = torch.empty((max(T, 1), m0.d), dtype=m0.torch_dtype, device=m0.device)
+        if kept_idx is None:
+            kept_idx = torch.empty(max(T, 1), dtype=torch.int32, device=m0.device)
+        if new_cu is None:
+            new_cu = torch.empty(B + 1, dtype=torch.int32, device=m0.device)
+        nv = (C.c_int32 * max(B, 1))(*[int(v) for v in visual_lens])
+        nt = (C.c_int32 * max(B, 1))(*[int(v) for v in text_lens])
+        attn_ptrs = None
+        if attn:
+            attn_ptrs = (C.c_void_p * n)(*[attn[l].data_ptr() if attn.get(l) is not None else None
+                                           for l in range(n)])
+        n_out = C.c_int32()
+        _check(load().fmoe_stack_forward(self._ctxs, self.plan, n, _ptr(x), _ptr(is_visual), _ptr(cu_seqlens),
+                                         nv, nt, B, T, attn_ptrs, _ptr(out), _ptr(kept_idx), _ptr(new_cu), None,
+                                         C.byref(n_out), _ptr(self._ws), self._ws.numel(), _stream()))
+        for l, m in enumerate(self.layers):   # the contexts' top-k now is the last layer's plan
+            m.cfg.k_text, m.cfg.k_visual = self.plan[l].k_text, self.plan[l].k_visual
+        return out[:n_out.value], kept_idx[:n_out.value], new_cu

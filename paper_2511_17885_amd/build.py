@@ -26,6 +26,7 @@ SOURCES = {
     "ffn.hip": [],
     "combine.hip": [],
     "diag.hip": [],
+    "stack.hip": [],
 }
 
 

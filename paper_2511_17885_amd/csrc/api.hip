@@ -1,6 +1,6 @@
 // C-ABI entry points: argument validation, workspace carve-up, kernel sequencing.
-// No entry point other than fmoe_set_weights (private router copy) allocates device memory, and
-// none synchronises with the host.
+// No entry point other than fmoe_set_weights (private router copy; packed expert weights of bf16
+// contexts) allocates device memory, and none synchronises with the host.
 
 #include <cstdarg>
 #include <cstdio>
@@ -66,6 +66,20 @@ int check_prune(const fmoe_prune_params* p) {
     return fmoe_fail(FMOE_ERR_INVALID_ARG, "prune: sim_mode %d", p->sim_mode);
   if (p->prune_mode < 0 || p->prune_mode > 2)
     return fmoe_fail(FMOE_ERR_INVALID_ARG, "prune: prune_mode %d", p->prune_mode);
+  return FMOE_OK;
+}
+
+// bf16 expert GEMMs address activation rows with 32-bit byte offsets into one buffer descriptor: the
+// layer input of n tokens and the hidden buffers of n tokens' rows must each stay below 4 GiB.
+int check_ffn_extent(const fmoe_ctx* ctx, int32_t n, const char* who) {
+  if (ctx->cfg.dtype != FMOE_BF16) return FMOE_OK;
+  const fmoe_config& c = ctx->cfg;
+  const size_t lim = 0xffffffffull;
+  const size_t kmax = ctx->kmax > 0 ? (size_t)ctx->kmax : 0;
+  if ((size_t)n * c.d_model * 2 > lim)
+    return fmoe_fail(FMOE_ERR_UNSUPPORTED, "%s: an activation tensor of %d tokens exceeds 4 GiB", who, n);
+  if ((size_t)n * kmax * c.d_ffn * 2 > lim || (size_t)n * c.n_shared * c.d_ffn_shared * 2 > lim)
+    return fmoe_fail(FMOE_ERR_UNSUPPORTED, "%s: a hidden buffer of %d tokens' rows exceeds 4 GiB", who, n);
   return FMOE_OK;
 }
 
@@ -267,6 +281,7 @@ int fmoe_prune(fmoe_ctx* ctx, const fmoe_prune_params* params, const float* prob
   if ((rc = check_prune(params)) != FMOE_OK) return rc;
   if ((rc = check_tokens(T)) != FMOE_OK) return rc;
   if (B < 0) return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_prune: B %d is negative", B);
+  if (T > 0 && B == 0) return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_prune: %d tokens but no sequence", T);
   if (!cu_seqlens || !new_cu_seqlens) return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_prune: cu_seqlens / new_cu_seqlens is NULL");
   if (T > 0 && (!probs || !is_visual || !kept_idx))
     return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_prune: probs / is_visual / kept_idx is NULL");
@@ -303,9 +318,11 @@ int fmoe_expert_ffn(fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, int32
                     const int32_t* n_kept_dev, const int32_t* expert_offsets,
                     const int32_t* perm_src, void* y, void* y_shared, void* ws, size_t ws_bytes,
                     void* stream) {
-  int rc = check_ctx(ctx, true);
+  int rc = check_ctx(ctx, false);
   if (rc != FMOE_OK) return rc;
   if ((rc = check_tokens(n_kept)) != FMOE_OK) return rc;
+  if ((rc = check_ffn_extent(ctx, n_kept, "fmoe_expert_ffn")) != FMOE_OK) return rc;
+  if ((rc = check_ctx(ctx, true)) != FMOE_OK) return rc;
   if (n_kept == 0) return FMOE_OK;
   if (!x) return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_expert_ffn: x is NULL");
   if (ctx->kmax > 0 && (!expert_offsets || !perm_src || !y))
@@ -344,18 +361,19 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
                        const float* attn_importance, int add_residual, void* out,
                        int32_t* kept_idx, int32_t* new_cu_seqlens, uint8_t* is_visual_out,
                        void* ws, size_t ws_bytes, void* stream) {
-  int rc = check_ctx(ctx, true);
+  int rc = check_ctx(ctx, false);
   if (rc != FMOE_OK) return rc;
   if ((rc = check_tokens(T)) != FMOE_OK) return rc;
+  if ((rc = check_ffn_extent(ctx, T, "fmoe_layer_forward")) != FMOE_OK) return rc;
+  if ((rc = check_ctx(ctx, true)) != FMOE_OK) return rc;
   if (B < 0) return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_layer_forward: B %d is negative", B);
+  if (T > 0 && B == 0) return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_layer_forward: %d tokens but no sequence", T);
   if (!cu_seqlens || !new_cu_seqlens)
     return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_layer_forward: cu_seqlens / new_cu_seqlens is NULL");
   if (T > 0 && (!x || !is_visual || !out || !kept_idx))
     return fmoe_fail(FMOE_ERR_NULL_PTR, "fmoe_layer_forward: x / is_visual / out / kept_idx is NULL");
   if (!aligned16(x) || !aligned16(out))
     return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_layer_forward: x / out not 16-byte aligned");
-  if (ctx->cfg.dtype == FMOE_BF16 && (size_t)T * ctx->cfg.d_model * 2 > 0xffffffffull)
-    return fmoe_fail(FMOE_ERR_UNSUPPORTED, "fmoe_layer_forward: x of %d tokens exceeds 4 GiB", T);
   const bool do_prune = params && params->prune_mode != 0 && params->retention < 1.0f;
   if (params && (rc = check_prune(params)) != FMOE_OK) return rc;
   if ((rc = check_ws(ctx, ws, ws_bytes, T, B)) != FMOE_OK) return rc;

@@ -304,6 +304,7 @@ __global__ __launch_bounds__(1024) void compact_kernel(
   __syncthreads();
   const int32_t* cuc = cached ? s_cu : cu;   // clamping a clamped bound changes nothing
   const int32_t* nvc = cached ? s_nv : seq_nv;
+  const int t_end = clampi(cuc[B], 0, T);
   const bool merging = gamma > 0.0f;
   const bool closed = merging && win_merged == nullptr;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -313,7 +314,8 @@ __global__ __launch_bounds__(1024) void compact_kernel(
 #pragma unroll
     for (int q = 0; q < CQ; ++q) {
       const int t = base + q * 1024 + threadIdx.x;
-      ord_q[q] = (t < T) ? vis_ord[t] : -2;   // -2: past the end, -1: text
+      // -2: past the end, -1: text; tokens past the last sequence have no ordinal and count as text
+      ord_q[q] = (t < T) ? (t < t_end ? vis_ord[t] : -1) : -2;
     }
 #pragma unroll
     for (int q = 0; q < CQ; ++q) {
@@ -577,13 +579,14 @@ __global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallA
   }
 
   // ---- all global inputs of this thread's tokens
+  const int t_end = a.prune ? clampi(a.cu[B], 0, T) : T;
   int ord_r[SB_TP];
   uint8_t vis_r[SB_TP];
   int ex[SB_TP][KM];   // expert per slot, later (expert << 16 | row within the expert)
 #pragma unroll
   for (int k = 0; k < SB_TP; ++k) {
     const int t = k * SB_THREADS + tid;
-    ord_r[k] = (a.prune && t < T) ? a.vis_ord[t] : -1;
+    ord_r[k] = (a.prune && t < t_end) ? a.vis_ord[t] : -1;   // past the last sequence: no ordinal, text
     vis_r[k] = (t < T && a.is_visual_out != nullptr) ? a.is_visual[t] : 0;
 #pragma unroll
     for (int sl = 0; sl < KM; ++sl) {

@@ -208,3 +208,128 @@ def test_bench_refuses_more_than_one_gpu():
                        text=True, timeout=120)
     assert r.returncode == 2
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_budget_rule_and_stage_ratio_entry_points(lib):
+    """fmoe_kept_counts (Sec. 3.2.3) against the rule written out here and against the counts the
+    oracle's pruning produces; fmoe_stage_retention (App. D) against beta^stages = r."""
+    import numpy as np
+    import oracle
+    rng = np.random.default_rng(3)
+    for r in (0.25, 0.5, 0.63, 0.75, 0.9, 1.0, 1e-3):
+        lens = [int(v) for v in rng.integers(0, 7000, size=9)] + [0, 1, 2, 3]
+        got = binding.kept_visual_lens(lens, r)
+        r32 = float(np.float32(r))
+        want = [min(max(int(np.floor(r32 * n + 0.5)), min(1, n)), n) for n in lens]
+        assert got == want, r
+    # the count the pruning itself keeps (oracle), on a small ragged batch
+    nv, nt = [41, 0, 7, 130], [2, 5, 0, 9]
+    vis = np.concatenate([np.r_[np.ones(v, np.uint8), np.zeros(t, np.uint8)] for v, t in zip(nv, nt)])
+    cu = np.concatenate([[0], np.cumsum([v + t for v, t in zip(nv, nt)])]).astype(np.int32)
+    probs = rng.random((int(cu[-1]), 10)).astype(np.float32)
+    _, new_cu, _ = oracle.prune(probs, vis, cu, 0.37, 4)
+    assert list(np.diff(new_cu)) == [v + t for v, t in zip(binding.kept_visual_lens(nv, 0.37), nt)]
+    for r, stages in ((0.5, 3), (0.25, 3), (0.75, 1), (1.0, 4), (0.1, 7)):
+        beta = binding.stage_retention(r, stages)
+        assert abs(beta ** stages - r) < 1e-6 and 0 < beta <= 1
+    buf = (C.c_int32 * 2)(5, 6)
+    assert lib.fmoe_kept_counts(buf, 2, 1.5, buf) == -1
+    assert lib.fmoe_kept_counts(buf, 2, 0.0, buf) == -1
+    assert lib.fmoe_kept_counts(buf, -1, 0.5, buf) == -1
+    assert lib.fmoe_kept_counts(None, 2, 0.5, buf) == -2
+    assert lib.fmoe_kept_counts(None, 0, 0.5, None) == 0
+    neg = (C.c_int32 * 1)(-3)
+    assert lib.fmoe_kept_counts(neg, 1, 0.5, neg) == -1
+    beta = C.c_float()
+    assert lib.fmoe_stage_retention(0.5, 0, C.byref(beta)) == -1
+    assert lib.fmoe_stage_retention(0.0, 2, C.byref(beta)) == -1
+    assert lib.fmoe_stage_retention(0.5, 2, None) == -2
+
+
+def test_stack_plan_and_stack_argument_checks(lib):
+    """fmoe_stack_plan: K everywhere below l_v, (K, K_v) from l_v on (Sec. 3.1); stages at the listed
+    layers with the per-stage ratio of App. D.  fmoe_stack_forward / _workspace_bytes refuse
+    inconsistent arguments before anything is enqueued."""
+    n = 12
+    plan = (binding.FmoeLayerPlan * n)()
+    stage = binding.prune_params(retention=0.5, window=3, gamma=0.05)
+    layers = (C.c_int32 * 3)(2, 5, 8)
+    assert lib.fmoe_stack_plan(n, 6, 3, 2, layers, 3, C.byref(stage), plan) == 0
+    beta = binding.stage_retention(0.5, 3)
+    for l in range(n):
+        assert (plan[l].k_text, plan[l].k_visual) == ((6, 6) if l < 2 else (6, 3))
+        if l in (2, 5, 8):
+            assert plan[l].prune.retention == beta and plan[l].prune.window == 3
+            assert abs(plan[l].prune.gamma - 0.05) < 1e-7 and plan[l].prune.prune_mode == 1
+        else:
+            assert plan[l].prune.prune_mode == 0 and plan[l].prune.retention == 1.0
+    assert lib.fmoe_stack_plan(n, 6, 3, n, None, 0, None, plan) == 0          # never reduced, never pruned
+    assert all(plan[l].k_visual == 6 and plan[l].prune.prune_mode == 0 for l in range(n))
+    assert lib.fmoe_stack_plan(n, 6, 3, 13, None, 0, None, plan) == -1
+    assert lib.fmoe_stack_plan(n, 6, 3, 2, (C.c_int32 * 2)(5, 2), 2, C.byref(stage), plan) == -1
+    assert lib.fmoe_stack_plan(n, 6, 3, 2, (C.c_int32 * 1)(12), 1, C.byref(stage), plan) == -1
+    assert lib.fmoe_stack_plan(n, 6, 3, 2, layers, 3, None, plan) == -2
+    assert lib.fmoe_stack_plan(0, 6, 3, 0, None, 0, None, plan) == -1
+    assert lib.fmoe_stack_plan(n, 6, 3, 2, None, 0, None, None) == -2
+
+    cfg = binding.FmoeConfig(64, 8, 32, 0, 0, 2, 1, 1, binding.FMOE_F32)
+    ctxs = (C.c_void_p * 2)()
+    for i in range(2):
+        c = C.c_void_p()
+        assert lib.fmoe_create(C.byref(c), C.byref(cfg), 0) == 0
+        ctxs[i] = c.value
+    plan2 = (binding.FmoeLayerPlan * 2)()
+    assert lib.fmoe_stack_plan(2, 2, 1, 1, (C.c_int32 * 1)(1), 1, C.byref(stage), plan2) == 0
+    small, big = lib.fmoe_stack_workspace_bytes(ctxs, plan2, 2, 64, 2), lib.fmoe_stack_workspace_bytes(ctxs, plan2, 2, 4096, 2)
+    assert 0 < small < big
+    assert big > lib.fmoe_workspace_bytes(ctxs[0], 4096, 2) + 2 * 4096 * 64 * 4       # two activation buffers on top
+    dummy = C.c_void_p(0x1000)
+    nv, nt = (C.c_int32 * 2)(30, 20), (C.c_int32 * 2)(4, 6)
+    args = lambda T, ws, wsb: (ctxs, plan2, 2, dummy, dummy, dummy, nv, nt, 2, T, None, dummy, dummy, dummy, None,
+                               None, ws, wsb, None)
+    assert lib.fmoe_stack_forward(*args(61, dummy, 1 << 30)) == -3            # lengths add up to 60
+    assert lib.fmoe_stack_forward(*args(60, None, 0)) == -4
+    assert lib.fmoe_stack_forward(*args(60, C.c_void_p(0x10000), 256)) == -4
+    assert lib.fmoe_stack_forward(ctxs, None, 2, *args(60, dummy, 0)[3:]) == -2
+    plan2[1].k_text = 9                                                        # above E = 8
+    assert lib.fmoe_stack_forward(*args(60, C.c_void_p(0x10000), 1 << 30)) == -1
+    plan2[1].k_text = 2
+    other = binding.FmoeConfig(128, 8, 32, 0, 0, 2, 1, 1, binding.FMOE_F32)     # another d_model
+    c = C.c_void_p()
+    assert lib.fmoe_create(C.byref(c), C.byref(other), 0) == 0
+    mixed = (C.c_void_p * 2)(ctxs[0], c.value)
+    assert lib.fmoe_stack_workspace_bytes(mixed, plan2, 2, 64, 2) == 0
+    assert lib.fmoe_stack_forward(mixed, *args(60, C.c_void_p(0x10000), 1 << 30)[1:]) == -3
+    for p in (ctxs[0], ctxs[1], c.value):
+        lib.fmoe_destroy(C.c_void_p(p))
+
+
+def test_four_gib_extents_and_empty_sequence_lists_are_refused(lib):
+    """bf16 expert GEMMs address activation rows with 32-bit byte offsets; every such offset is clamped
+    below 4 GiB inside the kernel and the host refuses buffers that could not be addressed -- before the
+    weights are even looked at, so the refusal needs no GPU.  A batch with tokens but no sequence is an
+    argument error (the pruning stage could not place its tokens)."""
+    dummy = C.c_void_p(0x1000)
+    cfg = binding.FmoeConfig(2048, 64, 1408, 2, 1408, 6, 3, 1, binding.FMOE_BF16)
+    ctx = C.c_void_p()
+    assert lib.fmoe_create(C.byref(ctx), C.byref(cfg), 0) == 0
+    T_big = (1 << 32) // (2 * 2048) + 1                                       # x alone passes 4 GiB
+    assert T_big < (1 << 24)
+    lf = lambda T, B: lib.fmoe_layer_forward(ctx, None, dummy, dummy, dummy, B, T, None, 0, dummy, dummy, dummy,
+                                              None, dummy, 0, None)
+    assert lf(T_big, 1) == -5 and b"4 GiB" in lib.fmoe_last_error()
+    T_hid = (1 << 32) // (2 * 6 * 1408) + 1                                   # x fits, the hidden buffer does not
+    assert T_hid * 2048 * 2 < (1 << 32)
+    assert lf(T_hid, 1) == -5 and b"hidden buffer" in lib.fmoe_last_error()
+    assert lib.fmoe_expert_ffn(ctx, dummy, None, T_hid, None, dummy, dummy, dummy, dummy, dummy, 0, None) == -5
+    assert lf(T_hid - 1, 1) == -1 and b"fmoe_set_weights" in lib.fmoe_last_error()   # in range: next check
+    lib.fmoe_destroy(ctx)
+    f32 = binding.FmoeConfig(2048, 64, 1408, 2, 1408, 6, 3, 1, binding.FMOE_F32)   # fp32 contexts use 64-bit pointers
+    assert lib.fmoe_create(C.byref(ctx), C.byref(f32), 0) == 0
+    assert lf(T_big, 1) == -1 and b"fmoe_set_weights" in lib.fmoe_last_error()
+    # tokens but no sequence
+    pp = binding.prune_params(retention=0.5, window=3)
+    assert lib.fmoe_prune(ctx, C.byref(pp), dummy, dummy, dummy, 0, 4, None, None, dummy, dummy, None, None, None,
+                          dummy, 0, None) == -1
+    assert b"no sequence" in lib.fmoe_last_error()
+    lib.fmoe_destroy(ctx)
