@@ -183,9 +183,15 @@ class FMoE:
         _check(self.lib.fmoe_set_selection(self._ctx, int(strategy), int(k_base), int(seed)))
 
     def set_weights(self, router_w, router_bias, w_gate, w_up, w_down, ws_gate=None, ws_up=None,
-                    ws_down=None):
+                    ws_down=None, release_packed=False):
+        """release_packed: a bf16 context reads its expert weights from the library's packed copies only,
+        so once the packing kernels have run the caller's expert tensors need not be kept alive; with
+        this flag the binding waits for the stream and holds on to the router bias alone."""
         self._weights = (router_w, router_bias, w_gate, w_up, w_down, ws_gate, ws_up, ws_down)
         _check(self.lib.fmoe_set_weights(self._ctx, *[_ptr(t) for t in self._weights], _stream()))
+        if release_packed and self.cfg.dtype == FMOE_BF16:
+            torch.cuda.current_stream().synchronize()
+            self._weights = (router_bias,)
 
     def workspace_bytes(self, max_tokens, max_seqs=1):
         return int(self.lib.fmoe_workspace_bytes(self._ctx, max_tokens, max_seqs))

@@ -81,7 +81,7 @@ class Workload:
     x: np.ndarray         # [T, d]
     is_visual: np.ndarray  # [T] uint8
     cu_seqlens: np.ndarray  # [B+1] int32
-    layers: List[LayerWeights]
+    layers: Sequence[LayerWeights]   # a list, or LazyLayers for the stack workloads
     # per-layer (k_text, k_visual) and the layer after which pruning runs (stack workloads)
     k_schedule: Optional[List[Sequence[int]]] = None
     prune_after_layer: Optional[int] = None
@@ -99,11 +99,46 @@ class Workload:
         return self.layers[0]
 
 
+class LazyLayers:
+    """The layers of a stack workload, each drawn on demand from a random stream of its own, so that a
+    12-layer stack of full-size layers (2.3 GB of fp32 per layer on the host) never has to exist at
+    once.  Indexing draws the layer again every time: callers keep what they need."""
+
+    def __init__(self, n_layers, draw):
+        self._n, self._draw = int(n_layers), draw
+
+    def __len__(self):
+        return self._n
+
+    def __getitem__(self, l):
+        if isinstance(l, slice):
+            return [self[i] for i in range(*l.indices(self._n))]
+        if l < 0:
+            l += self._n
+        if not 0 <= l < self._n:
+            raise IndexError(l)
+        return self._draw(l)
+
+    def __iter__(self):
+        return (self._draw(l) for l in range(self._n))
+
+
+def _round_bf16_inplace(a: np.ndarray) -> np.ndarray:
+    """round_to_dtype(a, BF16) without temporaries of the array's size (same values)."""
+    u = a.view(np.uint32)
+    bias = u >> np.uint32(16)
+    bias &= np.uint32(1)
+    bias += np.uint32(0x7FFF)
+    u += bias
+    u &= np.uint32(0xFFFF0000)
+    return a
+
+
 def _normal(rng: np.random.Generator, shape, std: float, dtype: str) -> np.ndarray:
     a = rng.standard_normal(shape, dtype=np.float32)
     if std != 1.0:
         a *= np.float32(std)
-    return round_to_dtype(a, dtype)
+    return _round_bf16_inplace(a) if dtype == BF16 else a
 
 
 def draw_layer_weights(rng, d, E, F, n_shared, F_shared, bias_std, dtype, w_std=0.02) -> LayerWeights:
@@ -120,6 +155,30 @@ def draw_layer_weights(rng, d, E, F, n_shared, F_shared, bias_std, dtype, w_std=
         ws_up = _normal(rng, (n_shared, F_shared, d), w_std, dtype)
         ws_down = _normal(rng, (n_shared, d, F_shared), w_std, dtype)
     return LayerWeights(router_w, router_bias, w_gate, w_up, w_down, ws_gate, ws_up, ws_down)
+
+
+def draw_layer_weights_parallel(entropy, d, E, F, n_shared, F_shared, bias_std, dtype, w_std=0.02,
+                                down_std=None) -> LayerWeights:
+    """The same tensors as draw_layer_weights, each from a stream of its own (entropy + [tensor index]),
+    so that the large ones can be drawn by separate threads.  down_std: standard deviation of the down
+    projections (default w_std)."""
+    import concurrent.futures as cf
+
+    def stream(j):
+        return np.random.Generator(np.random.PCG64(list(entropy) + [j]))
+
+    shapes = [(E, F, d), (E, F, d), (E, d, F)]
+    if n_shared > 0:
+        shapes += [(n_shared, F_shared, d), (n_shared, F_shared, d), (n_shared, d, F_shared)]
+    down_std = w_std if down_std is None else down_std
+    with cf.ThreadPoolExecutor(max_workers=3) as ex:
+        big = list(ex.map(lambda js: _normal(stream(2 + js[0]), js[1], down_std if js[0] % 3 == 2 else w_std, dtype),
+                          enumerate(shapes)))
+    router_w = _normal(stream(0), (E, d), w_std, dtype)
+    router_bias = None
+    if bias_std > 0.0:
+        router_bias = (stream(1).standard_normal(E, dtype=np.float32) * np.float32(bias_std)).astype(np.float32)
+    return LayerWeights(router_w, router_bias, *big, *([None] * (6 - len(big))))
 
 
 def draw_visual_mixture(rng, n_tokens, d, n_components, sigma, max_run=16) -> np.ndarray:
@@ -167,12 +226,20 @@ def make_workload(name: str, *, seed: int, dtype: str, d: int, E: int, F: int,
                   visual_lens: Sequence[int], text_lens: Sequence[int],
                   n_components: int = 0, sigma: float = 0.3, tile: Optional[int] = None,
                   bias_std: float = 0.0, n_layers: int = 1,
-                  k_schedule=None, prune_after_layer=None) -> Workload:
-    """Draw weights first (layer by layer), then activations, from one PCG64 stream."""
-    rng = np.random.Generator(np.random.PCG64(seed))
+                  k_schedule=None, prune_after_layer=None, independent_layers: bool = False,
+                  down_std: Optional[float] = None) -> Workload:
+    """Draw weights first (layer by layer), then activations, from one PCG64 stream.
+    independent_layers (stack workloads): the activations come from the stream seeded [seed, 0] and
+    layer l from the stream seeded [seed, 1, l], drawn on demand (LazyLayers)."""
     F_shared = F if F_shared is None else F_shared
-    layers = [draw_layer_weights(rng, d, E, F, n_shared, F_shared, bias_std, dtype)
-              for _ in range(n_layers)]
+    if independent_layers:
+        rng = np.random.Generator(np.random.PCG64([seed, 0]))
+        layers = LazyLayers(n_layers, lambda l: draw_layer_weights_parallel(
+            [seed, 1, l], d, E, F, n_shared, F_shared, bias_std, dtype, down_std=down_std))
+    else:
+        rng = np.random.Generator(np.random.PCG64(seed))
+        layers = [draw_layer_weights(rng, d, E, F, n_shared, F_shared, bias_std, dtype)
+                  for _ in range(n_layers)]
     xs, masks, cu = [], [], [0]
     for nv, nt in zip(visual_lens, text_lens):
         if n_components > 0:
@@ -242,14 +309,20 @@ def config5(n_layers: int = 12, d: int = 2048, E: int = 64, F: int = 1408, n_sha
     """Ragged batched prefill: 8 packed sequences (visual 1024..6400 step 256, +128 text),
     a 12-layer stack of config-3-shaped layers with x <- x + MoE(x); top-6/top-6 in layers
     0-1, top-6/top-3 from layer 2; pruning to 50 % once, after layer 2, per sequence.
-    `len_div`, `d`, `F`, `n_layers` shrink it for tests the oracle must finish quickly."""
+    `len_div`, `d`, `F`, `n_layers` shrink it for tests the oracle must finish quickly.
+    The stack has no normalisation layers (attention is an identity residual), and the SwiGLU expert
+    term grows with the square of its input's scale, so with N(0, 0.02) everywhere the residual stream
+    of twelve full-size layers diverges until fp32 overflows.  The down projections of the stack's
+    layers are therefore drawn with standard deviation 0.02 / sqrt(2 * 12), the usual scaling of
+    residual-branch output weights with depth, which keeps x at O(1) through the stack."""
     lens = [max(1, v // len_div) for v in config5_lengths(n_seqs=n_seqs)]
     sched = [(6, 6) if l < 2 else (6, 3) for l in range(n_layers)]
     return make_workload("c5_ragged_stack", seed=4, dtype=dtype, d=d, E=E, F=F, n_shared=n_shared,
                          k_text=6, k_visual=3, retention=0.5, window=3,
                          visual_lens=lens, text_lens=[max(1, text_len // len_div)] * n_seqs,
                          n_components=192, bias_std=1.0, n_layers=n_layers,
-                         k_schedule=sched, prune_after_layer=2)
+                         k_schedule=sched, prune_after_layer=2, independent_layers=True,
+                         down_std=0.02 / float(np.sqrt(24.0)))
 
 
 def small_random(seed: int, *, T_v: Sequence[int], T_t: Sequence[int], d: int, E: int, F: int,

@@ -58,3 +58,45 @@ def max_rel_err(got, ref):
     if scale == 0:
         return float(np.abs(got).max())
     return float(np.abs(got - ref).max() / scale)
+
+
+def elementwise_rel_err(got, ref):
+    """max over elements of |got - ref| / max(|ref|, 1e-3 * max |ref|): the element-wise figure, with a
+    floor so that elements near a cancellation do not divide by nothing."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    scale = np.abs(ref).max()
+    if scale == 0:
+        return float(np.abs(got).max())
+    return float((np.abs(got - ref) / np.maximum(np.abs(ref), 1e-3 * scale)).max())
+
+
+def assert_outputs_close(got, ref, dtype, what=""):
+    """The output bar: max-norm relative error within the storage dtype's tolerance.  The message carries
+    the element-wise figure as well."""
+    err = max_rel_err(got, ref)
+    assert err <= TOL[dtype], (f"{what}: max|d|/max|ref| = {err:.3e} > {TOL[dtype]:.0e}; element-wise "
+                               f"(floor 1e-3 max|ref|) = {elementwise_rel_err(got, ref):.3e}")
+    return err
+
+
+# relative size of half a unit in the last place of a stored value
+HALF_ULP = {W.F32: 2.0 ** -24, W.BF16: 2.0 ** -8}
+
+
+def assert_residual_outputs_close(got, ref_f64, x_rows, dtype, what=""):
+    """Outputs of a run with the residual added, x + MoE(x).  The input x is O(1) while the expert term
+    can be two orders of magnitude smaller, so an error bound relative to max |x + MoE(x)| would hide a
+    wrong expert term.  Bound used instead, per element: the tolerance times the largest |MoE term| of
+    the oracle (ref - x), plus the one rounding of the stored sum (half a unit in the last place of the
+    element itself), plus the roundings of the fp32 accumulator that holds x while the expert terms are
+    added to it (residual, shared experts, up to 16 slots: at most 20 additions of half an fp32 unit)."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref_f64, np.float64)
+    moe = ref - np.asarray(x_rows, np.float64)
+    scale = np.abs(moe).max()
+    bound = TOL[dtype] * scale + (HALF_ULP[dtype] + 20 * 2.0 ** -24) * np.maximum(np.abs(ref), np.abs(got))
+    diff = np.abs(got - ref)
+    worst = int(np.argmax(diff - bound))
+    assert (diff <= bound).all(), (f"{what}: |d| = {diff.flat[worst]:.3e} > bound {bound.flat[worst]:.3e} "
+                                   f"(max|MoE term| = {scale:.3e}, max|ref| = {np.abs(ref).max():.3e})")

@@ -9,7 +9,8 @@ import torch
 import oracle
 from paper_2511_17885_amd import binding
 from paper_2511_17885_amd import workloads as W
-from harness import TOL, dev, host, inputs, make_layer, max_rel_err, torch_dtype
+from harness import (TOL, assert_outputs_close, assert_residual_outputs_close, dev, host, inputs, make_layer,
+                     max_rel_err, torch_dtype)
 
 pytestmark = pytest.mark.gpu
 
@@ -41,6 +42,11 @@ SMALL = [
 
 def _wl(seed, kw):
     return W.small_random(seed, **kw)
+
+
+def _x_rows(wl, o):
+    """The rows a residual run adds to the expert term: the kept input rows, or the merged layer input."""
+    return o["x_merged"] if "x_merged" in o else wl.x[o["kept_idx"]]
 
 
 def _oracle(wl, **over):
@@ -299,7 +305,10 @@ def test_expert_ffn_and_combine(seed, kw):
     if wl.n_shared:   # per-expert outputs; the oracle holds their sum
         assert max_rel_err(host(ysh).astype(np.float64).sum(0)[:n], o["y_shared"]) <= tol
     out = m.combine(y, ysh, dev(o["inv_perm"]), dev(o["topk_gate"]), kept, n, residual=x)
-    assert max_rel_err(host(out)[:n], o["out_f64"]) <= tol
+    assert_residual_outputs_close(host(out)[:n], o["out_f64"], _x_rows(wl, o), wl.dtype, "combine + residual")
+    o_plain = _oracle(wl)                                   # and the expert term on its own
+    out = m.combine(y, ysh, dev(o["inv_perm"]), dev(o["topk_gate"]), kept, n)
+    assert_outputs_close(host(out)[:n], o_plain["out_f64"], wl.dtype, "combine")
 
 
 # ---------------------------------------------------------------- whole layer
@@ -318,10 +327,14 @@ def test_layer_forward(seed, kw):
     assert np.array_equal(host(kept)[:n], o["kept_idx"])
     assert np.array_equal(host(vis_out)[:n], wl.is_visual[o["kept_idx"]])
     if n:
-        assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
+        assert_residual_outputs_close(host(out)[:n], o["out_f64"], _x_rows(wl, o), wl.dtype, "layer + residual")
     # determinism: a second run gives identical bits
     out2, kept2, _, _ = m.layer_forward(x, vis, cu, pp, add_residual=True)
     assert torch.equal(out[:n], out2[:n]) and torch.equal(kept[:n], kept2[:n])
+    # the expert term on its own (Eq.4 without the residual), at the tolerance proper
+    out3, _, _, _ = m.layer_forward(x, vis, cu, pp)
+    if n:
+        assert_outputs_close(host(out3)[:n], _oracle(wl)["out_f64"], wl.dtype, "layer")
 
 
 def test_layer_forward_equals_chained_calls_and_no_prune_path():
@@ -366,7 +379,9 @@ def test_layer_forward_merge(seed, kw):
         assert np.array_equal(host(kept)[:n], o["kept_idx"])
         assert np.array_equal(host(vis_out)[:n], wl.is_visual[o["kept_idx"]])
         if n:
-            assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
+            assert_residual_outputs_close(host(out)[:n], o["out_f64"], _x_rows(wl, o), wl.dtype, f"gamma {gamma}")
+            out2, _, _, _ = m.layer_forward(x, vis, cu, pp)
+            assert_outputs_close(host(out2)[:n], _oracle(wl, gamma=gamma)["out_f64"], wl.dtype, f"gamma {gamma}")
 
 
 def test_layer_forward_merge_rejects_router_only_mode():
@@ -446,39 +461,53 @@ def test_layer_forward_replays_from_a_captured_graph(gamma):
 
 
 # ---------------------------------------------------------------- the benchmark configurations
-def _check_config(wl, sample=None, seed=0):
-    """Decisions on every token; outputs on every kept token, or on a sample of them evaluated
-    one by one with Eq.4 when the whole layer is too slow for the CPU."""
-    m = make_layer(wl)
-    x, vis, cu = inputs(wl)
-    pp = binding.prune_params(retention=wl.retention, window=wl.window)
-    out, kept, new_cu, _ = m.layer_forward(x, vis, cu, pp)
-    torch.cuda.synchronize()
+def _check_layer(m, wl, x_np, vis_np, cu_np, lw, k_text, k_visual, do_prune, add_residual=False, what=""):
+    """One fused layer on the GPU against the oracle's layer on the same input bytes: expert ids,
+    probabilities, kept set, sequence bounds and permutation bit for bit; outputs on EVERY kept row
+    within the dtype's tolerance.  Returns the oracle's result (its output feeds the next layer of a
+    teacher-forced stack: the oracle never sees a value from the GPU)."""
     is_bf16 = wl.dtype == W.BF16
-    o = _oracle(wl, ffn=sample is None)
+    td = torch_dtype(wl)
+    x, vis, cu = dev(x_np, td), dev(vis_np), dev(cu_np)
+    m.set_topk(k_text, k_visual)
+    pp = binding.prune_params(retention=wl.retention, window=wl.window) if do_prune else None
+    out, kept, new_cu, vis_out = m.layer_forward(x, vis, cu, pp, add_residual=add_residual, want_mask=True)
+    torch.cuda.synchronize()
+    o = oracle.layer_forward(x_np, vis_np, cu_np, lw, k_text=k_text, k_visual=k_visual, is_bf16=is_bf16,
+                             retention=wl.retention, window=wl.window, do_prune=do_prune,
+                             add_residual=add_residual)
     new_cu = host(new_cu)
     n = int(new_cu[-1])
-    assert np.array_equal(new_cu, o["new_cu_seqlens"])
-    assert np.array_equal(host(kept)[:n], o["kept_idx"])
+    assert np.array_equal(new_cu, o["new_cu_seqlens"]), what
+    assert np.array_equal(host(kept)[:n], o["kept_idx"]), what
+    assert np.array_equal(host(vis_out)[:n], vis_np[o["kept_idx"]]), what
     probs, idx, gate = m.route(x, vis)
-    assert np.array_equal(host(idx), o["topk_idx"])
-    assert np.array_equal(host(probs), o["probs"])
+    assert np.array_equal(host(idx), o["topk_idx"]), what
+    assert np.array_equal(host(probs), o["probs"]), what
+    assert np.abs(host(gate) - o["topk_gate"]).max() <= 1e-6, what
     offs, perm, inv = m.permute(idx.contiguous(), kept, n)
-    assert np.array_equal(host(offs), o["expert_offsets"])
-    assert np.array_equal(host(perm)[:o["expert_offsets"][-1]], o["perm_src"])
-    assert np.array_equal(host(inv)[:n], o["inv_perm"])
+    assert np.array_equal(host(offs), o["expert_offsets"]), what
+    assert np.array_equal(host(perm)[:o["expert_offsets"][-1]], o["perm_src"]), what
+    assert np.array_equal(host(inv)[:n], o["inv_perm"]), what
     got = host(out)[:n]
-    if sample is None:
-        assert max_rel_err(got, o["out_f64"]) <= TOL[wl.dtype]
+    assert np.isfinite(got).all(), what
+    if add_residual:
+        assert_residual_outputs_close(got, o["out_f64"], x_np[o["kept_idx"]], wl.dtype, what)
+        # and the expert term alone (Eq.4 without the residual) at the tolerance proper
+        out2, _, _, _ = m.layer_forward(x, vis, cu, pp)
+        torch.cuda.synchronize()
+        moe_ref = o["out_f64"] - x_np[o["kept_idx"]].astype(np.float64)
+        assert_outputs_close(host(out2)[:n], moe_ref, wl.dtype, what + ", expert term")
     else:
-        rng = np.random.default_rng(seed)
-        pos = np.sort(rng.choice(n, size=min(sample, n), replace=False))
-        _, ref = oracle.token_outputs(wl.x, o["kept_idx"][pos], o["topk_idx"], o["topk_gate"],
-                                      wl.weights, is_bf16)
-        scale = np.abs(ref).max()
-        assert np.abs(got[pos] - ref).max() / scale <= TOL[wl.dtype]
-        assert np.isfinite(got).all()
-    return n
+        assert_outputs_close(got, o["out_f64"], wl.dtype, what)
+    return o
+
+
+def _check_config(wl):
+    m = make_layer(wl)
+    o = _check_layer(m, wl, wl.x, wl.is_visual, wl.cu_seqlens, wl.weights, wl.k_text, wl.k_visual,
+                     do_prune=wl.retention < 1.0, what=wl.name)
+    return len(o["kept_idx"])
 
 
 def test_config1_tiny_fp32():
@@ -489,131 +518,282 @@ def test_config2_dsvl2_tiny():
     assert _check_config(W.config2()) == 768 + 64
 
 
-def test_config3_dsvl2_small_half_retention_sampled():
-    assert _check_config(W.config3(0.5), sample=48) == 1920 + 256
+@pytest.mark.parametrize("retention,kept_visual", [(0.25, 960), (0.5, 1920), (0.75, 2880)])
+def test_config3_dsvl2_small_retention_sweep(retention, kept_visual):
+    # every kept row of the full-size layer is compared (the oracle's layer takes about ten seconds)
+    assert _check_config(W.config3(retention)) == kept_visual + 256
 
 
-def test_config4_internvl35_sampled():
-    assert _check_config(W.config4(), sample=48) == 3968 + 256
-
-
-@pytest.mark.parametrize("retention,kept_visual", [(0.25, 960), (0.75, 2880)])
-def test_config3_retention_sweep_sampled(retention, kept_visual):
-    assert _check_config(W.config3(retention), sample=32) == kept_visual + 256
-
-
-def test_config3_full_activation_no_pruning_sampled():
-    # the standard MoE layer (k 6/6, r = 1): the compute-bound end of the expert GEMM
+def test_config3_full_activation_no_pruning():
+    # the standard MoE layer (k 6/6, r = 1): the reference point of the retention sweep, 384 rows per expert
     wl = W.config3(1.0, k_visual=6)
-    assert _check_config(wl, sample=32) == wl.T
+    assert _check_config(wl) == wl.T
 
 
-def test_config5_layer_full_size_ragged_sampled():
-    # one layer of config 5 at its real size: 8 packed sequences of 1152..6528 tokens (22k tokens here),
-    # d = 2048, 64 experts + 2 shared; the pruning layer's configuration (k 6/3, r = 0.5, W = 3)
-    wl = W.config5(n_layers=1)
-    lens = np.diff(wl.cu_seqlens)
-    nv = [int(wl.is_visual[s:e].sum()) for s, e in zip(wl.cu_seqlens[:-1], wl.cu_seqlens[1:])]
-    nt = [int(n - v) for n, v in zip(lens, nv)]
-    assert wl.B == 8 and wl.T > 16384                      # far beyond the single-workgroup dispatch path
-    assert _check_config(wl, sample=24) == binding.kept_count(nv, nt, wl.retention)
-
-
-def test_config5_layer_full_size_full_activation_sampled():
-    # the same layer as layers 0-1 run it: top-6 for every token, no pruning (~2900 rows per expert:
-    # the compute-bound end of the expert GEMM)
-    wl = W.config5(n_layers=1)
-    wl.k_visual, wl.retention = 6, 1.0
-    assert _check_config(wl, sample=24) == wl.T
+def test_config4_internvl35():
+    assert _check_config(W.config4()) == 3968 + 256
 
 
 # ---------------------------------------------------------------- the ragged multi-layer stack
-def _oracle_stack(wl, schedule=None):
+def _lens(wl):
+    lens = np.diff(wl.cu_seqlens)
+    nv = [int(wl.is_visual[s:e].sum()) for s, e in zip(wl.cu_seqlens[:-1], wl.cu_seqlens[1:])]
+    return nv, [int(n - v) for n, v in zip(lens, nv)]
+
+
+def _oracle_stack(wl, schedule=None, layers=None):
     """x <- x + MoE_l(x) layer by layer on the CPU; `schedule` = {layer: dict(retention, window, alpha,
-    gamma)} (default: one stage after `prune_after_layer`)."""
+    gamma)} (default: one stage after `prune_after_layer`).  Returns the final (x, kept_total, cu) and
+    the per-layer records (input x / mask / cu, the oracle's result)."""
     is_bf16 = wl.dtype == W.BF16
     if schedule is None:
         schedule = {wl.prune_after_layer: dict(retention=wl.retention, window=wl.window)}
     x, vis, cu = wl.x, wl.is_visual, wl.cu_seqlens
     kept_total = None
-    for l, lw in enumerate(wl.layers):
+    records = []
+    for l in range(len(wl.layers)):
+        lw = wl.layers[l] if layers is None else layers[l]
         kt, kv = wl.k_schedule[l]
         st = schedule.get(l)
         o = oracle.layer_forward(x, vis, cu, lw, k_text=kt, k_visual=kv, is_bf16=is_bf16,
                                  add_residual=True, do_prune=st is not None,
                                  **(st if st is not None else dict(retention=1.0, window=wl.window)))
+        records.append(dict(x=x, vis=vis, cu=cu, o=o, stage=st))
         if st is not None:
             kept = o["kept_idx"]
             kept_total = kept if kept_total is None else kept_total[kept]
             vis, cu = vis[kept], o["new_cu_seqlens"]
         x = o["out"]
+    return x, kept_total, cu, records
+
+
+def _gpu_layers(wl):
+    return [make_layer(wl, layer=l) for l in range(len(wl.layers))]
+
+
+def _gpu_stack(wl, layers, schedule=None):
+    """The stack through fmoe_stack_forward.  schedule: {layer: prune params}."""
+    if schedule is None:
+        schedule = {wl.prune_after_layer: binding.prune_params(retention=wl.retention, window=wl.window, prune_mode=2)}
+    stack = binding.FMoEStack(layers, wl.k_schedule, prune_schedule=schedule)
+    x, vis, cu = inputs(wl)
+    nv, nt = _lens(wl)
+    out, kept, new_cu = stack.forward(x, vis, cu, nv, nt)
+    torch.cuda.synchronize()
+    return out, kept, new_cu
+
+
+def _gpu_chain(wl, layers, schedule):
+    """The same stack as single fmoe_layer_forward calls chained by the test (what fmoe_stack_forward
+    must reproduce bit for bit: same kernels, same order)."""
+    x, vis, cu = inputs(wl)
+    kept_total = None
+    for l, m in enumerate(layers):
+        m.set_topk(*wl.k_schedule[l])
+        pp = schedule.get(l)
+        out, kept, new_cu, vis_out = m.layer_forward(x, vis, cu, pp, add_residual=True, want_mask=pp is not None)
+        if pp is not None:
+            n = int(host(new_cu)[-1])
+            kept_total = kept[:n].clone() if kept_total is None else kept_total[kept[:n].long()]
+            x, vis, cu = out[:n].clone(), vis_out[:n].clone(), new_cu.clone()
+        else:
+            x = out[:x.shape[0]].clone()
     return x, kept_total, cu
 
 
-def _gpu_stack(wl, schedule=None):
-    layers = [make_layer(wl, layer=l) for l in range(len(wl.layers))]
-    if schedule is None:
-        stack = binding.FMoEStack(layers, wl.k_schedule, wl.prune_after_layer,
-                                  binding.prune_params(retention=wl.retention, window=wl.window, prune_mode=2))
-    else:
-        stack = binding.FMoEStack(layers, wl.k_schedule, prune_schedule=schedule)
-    x, vis, cu = inputs(wl)
-    lens = np.diff(wl.cu_seqlens)
-    nv = [int(wl.is_visual[s:e].sum()) for s, e in zip(wl.cu_seqlens[:-1], wl.cu_seqlens[1:])]
-    nt = [int(n - v) for n, v in zip(lens, nv)]
-    out, kept, new_cu = stack.forward(x, vis, cu, nv, nt)
-    torch.cuda.synchronize()
-    return host(out), host(kept), host(new_cu), nv, nt
+def _teacher_forced(wl, layers, records, only=None):
+    """Every GPU layer gets the ORACLE's input of that layer: decisions bit for bit and outputs on every
+    kept row at the dtype's tolerance, at every layer, unconditionally."""
+    for l, r in enumerate(records):
+        if only is not None and l not in only:
+            continue
+        st = r["stage"]
+        m = layers[l]
+        kt, kv = wl.k_schedule[l]
+        is_bf16 = wl.dtype == W.BF16
+        td = torch_dtype(wl)
+        x, vis, cu = dev(r["x"], td), dev(r["vis"]), dev(r["cu"])
+        m.set_topk(kt, kv)
+        pp = None
+        if st is not None:
+            pp = binding.prune_params(retention=st["retention"], window=st["window"], alpha=st.get("alpha", 1.0),
+                                      gamma=st.get("gamma", 0.0), prune_mode=1 if st.get("gamma", 0.0) > 0 else 2)
+        out, kept, new_cu, _ = m.layer_forward(x, vis, cu, pp, add_residual=True)
+        torch.cuda.synchronize()
+        o = r["o"]
+        new_cu = host(new_cu)
+        n = int(new_cu[-1])
+        assert np.array_equal(new_cu, o["new_cu_seqlens"]), l
+        assert np.array_equal(host(kept)[:n], o["kept_idx"]), l
+        _, idx, gate = m.route(x, vis, want_probs=False)
+        if "x_merged" not in o:                       # (with merging the list is that of the merged input)
+            assert np.array_equal(host(idx), o["topk_idx"]), l
+        assert_residual_outputs_close(host(out)[:n], o["out_f64"], _x_rows_of(r), wl.dtype, f"layer {l}")
+
+
+def _x_rows_of(r):
+    o = r["o"]
+    return o["x_merged"] if "x_merged" in o else r["x"][o["kept_idx"]]
 
 
 @pytest.mark.parametrize("gamma", [0.0, 0.05])
 def test_stack_three_stage_schedule_fp32(gamma):
     # App. D: r = 0.5 reached in three stages of beta = r^(1/3) after layers 2, 5, 8 (the DeepSeek-VL2
-    # setting of App. A: W = 3, gamma = 0.05), reduced top-k from layer 2 on; fp32 so that every
-    # decision down the stack is compared bit for bit
+    # setting of App. A: W = 3, gamma = 0.05), reduced top-k from layer 2 on
     wl = W.config5(n_layers=10, d=128, E=64, F=64, len_div=32, text_len=128, dtype=W.F32)
     sched = binding.stage_schedule(0.5, [2, 5, 8], window=3, gamma=gamma)
     assert abs(sched[2].retention ** 3 - 0.5) < 1e-6
     o_sched = {l: dict(retention=p.retention, window=p.window, alpha=p.alpha, gamma=p.gamma)
                for l, p in sched.items()}
-    out, kept, new_cu, nv, nt = _gpu_stack(wl, sched)
-    ref, ref_kept, ref_cu = _oracle_stack(wl, o_sched)
-    assert np.array_equal(new_cu, ref_cu)
-    assert np.array_equal(kept, ref_kept)
+    layers = _gpu_layers(wl)
+    ref, ref_kept, ref_cu, records = _oracle_stack(wl, o_sched)
+    _teacher_forced(wl, layers, records)                      # per layer: 1e-5, decisions bit for bit
+    out, kept, new_cu = _gpu_stack(wl, layers, sched)         # the library's stack driver ...
+    c_out, c_kept, c_cu = _gpu_chain(wl, layers, sched)       # ... equals the chained single-layer calls
+    assert torch.equal(out, c_out) and torch.equal(kept, c_kept) and torch.equal(new_cu, c_cu)
+    # (free-running, the two sides' activations differ by fp32 rounding after the first layer, which may
+    # flip a near-tied later decision: decisions are compared layer by layer on identical inputs above;
+    # the per-sequence counts are exact whatever near-ties do)
+    assert np.array_equal(host(new_cu), ref_cu)
+    assert kept.shape[0] == ref_kept.shape[0]
+    nv, nt = _lens(wl)
     lens = nv
     for _ in range(3):
         lens = binding.kept_visual_lens(lens, sched[2].retention)
     assert out.shape[0] == sum(lens) + sum(nt) == ref.shape[0]
     assert abs(sum(lens) / sum(nv) - 0.5) < 0.02           # the cumulative ratio of App. D
-    assert max_rel_err(out, ref) <= 10 * TOL[W.F32]
 
 
 def test_stack_ragged_12_layers_fp32():
     # config 5 in structure (8 ragged sequences, 12 layers, k 6/6 then 6/3, pruning after layer 2)
-    # at sizes the oracle finishes in seconds; fp32 storage keeps the two sides' activations within
-    # 1e-6 of each other, so every routing and pruning decision down the stack must agree
+    # at sizes the oracle finishes in seconds
     wl = W.config5(n_layers=12, d=128, E=64, F=64, len_div=32, text_len=128, dtype=W.F32)
-    out, kept, new_cu, nv, nt = _gpu_stack(wl)
-    ref, ref_kept, ref_cu = _oracle_stack(wl)
-    assert np.array_equal(new_cu, ref_cu)
-    assert np.array_equal(kept, ref_kept)
-    assert out.shape[0] == binding.kept_count(nv, nt, wl.retention) == ref.shape[0]
-    assert max_rel_err(out, ref) <= 12 * TOL[W.F32]      # one layer's bound per layer
+    layers = _gpu_layers(wl)
+    ref, ref_kept, ref_cu, records = _oracle_stack(wl)
+    _teacher_forced(wl, layers, records)
+    sched = {wl.prune_after_layer: binding.prune_params(retention=wl.retention, window=wl.window, prune_mode=2)}
+    out, kept, new_cu = _gpu_stack(wl, layers)
+    c_out, c_kept, c_cu = _gpu_chain(wl, layers, sched)
+    assert torch.equal(out, c_out) and torch.equal(kept, c_kept) and torch.equal(new_cu, c_cu)
+    assert np.array_equal(host(new_cu), ref_cu)
+    nv, nt = _lens(wl)
+    assert out.shape[0] == binding.kept_count(nv, nt, wl.retention) == ref.shape[0] == kept.shape[0]
 
 
-def test_stack_ragged_bf16_prune_point():
-    # bf16 storage: layers 0-2 (the two full-activation layers and the pruning layer).  Rounding
-    # differences between the sides can flip later near-tied decisions, so the deep stack is
-    # checked in fp32 above and only the first three layers here.
-    wl = W.config5(n_layers=3, d=256, E=64, F=128, len_div=16, text_len=64)
-    out, kept, new_cu, nv, nt = _gpu_stack(wl)
-    ref, ref_kept, ref_cu = _oracle_stack(wl)
+def test_stack_without_stages_returns_the_identity_index_list():
+    wl = W.config5(n_layers=2, d=64, E=16, F=32, len_div=64, text_len=64, dtype=W.F32)
+    layers = _gpu_layers(wl)
+    out, kept, new_cu = _gpu_stack(wl, layers, schedule={})
+    c_out, _, _ = _gpu_chain(wl, layers, {})
+    assert torch.equal(out, c_out)
+    assert np.array_equal(host(kept), np.arange(wl.T)) and np.array_equal(host(new_cu), wl.cu_seqlens)
+
+
+def test_stack_ragged_bf16_teacher_forced():
+    # bf16 storage, config 5's schedule over six layers.  Rounding differences between the sides can flip
+    # later near-tied decisions of a free-running stack, so every GPU layer is fed the oracle's input for
+    # that layer: ids, kept set and permutation must then agree bit for bit and the outputs within 2e-2
+    # at every layer
+    wl = W.config5(n_layers=6, d=256, E=64, F=128, len_div=16, text_len=64)
+    layers = _gpu_layers(wl)
+    ref, ref_kept, ref_cu, records = _oracle_stack(wl)
+    _teacher_forced(wl, layers, records)
+    sched = {wl.prune_after_layer: binding.prune_params(retention=wl.retention, window=wl.window, prune_mode=2)}
+    out, kept, new_cu = _gpu_stack(wl, layers)
+    c_out, c_kept, c_cu = _gpu_chain(wl, layers, sched)
+    assert torch.equal(out, c_out) and torch.equal(kept, c_kept) and torch.equal(new_cu, c_cu)
+    nv, nt = _lens(wl)
     assert out.shape[0] == binding.kept_count(nv, nt, wl.retention) == ref.shape[0]
-    assert np.array_equal(new_cu, ref_cu)
-    same = np.intersect1d(kept, ref_kept).size / ref_kept.size
-    assert same >= 0.98                                   # kept sets agree but for flipped near-ties
-    if np.array_equal(kept, ref_kept):
-        assert max_rel_err(out, ref) <= 3 * TOL[W.BF16]
+    assert np.array_equal(host(new_cu), ref_cu)               # counts are exact whatever the near-ties do
+
+
+# ---------------------------------------------------------------- config 5 at its real size
+# 8 packed sequences (22016 tokens), d = 2048, 64 experts of 1408 + 2 shared, 12 layers of distinct
+# weights, k 6/6 in layers 0-1 and 6/3 from layer 2, pruning to 50 % once in layer 2.
+_C5 = {}
+
+
+def _c5():
+    if "wl" not in _C5:
+        _C5["wl"] = W.config5()
+        _C5["input"] = (_C5["wl"].x, _C5["wl"].is_visual, _C5["wl"].cu_seqlens)
+    return _C5["wl"]
+
+
+@pytest.mark.parametrize("layer", [0, 1, 2, 3])
+def test_config5_full_size_layers_teacher_forced(layer):
+    """Layers 0-3 of the full-size stack (two full-activation layers with about 2000 rows per expert, the
+    pruning layer, the first layer on the pruned batch), each on the oracle's own output of the layer
+    before it: every decision bit for bit, outputs on all kept rows."""
+    wl = _c5()
+    if layer > 0 and _C5.get("done") != layer - 1:
+        pytest.skip("needs the oracle's output of the layer before (run the layers in order)")
+    x_np, vis_np, cu_np = _C5["input"]
+    lw = wl.layers[layer]
+    kt, kv = wl.k_schedule[layer]
+    td = torch_dtype(wl)
+    m = binding.FMoE(d_model=wl.d, n_experts=wl.E, d_ffn=wl.F, n_shared=wl.n_shared, d_ffn_shared=wl.F_shared,
+                     k_text=kt, k_visual=kv, dtype=wl.dtype)
+    m.set_weights(dev(lw.router_w, td), dev(lw.router_bias), dev(lw.w_gate, td), dev(lw.w_up, td),
+                  dev(lw.w_down, td), dev(lw.ws_gate, td), dev(lw.ws_up, td), dev(lw.ws_down, td))
+    do_prune = layer == wl.prune_after_layer
+    o = _check_layer(m, wl, x_np, vis_np, cu_np, lw, kt, kv, do_prune, add_residual=True, what=f"c5 layer {layer}")
+    if layer < 2:
+        assert len(o["kept_idx"]) == wl.T and int(o["expert_offsets"][-1]) == 6 * wl.T
+    if do_prune:
+        nv, nt = _lens(wl)
+        assert len(o["kept_idx"]) == binding.kept_count(nv, nt, wl.retention)
+        vis_np, cu_np = vis_np[o["kept_idx"]], o["new_cu_seqlens"]
+    _C5["input"] = (o["out"], vis_np, cu_np)
+    _C5["done"] = layer
+    m.close()
+    del m
+    torch.cuda.empty_cache()
+
+
+def test_config5_full_size_stack_runs_all_twelve_layers():
+    """The whole config-5 stack at its real size through fmoe_stack_forward: row count, sequence bounds
+    and index list against the host bookkeeping, outputs finite; the first three layers re-run as
+    chained single-layer calls reproduce the stack's pruning decisions."""
+    import concurrent.futures as cf
+    wl = _c5()
+    td = torch_dtype(wl)
+
+    def make(l):
+        lw = wl.layers[l]
+        return lw
+
+    layers = []
+    with cf.ThreadPoolExecutor(max_workers=3) as ex:
+        for l, lw in enumerate(ex.map(make, range(len(wl.layers)))):
+            kt, kv = wl.k_schedule[l]
+            m = binding.FMoE(d_model=wl.d, n_experts=wl.E, d_ffn=wl.F, n_shared=wl.n_shared,
+                             d_ffn_shared=wl.F_shared, k_text=kt, k_visual=kv, dtype=wl.dtype)
+            m.set_weights(dev(lw.router_w, td), dev(lw.router_bias), dev(lw.w_gate, td), dev(lw.w_up, td),
+                          dev(lw.w_down, td), dev(lw.ws_gate, td), dev(lw.ws_up, td), dev(lw.ws_down, td),
+                          release_packed=True)
+            layers.append(m)
+    sched = {wl.prune_after_layer: binding.prune_params(retention=wl.retention, window=wl.window, prune_mode=2)}
+    out, kept, new_cu = _gpu_stack(wl, layers, sched)
+    nv, nt = _lens(wl)
+    n = binding.kept_count(nv, nt, wl.retention)
+    assert out.shape[0] == n == kept.shape[0]
+    kept_v = binding.kept_visual_lens(nv, wl.retention)
+    assert list(np.diff(host(new_cu))) == [v + t for v, t in zip(kept_v, nt)]
+    k = host(kept)
+    assert (np.diff(k) > 0).all() and k[0] >= 0 and k[-1] < wl.T
+    assert wl.is_visual[k].sum() == sum(kept_v) and (wl.is_visual[k] == 0).sum() == sum(nt)
+    assert torch.isfinite(out.float()).all()
+    # layers 0-2 as chained calls: same bits up to the stage, same kept set
+    x, vis, cu = inputs(wl)
+    for l in range(3):
+        layers[l].set_topk(*wl.k_schedule[l])
+        o, kp, nc, _ = layers[l].layer_forward(x, vis, cu, sched.get(l), add_residual=True)
+        x = o
+    assert torch.equal(kp[:n], kept) and torch.equal(nc, new_cu)
+    for m in layers:
+        m.close()
+    torch.cuda.empty_cache()
 
 
 # ---------------------------------------------------------------- diagnostics (the paper's analysis statistics)
@@ -718,7 +898,10 @@ def test_layer_forward_ablation_switches(seed, kw):
     new_cu = host(new_cu)
     n = int(new_cu[-1])
     assert np.array_equal(new_cu, o["new_cu_seqlens"]) and np.array_equal(host(kept)[:n], o["kept_idx"])
-    assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
+    assert_residual_outputs_close(host(out)[:n], o["out_f64"], _x_rows(wl, o), wl.dtype, "MinK + mean merge")
+    out2, _, _, _ = m.layer_forward(x, vis, cu, pp)
+    o2 = _oracle(wl, gamma=0.3, merge_mean=True, strategy=oracle.MINK, k_base=wl.k_text)
+    assert_outputs_close(host(out2)[:n], o2["out_f64"], wl.dtype, "MinK + mean merge, expert term")
     # mean mode alone, through fmoe_prune
     o_probs, _, _ = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias,
                                  wl.k_text, wl.k_visual)
@@ -776,7 +959,10 @@ def test_randomized_layer_sweep(seed):
     assert np.array_equal(host(kept)[:n], o["kept_idx"]), (kw, extra)
     assert np.array_equal(host(vis_out)[:n], wl.is_visual[o["kept_idx"]])
     if n:
-        assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype], (kw, extra)
+        assert_residual_outputs_close(host(out)[:n], o["out_f64"], _x_rows(wl, o), wl.dtype, str((kw, extra)))
+        out2, _, _, _ = m.layer_forward(x, vis, cu, pp, attn=dev(attn))
+        over["add_residual"] = False
+        assert_outputs_close(host(out2)[:n], _oracle(wl, **over)["out_f64"], wl.dtype, str((kw, extra)))
 
 
 @pytest.mark.parametrize("T_v,T_t,window", [
@@ -819,7 +1005,9 @@ def test_layer_forward_general_chain_at_the_widest_routing():
     n = int(new_cu[-1])
     assert np.array_equal(new_cu, o["new_cu_seqlens"])
     assert np.array_equal(host(kept)[:n], o["kept_idx"])
-    assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
+    assert_residual_outputs_close(host(out)[:n], o["out_f64"], _x_rows(wl, o), wl.dtype, "widest routing")
+    out2, _, _, _ = m.layer_forward(x, vis, cu, binding.prune_params(retention=wl.retention, window=wl.window))
+    assert_outputs_close(host(out2)[:n], _oracle(wl)["out_f64"], wl.dtype, "widest routing, expert term")
 
 
 @pytest.mark.parametrize("d,F", [(448, 576), (576, 640), (640, 704), (832, 960), (960, 448)])
@@ -835,7 +1023,9 @@ def test_expert_ffn_k_loop_lengths(d, F):
     out, kept, new_cu, _ = m.layer_forward(x, vis, cu, binding.prune_params(retention=0.5, window=3),
                                            add_residual=True)
     assert np.array_equal(host(kept)[:n], o["kept_idx"])
-    assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[W.BF16]
+    assert_residual_outputs_close(host(out)[:n], o["out_f64"], _x_rows(wl, o), wl.dtype, "k loop")
+    out2, _, _, _ = m.layer_forward(x, vis, cu, binding.prune_params(retention=0.5, window=3))
+    assert_outputs_close(host(out2)[:n], _oracle(wl)["out_f64"], wl.dtype, "k loop, expert term")
     y, ysh = m.expert_ffn(x, dev(o["kept_idx"]), n, dev(o["expert_offsets"]), dev(o["perm_src"]))
     M = int(o["expert_offsets"][-1])
     assert max_rel_err(host(y)[:M], o["y"]) <= TOL[W.BF16]
