@@ -201,6 +201,19 @@ int fmoe_permute(fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* kept_idx
                  const int32_t* n_kept_dev, int32_t* expert_offsets, int32_t* perm_src,
                  int32_t* inv_perm, void* ws, size_t ws_bytes, void* stream);
 
+/* fmoe_permute for callers that cannot allocate device memory or bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and bit-identical results; the scratch of the kernels (4.25 MiB) is a static device array that each
+ * GPU running the library holds until the process ends.  The call allocates nothing and is kernel
+ * launches only.  Limits: n_kept <= 65536 and n_kept * Kmax <= 2^20, else FMOE_ERR_UNSUPPORTED (use
+ * fmoe_permute).  All calls on one GPU share the array: calls that overlap on one GPU (different
+ * streams or threads) race and must be serialised by the caller; nothing has to be cleared between
+ * calls (every scratch entry a call reads it has written itself).  The context's GPU must be the
+ * current device, as for every other hot call. */
+int fmoe_permute_noalloc(fmoe_ctx* ctx, const int32_t* topk_idx, const int32_t* kept_idx, int32_t n_kept,
+                         const int32_t* n_kept_dev, int32_t* expert_offsets, int32_t* perm_src,
+                         int32_t* inv_perm, void* stream);
+
 /* The expert FFNs of Eq.4 as a grouped GEMM: for every row r of expert e,
  * y[r] = FFN_e(x[token(perm_src[r])]); the activation silu(.)*(.) is rounded to dtype between
  * the two products.  y [n_kept*Kmax capacity, H] dtype.  y_shared [N_s, n_kept, H] dtype or NULL

@@ -24,7 +24,7 @@ EXPORTS = ["fmoe_version", "fmoe_last_error", "fmoe_create", "fmoe_destroy", "fm
            "fmoe_profile_slots", "fmoe_profile_name", "fmoe_profile_read", "fmoe_adjacent_similarity",
            "fmoe_magnitude_stability", "fmoe_row_cosine", "fmoe_gate_cosine", "fmoe_flops_ratios",
            "fmoe_kept_counts", "fmoe_stage_retention", "fmoe_stack_plan", "fmoe_stack_workspace_bytes",
-           "fmoe_stack_forward"]
+           "fmoe_stack_forward", "fmoe_permute_noalloc"]
 
 
 class FmoeConfig(C.Structure):
@@ -83,6 +83,7 @@ def load():
     lib.fmoe_prune.argtypes = [vp, C.POINTER(FmoePruneParams), vp, vp, vp, i32, i32, vp, vp, vp, vp,
                                vp, vp, vp, vp, sz, vp]
     lib.fmoe_permute.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.fmoe_permute_noalloc.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.fmoe_expert_ffn.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fmoe_combine.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.fmoe_layer_forward.argtypes = [vp, C.POINTER(FmoePruneParams), vp, vp, vp, i32, i32, vp,
@@ -253,6 +254,15 @@ class FMoE:
         ws = self.workspace(n_kept, 1)
         _check(self.lib.fmoe_permute(self._ctx, _ptr(topk_idx), _ptr(kept_idx), n_kept, _ptr(n_kept_dev),
                                      _ptr(offs), _ptr(perm), _ptr(inv), _ptr(ws), ws.numel(), _stream()))
+        return offs, perm, inv
+
+    def permute_noalloc(self, topk_idx, kept_idx, n_kept, n_kept_dev=None):
+        """fmoe_permute_noalloc: the same permutation with the kernels' scratch in the library's static
+        device array (no workspace, no allocation inside the call; outputs are the caller's)."""
+        K = max(self.kmax, 1)
+        offs, perm, inv = self._i32(self.E + 1), self._i32(max(n_kept * K, 1)), self._i32(max(n_kept, 1), K)
+        _check(self.lib.fmoe_permute_noalloc(self._ctx, _ptr(topk_idx), _ptr(kept_idx), n_kept, _ptr(n_kept_dev),
+                                             _ptr(offs), _ptr(perm), _ptr(inv), _stream()))
         return offs, perm, inv
 
     def expert_ffn(self, x, kept_idx, n_kept, expert_offsets, perm_src, n_kept_dev=None):

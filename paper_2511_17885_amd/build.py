@@ -27,6 +27,7 @@ SOURCES = {
     "combine.hip": [],
     "diag.hip": [],
     "stack.hip": [],
+    "noalloc.hip": [],
 }
 
 

@@ -333,3 +333,21 @@ def test_four_gib_extents_and_empty_sequence_lists_are_refused(lib):
                           dummy, 0, None) == -1
     assert b"no sequence" in lib.fmoe_last_error()
     lib.fmoe_destroy(ctx)
+
+
+def test_permute_noalloc_refuses_sizes_beyond_its_static_scratch(lib):
+    cfg = binding.FmoeConfig(64, 8, 32, 0, 0, 8, 1, 1, binding.FMOE_F32)
+    ctx = C.c_void_p()
+    assert lib.fmoe_create(C.byref(ctx), C.byref(cfg), 0) == 0
+    dummy = C.c_void_p(0x1000)
+    call = lambda n: lib.fmoe_permute_noalloc(ctx, dummy, None, n, None, dummy, dummy, dummy, None)
+    assert call(65537) == -5 and b"static scratch" in lib.fmoe_last_error()
+    assert call(-1) == -1
+    assert lib.fmoe_set_topk(ctx, 8, 8) == 0
+    assert lib.fmoe_permute_noalloc(ctx, dummy, None, 16, None, None, dummy, dummy, None) == -2
+    lib.fmoe_destroy(ctx)
+    big = binding.FmoeConfig(64, 32, 32, 0, 0, 16, 16, 1, binding.FMOE_F32)   # 65536 x 16 = 2^20 slots: the limit
+    assert lib.fmoe_create(C.byref(ctx), C.byref(big), 0) == 0
+    assert lib.fmoe_permute_noalloc(ctx, dummy, None, 65536, None, None, dummy, dummy, None) == -2   # passes the size check
+    lib.fmoe_destroy(ctx)
+    assert lib.fmoe_permute_noalloc(None, dummy, None, 4, None, dummy, dummy, dummy, None) == -2
