@@ -31,10 +31,43 @@ SOURCES = {
 }
 
 
+def check_accumulation_registers(asm_path):
+    """The dense-shape expert GEMM kernels (ffn_dense_kernel) keep their accumulators in accumulation
+    registers that the kernel names itself, which the compiler's register allocator does not see.  This
+    reads the device assembly the compiler wrote for ffn.hip and fails if, inside those kernels, the
+    compiler placed anything of its own in an accumulation register (any a<N> operand outside the
+    kernel's own inline-assembly blocks)."""
+    import re
+    inside = in_asm = False
+    kernels = 0
+    for n, line in enumerate(open(asm_path), 1):
+        if re.match(r"^_ZN\S*ffn_dense_kernel\S*:", line):
+            inside, in_asm = True, False
+            kernels += 1
+            name = line.split(":")[0]
+            continue
+        if not inside:
+            continue
+        if "s_endpgm" in line:
+            inside = False
+        elif "ASMSTART" in line:
+            in_asm = True
+        elif "ASMEND" in line:
+            in_asm = False
+        elif not in_asm and re.search(r"\ba\[?\d", line.split(";")[0]):
+            raise RuntimeError(f"{asm_path}:{n}: the compiler uses an accumulation register inside {name}, which "
+                               f"keeps hand-placed accumulators there: {line.strip()}")
+    if kernels == 0:
+        raise RuntimeError(f"{asm_path}: no ffn_dense_kernel found to check")
+    return kernels
+
+
 def _compile(name, extra, verbose):
     src = os.path.join(CSRC, name)
     obj = os.path.join(OBJ, name.replace(".hip", ".o"))
     cmd = ["hipcc", "-c", src, "-o", obj] + COMMON + extra
+    if name == "ffn.hip":
+        cmd.append("-save-temps=obj")   # keeps the device assembly beside the object, for the check below
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -44,6 +77,8 @@ def _compile(name, extra, verbose):
         raise RuntimeError(f"hipcc failed on {name}:\n{err}")
     if err.strip() and verbose:
         print(err, flush=True)
+    if name == "ffn.hip":
+        check_accumulation_registers(os.path.join(OBJ, "ffn-hip-amdgcn-amd-amdhsa-gfx950.s"))
     return obj
 
 

@@ -566,7 +566,7 @@ const char* fmoe_profile_name(int slot) {
       "route_kernel", "seq_ordinals_kernel", "window_score_kernel", "select_kernel", "compact_kernel",
       "prune_dispatch_small_kernel", "permute_count_kernel", "permute_scan_kernel",
       "permute_scatter_kernel", "build_tiles_kernel", "ffn_stream_kernel<true>",
-      "ffn_stream_kernel<false>", "combine_kernel"};
+      "ffn_stream_kernel<false>", "combine_kernel", "ffn_dense_kernel<true>", "ffn_dense_kernel<false>"};
   return (slot >= 0 && slot < SLOT_COUNT) ? names[slot] : "";
 }
 

@@ -14,12 +14,13 @@
 #define FMOE_TILE_M 64        // rows per grouped-GEMM tile (tile list granularity)
 #define FMOE_TILE_RUN 8       // row tiles per run of a group in the tile lists
 #define FMOE_SEG_MIN_TILES 256   // tile entries from which each XCD takes a contiguous segment of the list
+#define FMOE_DENSE_MIN_ROWS 768  // routed-row capacity per expert from which the expert GEMMs take their dense shape
 
 // ---- optional per-kernel timing (instrumentation; off by default)
 enum fmoe_kernel_slot {
   SLOT_ROUTE = 0, SLOT_ORDINALS, SLOT_SCORES, SLOT_SELECT, SLOT_COMPACT, SLOT_DISPATCH,
   SLOT_PERM_COUNT, SLOT_PERM_SCAN, SLOT_PERM_SCATTER, SLOT_TILES, SLOT_GEMM1, SLOT_GEMM2,
-  SLOT_COMBINE, SLOT_COUNT
+  SLOT_COMBINE, SLOT_GEMM1_DENSE, SLOT_GEMM2_DENSE, SLOT_COUNT
 };
 struct fmoe_prof {
   bool on;

@@ -30,6 +30,7 @@
 // The fp32 storage type (a correctness configuration) uses a plain LDS-tiled kernel on the fp32
 // MFMA with the caller's weight layout.
 
+#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -49,8 +50,17 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
 // ======================================================================== bf16: weight-stream kernel
 constexpr int SBM = 128;        // rows per tile: 8 MFMA row blocks of 16
 constexpr int SBK = 64;         // k per tile: two 32-wide MFMA steps; one LDS row = 128 bytes
-constexpr int A_STAGES = 4;     // LDS ring of activation k-tiles
-constexpr int B_SLOTS = 4;      // register ring of weight k-tiles
+constexpr int A_STAGES = 4;     // LDS ring of activation k-tiles (weight-stream shape)
+constexpr int B_SLOTS = 4;      // register ring of weight k-tiles (weight-stream shape)
+// The dense shape of the kernel, for long row lists (hundreds of rows per expert, where the matrix pipes
+// and not the weight stream bound the kernel): a workgroup owns 128 rows x 16 column blocks, i.e. each
+// wavefront four column blocks instead of one, with one wavefront per SIMD and the whole register file.
+// A wavefront's activation fragments then feed four times as many matrix instructions, so the LDS reads
+// per flop drop to a quarter and the L2 reads per flop (one activation tile per 16 instead of 4 column
+// blocks) to about a half; since no second wavefront shares the SIMD, the fragments of the next group
+// of matrix instructions are fetched from LDS while the current group executes.
+constexpr int DA_STAGES = 4;    // LDS ring of activation k tiles (64 wide)
+constexpr int DB_SLOTS = 4;     // register ring of weight k steps (32 wide)
 
 struct StreamProblem {
   const bf16_t* A;            // [*, lda]
@@ -76,7 +86,8 @@ struct StreamArgs {
   int E;
   const fmoe_tile* tiles;
   const int32_t* n_tiles;     // device
-  int cols;                   // column tiles per tile entry in this launch
+  int cols;                   // work items per tile entry in this launch (column tiles, or groups of them)
+  int cols_entry;             // column tiles per tile entry
 };
 
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt = bits 15:14 | 3:0)
@@ -129,6 +140,49 @@ __device__ __forceinline__ void lds_read_frags(uint32_t addr, u32x4_t (&f)[NRB])
                  : "v"(addr) : "memory");
   }
 }
+// The same reads without the wait: lds_issue_frags starts them, lds_settle_frags waits for them and is
+// the point from which the compiler may use the registers (they are in/out operands of the wait).
+template <int NRB>
+__device__ __forceinline__ void lds_issue_frags(uint32_t addr, u32x4_t (&f)[NRB]) {
+  static_assert(NRB == 2 || NRB == 3 || NRB == 4, "supported fragment counts");
+  if constexpr (NRB == 2) {
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:2048"
+                 : "=&v"(f[0]), "=&v"(f[1]) : "v"(addr) : "memory");
+  } else if constexpr (NRB == 3) {
+    asm volatile("ds_read_b128 %0, %3\n\tds_read_b128 %1, %3 offset:2048\n\tds_read_b128 %2, %3 offset:4096"
+                 : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]) : "v"(addr) : "memory");
+  } else {
+    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:2048\n\t"
+                 "ds_read_b128 %2, %4 offset:4096\n\tds_read_b128 %3, %4 offset:6144"
+                 : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]), "=&v"(f[3]) : "v"(addr) : "memory");
+  }
+}
+// ... and with a compile-time byte offset OFF on top of the address register, so that one register serves
+// every stage of the ring
+template <int NRB, int OFF>
+__device__ __forceinline__ void lds_issue_frags_at(uint32_t addr, u32x4_t (&f)[NRB]) {
+  static_assert(NRB == 2 || NRB == 4, "supported fragment counts");
+  static_assert(OFF >= 0 && OFF + (NRB - 1) * 2048 < 65536, "offset field of an LDS instruction");
+  if constexpr (NRB == 2) {
+    asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4"
+                 : "=&v"(f[0]), "=&v"(f[1]) : "v"(addr), "n"(OFF), "n"(OFF + 2048) : "memory");
+  } else {
+    asm volatile("ds_read_b128 %0, %4 offset:%5\n\tds_read_b128 %1, %4 offset:%6\n\t"
+                 "ds_read_b128 %2, %4 offset:%7\n\tds_read_b128 %3, %4 offset:%8"
+                 : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]), "=&v"(f[3])
+                 : "v"(addr), "n"(OFF), "n"(OFF + 2048), "n"(OFF + 4096), "n"(OFF + 6144) : "memory");
+  }
+}
+template <int NRB>
+__device__ __forceinline__ void lds_settle_frags(u32x4_t (&f)[NRB]) {
+  if constexpr (NRB == 2) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]) : : "memory");
+  } else if constexpr (NRB == 3) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]) : : "memory");
+  } else {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) : : "memory");
+  }
+}
 #define FMOE_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 // One (row tile, column tile) work item.  NAB = number of live 32-row bands of the tile (1..4):
@@ -152,13 +206,90 @@ __device__ __forceinline__ void block_barrier() {
   asm volatile("" ::: "memory");
 }
 
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {   // f(integral_constant<int, i>) for i in [I, N)
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+// Byte offsets (into the buffer descriptor over P.A) of the activation rows this lane fetches: rows
+// 32*it + 8*wave + lane/8 of the tile, through the two-level gather; rows past the tile reuse its last row.
+template <int NAB>
+__device__ __forceinline__ void gather_offsets(const StreamProblem& P, const fmoe_tile& tile, uint32_t (&a_src)[NAB]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t a_max_row = 0xffffffffu / ((uint32_t)P.lda * 2u) - 1u;
+#pragma unroll
+  for (int it = 0; it < NAB; ++it) {
+    const int r = 32 * it + 8 * wave + (lane >> 3);
+    int src = tile.row0 + (r < tile.rows ? r : tile.rows - 1);
+    if (P.map1) {
+      src = P.map1[src];
+      if (P.map1_limit > 0) src = src < 0 ? 0 : (src >= P.map1_limit ? P.map1_limit - 1 : src);
+    }
+    if (P.map2) src = P.map2[src];
+    src = (uint32_t)src < a_max_row ? src : (int)a_max_row;   // offsets stay below 4 GiB whatever the input
+    a_src[it] = (uint32_t)src * (uint32_t)P.lda * 2u;
+  }
+}
+
+// Epilogue of one 128-row x 4-column-block output tile (column tile nt of the packing): accumulator
+// register v of lane l holds row 4*(l/16) + v, column l%16 of a 16x16 block.  The tile is transposed
+// through LDS (the activation ring, free once every wavefront has passed the opening barrier) so that
+// global memory sees whole 128/256-byte row segments instead of 32-byte pieces.
+template <bool SWIGLU, int NAB, int STAGES, typename ACC>
+__device__ __forceinline__ void store_tile(const StreamProblem& P, const fmoe_tile& tile, int nt, ACC acc,
+                                           bf16_t* As) {   // acc(rb, f): accumulator of row block rb, fragment f
+  constexpr int NRB = 2 * NAB;
+  constexpr int BC = SWIGLU ? 64 : 128;    // output columns of the block
+  constexpr int CS = BC + 8;               // LDS row stride (elements): rows 4 apart land 16 banks apart
+  static_assert(SBM * CS <= STAGES * SBM * SBK, "output tile fits in the activation ring");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int N = P.N;
+  __syncthreads();   // every wavefront is done with what the ring held
+  static_for<0, NRB>([&](auto rbc) {
+    constexpr int rb = decltype(rbc)::value;
+    const f32x4_t c0 = acc(rbc, std::integral_constant<int, 0>{});
+    const f32x4_t c1 = acc(rbc, std::integral_constant<int, 1>{});
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int row = rb * 16 + 4 * (lane >> 4) + v;
+      if (SWIGLU) {
+        As[row * CS + wave * 16 + (lane & 15)] = f32_to_bf16(silu_mul(c0[v], c1[v]));
+      } else {
+        As[row * CS + wave * 32 + (lane & 15)] = f32_to_bf16(c0[v]);
+        As[row * CS + wave * 32 + 16 + (lane & 15)] = f32_to_bf16(c1[v]);
+      }
+    }
+  });
+  __syncthreads();
+  constexpr int CPR = BC / 8;              // 16-byte chunks per row
+  constexpr int RPP = 256 / CPR;           // rows per pass of the block
+  const int col = nt * BC + (tid % CPR) * 8;
+  const bool vec_ok = ((P.ldc & 7) == 0) && (col + 8 <= N) &&
+                      ((reinterpret_cast<uintptr_t>(P.C) & 15) == 0);
+#pragma unroll
+  for (int r0 = 0; r0 < 32 * NAB; r0 += RPP) {
+    const int row = r0 + tid / CPR;
+    if (row >= tile.rows || col >= N) continue;
+    const bf16_t* src = &As[row * CS + (tid % CPR) * 8];
+    bf16_t* dst = P.C + (size_t)(tile.row0 + row) * P.ldc + col;
+    if (vec_ok) {
+      *reinterpret_cast<u32x4_t*>(dst) = *reinterpret_cast<const u32x4_t*>(src);
+    } else {
+      for (int i = 0; i < 8 && col + i < N; ++i) dst[i] = src[i];
+    }
+  }
+}
+
 template <bool SWIGLU, int NAB>
 __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_tile& tile, int group, int nt,
                                             bf16_t* As) {
   constexpr int NRB = 2 * NAB;   // 16-row MFMA blocks computed
   constexpr int PER_STEP = NAB + 4;   // loads a wavefront issues per k step
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int N = P.N, K = P.K;
+  const int K = P.K;
   const int NT = (K + SBK - 1) / SBK;
 
   // this workgroup's weight stream: tile nt of the packing, 16 KB per k tile, 4 KB per wavefront
@@ -174,19 +305,7 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
   const __amdgpu_buffer_rsrc_t a_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(P.A), 0, 0xffffffff, 0x00020000);
   const int a_kc = ((lane & 7) ^ ((4 * wave + (lane >> 4)) & 7)) * 8;
-  const uint32_t a_max_row = 0xffffffffu / ((uint32_t)P.lda * 2u) - 1u;
-#pragma unroll
-  for (int it = 0; it < NAB; ++it) {
-    const int r = 32 * it + 8 * wave + (lane >> 3);
-    int src = tile.row0 + (r < tile.rows ? r : tile.rows - 1);
-    if (P.map1) {
-      src = P.map1[src];
-      if (P.map1_limit > 0) src = src < 0 ? 0 : (src >= P.map1_limit ? P.map1_limit - 1 : src);
-    }
-    if (P.map2) src = P.map2[src];
-    src = (uint32_t)src < a_max_row ? src : (int)a_max_row;   // offsets stay below 4 GiB whatever the input
-    a_src[it] = (uint32_t)src * (uint32_t)P.lda * 2u;
-  }
+  gather_offsets<NAB>(P, tile, a_src);
 
   f32x4_t acc[NRB][2];
 #pragma unroll
@@ -335,44 +454,7 @@ __device__ __forceinline__ void stream_tile(const StreamProblem& P, const fmoe_t
     default: break;   // 0: K is a multiple of the steady loop's stride plus its look-ahead
   }
 
-  // epilogue: accumulator register v of lane l holds row 4*(l/16) + v, column l%16 of a 16x16 block.
-  // The block's output tile is transposed through LDS (the activation ring is free by now) so that
-  // global memory sees whole 128/256-byte row segments instead of 32-byte pieces.
-  constexpr int BC = SWIGLU ? 64 : 128;    // output columns of the block
-  constexpr int CS = BC + 8;               // LDS row stride (elements): rows 4 apart land 16 banks apart
-  static_assert(SBM * CS <= A_STAGES * SBM * SBK, "output tile fits in the activation ring");
-  block_barrier();   // every wavefront has read its last operands
-#pragma unroll
-  for (int rb = 0; rb < NRB; ++rb) {
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int row = rb * 16 + 4 * (lane >> 4) + v;
-      if (SWIGLU) {
-        As[row * CS + wave * 16 + (lane & 15)] = f32_to_bf16(silu_mul(acc[rb][0][v], acc[rb][1][v]));
-      } else {
-        As[row * CS + wave * 32 + (lane & 15)] = f32_to_bf16(acc[rb][0][v]);
-        As[row * CS + wave * 32 + 16 + (lane & 15)] = f32_to_bf16(acc[rb][1][v]);
-      }
-    }
-  }
-  __syncthreads();
-  constexpr int CPR = BC / 8;              // 16-byte chunks per row
-  constexpr int RPP = 256 / CPR;           // rows per pass of the block
-  const int col = nt * BC + (tid % CPR) * 8;
-  const bool vec_ok = ((P.ldc & 7) == 0) && (col + 8 <= N) &&
-                      ((reinterpret_cast<uintptr_t>(P.C) & 15) == 0);
-#pragma unroll
-  for (int r0 = 0; r0 < 32 * NAB; r0 += RPP) {
-    const int row = r0 + tid / CPR;
-    if (row >= tile.rows || col >= N) continue;
-    const bf16_t* src = &As[row * CS + (tid % CPR) * 8];
-    bf16_t* dst = P.C + (size_t)(tile.row0 + row) * P.ldc + col;
-    if (vec_ok) {
-      *reinterpret_cast<u32x4_t*>(dst) = *reinterpret_cast<const u32x4_t*>(src);
-    } else {
-      for (int i = 0; i < 8 && col + i < N; ++i) dst[i] = src[i];
-    }
-  }
+  store_tile<SWIGLU, NAB, A_STAGES>(P, tile, nt, [&](auto rb, auto f) { return acc[rb][f]; }, As);
 }
 
 template <bool SWIGLU>
@@ -439,6 +521,253 @@ __global__ __launch_bounds__(256, 2) void ffn_stream_kernel(StreamArgs a) {
     case 3: stream_tile<SWIGLU, 3>(P, tile, group, nt, As); break;
     default: stream_tile<SWIGLU, 4>(P, tile, group, nt, As); break;
   }
+}
+
+// The dense shape keeps its 64 accumulators (256 registers, the whole accumulation register file of a
+// wavefront) in registers it names itself: accumulator IDX is a[4*IDX : 4*IDX+3].  The compiler's
+// allocator cannot place that many accumulators (it moves them through the vector registers and
+// spills), and, being volatile, the instructions keep their place between the LDS reads that are
+// started before a group of them and waited for after it.  The compiler does not see these registers:
+// dense_claim_acc() tells it that the kernel owns them (so that a wavefront is given all 512
+// registers), the build scans the generated code of the dense kernel and fails if the compiler itself
+// placed anything in an accumulation register, and the parity tests run this shape on every size.
+template <int IDX>
+__device__ __forceinline__ void mfma_at(bf16x8_t a, bf16x8_t b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 a[%0:%1], %2, %3, a[%0:%1]" : : "n"(4 * IDX), "n"(4 * IDX + 3), "v"(a), "v"(b));
+}
+template <int IDX>
+__device__ __forceinline__ f32x4_t read_acc() {
+  float r0, r1, r2, r3;
+  asm volatile("v_accvgpr_read_b32 %0, a[%4]\n\tv_accvgpr_read_b32 %1, a[%5]\n\t"
+               "v_accvgpr_read_b32 %2, a[%6]\n\tv_accvgpr_read_b32 %3, a[%7]"
+               : "=v"(r0), "=v"(r1), "=v"(r2), "=v"(r3)
+               : "n"(4 * IDX), "n"(4 * IDX + 1), "n"(4 * IDX + 2), "n"(4 * IDX + 3));
+  return f32x4_t{r0, r1, r2, r3};
+}
+#include "dense_regs.inc"   // dense_claim_acc(): zeroes a0..a255 and lists them as written
+
+// ---- the dense shape: one (row tile, group of DNCB column tiles) work item per workgroup.
+// Wavefront w owns column block w of each of the DNCB column tiles nt4 .. nt4+DNCB-1 of the packing (so
+// the epilogue of the weight-stream shape serves each of them in turn).  Column tiles at or past
+// `ct_limit` do not belong to this work item: their weights are still fetched (clamped into the packing,
+// so that every load stays unconditional) but nothing is stored for them.
+// The k loop advances in steps of 32: the weights of a step are one register-ring slot (DB_SLOTS slots,
+// DB_SLOTS-1 steps in flight), the activations stay in k tiles of 64 in the LDS ring (DA_STAGES tiles,
+// DA_STAGES-1 in flight) with one workgroup barrier per tile.  Every step issues its loads
+// unconditionally -- past the end of the reduction they fetch the last step / tile again, into slots
+// nobody reads -- so the number of loads in flight at every wait is a compile-time constant and there
+// is no separate code for the last steps.
+// Per step and group of HB row blocks a wavefront issues HB LDS reads for 2*HB*DNCB matrix instructions;
+// the reads of the next group are issued before the current group's matrix instructions and waited for
+// after them.
+template <bool SWIGLU, int NAB, int DNCB>
+__device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_tile& tile, int group, int nt4,
+                                           int ct_limit, bf16_t* As) {
+  constexpr int NRB = 2 * NAB;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // the wavefront's number as a scalar: what depends on it alone (LDS destinations of the direct loads,
+  // the base of the weight stream) is then computed once per wavefront, not per lane
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int K = P.K;
+  const int NT = (K + SBK - 1) / SBK;
+  const int NKS = 2 * NT;
+  const int n_pack_tiles = (P.nbw + 3) / 4;
+
+  // weight stream of column tile j: one buffer descriptor over the packed weights, a wavefront-uniform
+  // byte offset (scalar) and the lane's 16 bytes (one vector register for all loads); the host refuses
+  // this shape when the packed weights of a launch exceed 4 GiB
+  const __amdgpu_buffer_rsrc_t b_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4_t*>(P.Bp), 0, 0xffffffff, 0x00020000);
+  uint32_t bbase[DNCB];
+#pragma unroll
+  for (int j = 0; j < DNCB; ++j) {
+    int pt = nt4 + j;
+    pt = pt < n_pack_tiles ? pt : n_pack_tiles - 1;
+    bbase[j] = (uint32_t)(((size_t)group * P.group_stride + (size_t)pt * (P.ks / 2) * 1024 + wave * 256) * 16);
+  }
+  const uint32_t lane16 = (uint32_t)lane * 16u;
+  uint32_t a_src[NAB];
+  const __amdgpu_buffer_rsrc_t a_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(P.A), 0, 0xffffffff, 0x00020000);
+  const int a_kc = ((lane & 7) ^ ((4 * wave + (lane >> 4)) & 7)) * 8;
+  gather_offsets<NAB>(P, tile, a_src);
+
+  dense_claim_acc<DNCB * 64>();   // accumulator (j, rb, f) is number (j*NRB + rb)*2 + f, all zero now
+
+  u32x4_t breg[DB_SLOTS][DNCB][2];   // [ring slot][column tile][fragment]
+  // weights of k step ks (clamped to the last one): two fragments per column tile
+  auto loadB1 = [&](int slot, int ks, int i) {   // load i of the step's 2*DNCB
+    const int kc = ks < NKS ? ks : NKS - 1;
+    const uint32_t koff = (uint32_t)(((kc >> 1) * 1024 + (kc & 1) * 128 + (i & 1) * 64) * 16);   // uniform
+    breg[slot][i >> 1][i & 1] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, lane16, bbase[i >> 1] + koff, 0);
+  };
+  // activations of k tile t (clamped to the last one); k past K re-reads the row's last chunk, where
+  // the packed weights are zero
+  auto loadA1 = [&](int stage, int t, int it) {
+    const int tc = t < NT ? t : NT - 1;
+    const int k = tc * SBK + a_kc;
+    const int kk = k < K ? k : K - 8;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        a_rsrc, FMOE_LPTR(As + stage * (SBM * SBK) + (32 * it + 8 * wave) * SBK), 16,
+        a_src[it] + (uint32_t)kk * 2u, 0, 0, 0);
+  };
+  const uint32_t lds0 = (uint32_t)(uintptr_t)FMOE_LPTR(As);
+  const uint32_t frag_row = lds0 + (uint32_t)(lane & 15) * (SBK * 2);
+  const uint32_t frag_a0 = frag_row + (uint32_t)(((lane >> 4)) ^ ((lane & 15) >> 1)) * 16;
+  const uint32_t frag_a1 = frag_row + (uint32_t)(((lane >> 4) + 4) ^ ((lane & 15) >> 1)) * 16;
+
+  constexpr int HB = (NRB > 4) ? NRB / 2 : NRB;   // row blocks whose operands are fetched together
+  constexpr int NH = NRB / HB;                    // such groups per k step
+  constexpr int B_AHEAD = DB_SLOTS - 1, A_AHEAD = DA_STAGES - 1;
+  constexpr int UNROLL = 2 * DA_STAGES;           // k steps per round: ring indices are compile-time
+  static_assert(UNROLL % DB_SLOTS == 0, "ring indices must be static");
+  static_assert(2 * A_AHEAD >= B_AHEAD, "a tile's activations are issued before its weights");
+  // loads newer than the weights of the step about to run: those of the last B_AHEAD-1 steps, of which
+  // every second one also carries a tile of activations
+  constexpr int NEWER_EVEN = (B_AHEAD - 1) * 2 * DNCB + ((B_AHEAD - 1) / 2) * NAB;        // before an even step
+  constexpr int NEWER_ODD = (B_AHEAD - 1) * 2 * DNCB + (B_AHEAD / 2) * NAB;               // before an odd step
+
+  // With one wavefront per SIMD (DNCB 4) the next group's fragments are fetched while the current group
+  // multiplies; with two (DNCB 2) the other wavefront covers the LDS latency and registers are short.
+  constexpr bool PREFETCH = DNCB == 4;
+  u32x4_t fa[PREFETCH ? 2 : 1][HB];
+  // k step `ks` = round base + U (U static): products of the step, loads of the steps further on
+  auto kstep = [&](auto uc, int ks) {
+    constexpr int U = decltype(uc)::value;
+    constexpr int slot = U % DB_SLOTS, s = U & 1, stage = (U >> 1) % DA_STAGES;
+    constexpr int new_slot = (U + B_AHEAD) % DB_SLOTS, new_stage = ((U >> 1) + A_AHEAD) % DA_STAGES;
+    constexpr int NL = 2 * DNCB + (s == 0 ? NAB : 0);   // loads this step issues
+    constexpr int stage_off = stage * (SBM * SBK * 2);
+    if constexpr (s == 0) {
+      FMOE_WAIT_VM(NEWER_EVEN);
+      block_barrier();   // every wavefront's share of the tile is in LDS; all are done with the tile before
+      if constexpr (PREFETCH) {
+        lds_issue_frags_at<HB, stage_off>(frag_a0, fa[0]);
+        lds_settle_frags<HB>(fa[0]);
+      }
+    } else {
+      FMOE_WAIT_VM(NEWER_ODD);
+    }
+    static_for<0, NH>([&](auto hc) {
+      constexpr int h = decltype(hc)::value;
+      constexpr int g = s * NH + h;            // group within the tile
+      constexpr int h0 = h * HB;
+      constexpr int cur = PREFETCH ? (g & 1) : 0;
+      if constexpr (!PREFETCH) {
+        lds_issue_frags_at<HB, stage_off + h0 * 2048>(s ? frag_a1 : frag_a0, fa[0]);
+        lds_settle_frags<HB>(fa[0]);
+      } else if constexpr (g + 1 < 2 * NH) {   // the next group's fragments travel while this group multiplies
+        constexpr int s1 = (g + 1) / NH, h1 = ((g + 1) % NH) * HB;
+        lds_issue_frags_at<HB, stage_off + h1 * 2048>(s1 ? frag_a1 : frag_a0, fa[(g + 1) & 1]);
+      }
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {           // load i of the step goes out with group i*NH/NL
+        if ((i * NH) / NL != h) continue;
+        if (s == 0 && i < NAB) loadA1(new_stage, (ks >> 1) + A_AHEAD, i);
+        else loadB1(new_slot, ks + B_AHEAD, i - (s == 0 ? NAB : 0));
+      }
+      static_for<0, DNCB>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        const bf16x8_t fb0 = __builtin_bit_cast(bf16x8_t, breg[slot][j][0]);
+        const bf16x8_t fb1 = __builtin_bit_cast(bf16x8_t, breg[slot][j][1]);
+        static_for<0, HB>([&](auto rc) {
+          constexpr int rb = decltype(rc)::value;
+          const bf16x8_t a8 = __builtin_bit_cast(bf16x8_t, fa[cur][rb]);
+          mfma_at<(j * NRB + h0 + rb) * 2>(a8, fb0);
+          mfma_at<(j * NRB + h0 + rb) * 2 + 1>(a8, fb1);
+        });
+      });
+      if constexpr (PREFETCH && g + 1 < 2 * NH) lds_settle_frags<HB>(fa[(g + 1) & 1]);
+    });
+  };
+
+  // prologue: what the steps before the first would have issued, in their order (activations reach
+  // 2*A_AHEAD steps back, weights B_AHEAD)
+  static_for<0, 2 * A_AHEAD>([&](auto qc) {
+    constexpr int q = decltype(qc)::value - 2 * A_AHEAD;   // step number, negative
+    if constexpr ((q + 2 * A_AHEAD) % 2 == 0) {            // an even step: activations of tile q/2 + A_AHEAD
+      constexpr int t = q / 2 + A_AHEAD;
+#pragma unroll
+      for (int it = 0; it < NAB; ++it) loadA1(t % DA_STAGES, t, it);
+    }
+    if constexpr (q + B_AHEAD >= 0) {
+#pragma unroll
+      for (int i = 0; i < 2 * DNCB; ++i) loadB1((q + B_AHEAD) % DB_SLOTS, q + B_AHEAD, i);
+    }
+    asm volatile("" ::: "memory");
+  });
+  int ks0 = 0;
+  for (; ks0 + UNROLL <= NKS; ks0 += UNROLL)
+    static_for<0, UNROLL>([&](auto uc) { kstep(uc, ks0 + decltype(uc)::value); });
+  switch (NKS - ks0) {   // left-over steps (an even number below UNROLL), uniform
+    case 2: static_for<0, 2>([&](auto uc) { kstep(uc, ks0 + decltype(uc)::value); }); break;
+    case 4: static_for<0, 4>([&](auto uc) { kstep(uc, ks0 + decltype(uc)::value); }); break;
+    case 6: static_for<0, 6>([&](auto uc) { kstep(uc, ks0 + decltype(uc)::value); }); break;
+    default: break;
+  }
+  static_assert(UNROLL == 8, "the switch above covers 2, 4 and 6 left-over steps");
+  FMOE_WAIT_VM(0);   // the loads issued past the end have landed before the ring is reused
+  // the last matrix instructions have retired before their accumulators are read (24 idle cycles
+  // cover the longest read-after-write distance of a 16x16x32 instruction)
+  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+  static_for<0, DNCB>([&](auto jc) {
+    constexpr int j = decltype(jc)::value;
+    if (nt4 + j < ct_limit)   // uniform
+      store_tile<SWIGLU, NAB, DA_STAGES>(P, tile, nt4 + j, [&](auto rbc, auto fc) {
+        return read_acc<(j * NRB + decltype(rbc)::value) * 2 + decltype(fc)::value>();
+      }, As);
+  });
+}
+
+// Work decode as in ffn_stream_kernel, with column tiles taken DNCB at a time (a.cols = such groups per
+// tile entry, a.cols_entry = column tiles per tile entry).
+template <bool SWIGLU, int DNCB>
+__global__ __launch_bounds__(256, DNCB == 4 ? 1 : 2) void ffn_dense_kernel(StreamArgs a) {
+  __shared__ __align__(16) bf16_t As[DA_STAGES * SBM * SBK];
+  const int n_tiles = *a.n_tiles;
+  const int item = blockIdx.x;
+  const int xcd = item & 7;
+  const int rr = item >> 3;
+  const int batch = rr / a.cols;
+  int nt_launch = rr - batch * a.cols;
+  int ti;
+  if (n_tiles >= FMOE_SEG_MIN_TILES) {
+    const int s0 = (int)(((long long)n_tiles * xcd) >> 3);
+    const int s1 = (int)(((long long)n_tiles * (xcd + 1)) >> 3);
+    if (batch >= s1 - s0) return;
+    ti = s0 + batch;
+  } else {
+    ti = batch * 8 + xcd;
+    if (ti >= n_tiles) return;
+  }
+  fmoe_tile tile = a.tiles[ti];
+  const bool shared = tile.group >= a.E;
+  StreamProblem P;
+#define FMOE_SEL(f) P.f = shared ? a.p1.f : a.p0.f
+  FMOE_SEL(A); FMOE_SEL(lda); FMOE_SEL(map1); FMOE_SEL(map2); FMOE_SEL(map1_limit); FMOE_SEL(Bp);
+  FMOE_SEL(group_stride); FMOE_SEL(nbw); FMOE_SEL(ks); FMOE_SEL(C); FMOE_SEL(ldc); FMOE_SEL(N);
+  FMOE_SEL(K); FMOE_SEL(n_col_tiles); FMOE_SEL(a_group_off); FMOE_SEL(c_group_off);
+#undef FMOE_SEL
+  // column tiles this entry really has, and groups of DNCB of them
+  const int ct_here = (P.n_col_tiles - tile.col0 < a.cols_entry) ? (P.n_col_tiles - tile.col0) : a.cols_entry;
+  const int c_eff = (ct_here + DNCB - 1) / DNCB;
+  if (nt_launch >= c_eff) return;
+  if (tile.nrt > 1) {   // column-major re-deal inside a run of row tiles, as in the weight-stream shape
+    const int w = tile.rt * c_eff + nt_launch;
+    const int r2 = w % tile.nrt;
+    nt_launch = w / tile.nrt;
+    ti = ti - tile.rt + r2;
+    tile = a.tiles[ti];
+  }
+  const int nt4 = tile.col0 + nt_launch * DNCB;
+  const int ct_limit = tile.col0 + ct_here;
+  const int group = shared ? tile.group - a.E : tile.group;
+  if (shared) {
+    P.A += (size_t)group * P.a_group_off;
+    P.C += (size_t)group * P.c_group_off;
+  }
+  if (tile.rows > 64) dense_tile<SWIGLU, 4, DNCB>(P, tile, group, nt4, ct_limit, As);   // uniform per block
+  else dense_tile<SWIGLU, 2, DNCB>(P, tile, group, nt4, ct_limit, As);
 }
 
 // Packing: unit u (16 bytes = 8 consecutive k) -> (group, tile of 4 column blocks, 64-wide k tile,
@@ -827,8 +1156,22 @@ int run_ffn_bf16(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, in
   g2.tiles = reinterpret_cast<fmoe_tile*>(base + L.tiles2);
   g1.n_tiles = tile_count;
   g2.n_tiles = tile_count + 1;
-  g1.cols = geo.cols1;
-  g2.cols = geo.cols2;
+  g1.cols = g1.cols_entry = geo.cols1;
+  g2.cols = g2.cols_entry = geo.cols2;
+  // Shape of the kernel: the dense one when the rows this call can route average FMOE_DENSE_MIN_ROWS per
+  // expert or more (the matrix pipes bound the kernel there), else the weight-stream one.
+  // FMOE_FFN_SHAPE=stream|dense in the environment overrides the rule (for measurements).
+  int dense = ((long long)n_cap * ctx->kmax >= (long long)FMOE_DENSE_MIN_ROWS * E) ? 4 : 0;
+  static const char* shape_env = getenv("FMOE_FFN_SHAPE");
+  if (shape_env && shape_env[0] == 's') dense = 0;
+  if (shape_env && shape_env[0] == 'd') dense = shape_env[1] == '2' ? 2 : 4;   // "dense" / "d2"
+  // the dense shape addresses the packed weights with 32-bit byte offsets
+  for (int w = 0; w < 4; ++w)
+    if (fmoe_packed_bytes(ctx, w) > 0xffffffffull) dense = 0;
+  if (dense) {
+    g1.cols = (geo.cols1 + dense - 1) / dense;
+    g2.cols = (geo.cols2 + dense - 1) / dense;
+  }
   {
     StreamProblem& p = g1.p0;
     p.A = static_cast<const bf16_t*>(x); p.lda = d; p.map1 = perm_src; p.map2 = kept_idx; p.map1_limit = n_cap;
@@ -858,16 +1201,18 @@ int run_ffn_bf16(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, in
   }
   const unsigned batches = (unsigned)((geo.tile_cap + 7) / 8);
   {
-    fmoe_prof_scope prof(ctx, SLOT_GEMM1, stream);
+    fmoe_prof_scope prof(ctx, dense ? SLOT_GEMM1_DENSE : SLOT_GEMM1, stream);
     const unsigned items = batches * 8 * g1.cols;
-    hipLaunchKernelGGL((ffn_stream_kernel<true>), dim3(items),
-                       dim3(256), 0, stream, g1);
+    if (dense == 4) hipLaunchKernelGGL((ffn_dense_kernel<true, 4>), dim3(items), dim3(256), 0, stream, g1);
+    else if (dense == 2) hipLaunchKernelGGL((ffn_dense_kernel<true, 2>), dim3(items), dim3(256), 0, stream, g1);
+    else hipLaunchKernelGGL((ffn_stream_kernel<true>), dim3(items), dim3(256), 0, stream, g1);
   }
   {
-    fmoe_prof_scope prof(ctx, SLOT_GEMM2, stream);
+    fmoe_prof_scope prof(ctx, dense ? SLOT_GEMM2_DENSE : SLOT_GEMM2, stream);
     const unsigned items = batches * 8 * g2.cols;
-    hipLaunchKernelGGL((ffn_stream_kernel<false>), dim3(items),
-                       dim3(256), 0, stream, g2);
+    if (dense == 4) hipLaunchKernelGGL((ffn_dense_kernel<false, 4>), dim3(items), dim3(256), 0, stream, g2);
+    else if (dense == 2) hipLaunchKernelGGL((ffn_dense_kernel<false, 2>), dim3(items), dim3(256), 0, stream, g2);
+    else hipLaunchKernelGGL((ffn_stream_kernel<false>), dim3(items), dim3(256), 0, stream, g2);
   }
   return FMOE_OK;
 }

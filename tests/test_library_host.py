@@ -351,3 +351,28 @@ def test_permute_noalloc_refuses_sizes_beyond_its_static_scratch(lib):
     assert lib.fmoe_permute_noalloc(ctx, dummy, None, 65536, None, None, dummy, dummy, None) == -2   # passes the size check
     lib.fmoe_destroy(ctx)
     assert lib.fmoe_permute_noalloc(None, dummy, None, 4, None, dummy, dummy, dummy, None) == -2
+
+
+def test_build_check_catches_compiler_use_of_hand_placed_accumulation_registers(tmp_path):
+    """The dense-shape GEMM kernels name their accumulation registers themselves; the build reads the
+    compiler's assembly and must refuse any a<N> operand the compiler placed inside those kernels."""
+    from paper_2511_17885_amd import build
+    ok = ("_ZN1x16ffn_dense_kernelILb1ELi2EEEv:\n\tv_add_u32 v1, v2, v3\n\t;;#ASMSTART\n"
+          "\tv_mfma_f32_16x16x32_bf16 a[0:3], v[4:7], v[8:11], a[0:3]\n\t;;#ASMEND\n\ts_endpgm\n"
+          "_ZN1x17ffn_stream_kernelILb1EEEv:\n\tv_accvgpr_write_b32 a7, v0\n\ts_endpgm\n")
+    p = tmp_path / "ok.s"
+    p.write_text(ok)
+    assert build.check_accumulation_registers(str(p)) == 1
+    for planted in ("\tv_accvgpr_write_b32 a5, v102\n", "\tbuffer_load_dwordx4 a[8:11], v1, s[0:3], 0 offen\n"):
+        bad = tmp_path / "bad.s"
+        bad.write_text(ok.replace("\tv_add_u32 v1, v2, v3\n", planted))
+        with pytest.raises(RuntimeError):
+            build.check_accumulation_registers(str(bad))
+    none = tmp_path / "none.s"
+    none.write_text("_ZN1x17ffn_stream_kernelILb1EEEv:\n\ts_endpgm\n")
+    with pytest.raises(RuntimeError):
+        build.check_accumulation_registers(str(none))
+    # and the assembly of the library as built passes
+    real = os.path.join(os.path.dirname(binding.LIB_PATH), "_build", "ffn-hip-amdgcn-amd-amdhsa-gfx950.s")
+    if os.path.exists(real):
+        assert build.check_accumulation_registers(real) == 4
