@@ -39,7 +39,7 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 MFMA_F32_PEAK_TFLOPS = 157.3
 VALU_F32_PEAK_TFLOPS = 157.3
-GEMM1, GEMM2 = "ffn_stream_kernel<true>", "ffn_stream_kernel<false>"
+GEMM1, GEMM2 = "gate_up_gemm", "down_gemm"   # work-table keys; the kernel that ran is named by the profile slots
 # HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs per workload
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch; the factors are what a 256 MiB device copy
 # reads on the same counters), averaged over the launches of one step -- profiles/*_hbm_traffic.md.
@@ -56,7 +56,7 @@ def _dev(a, t=None):
     return r.to(t).contiguous() if t is not None else r
 
 
-def _make_ctx(binding, wl, lw, td, k_text=None, k_visual=None, release=True):
+def _make_ctx(binding, wl, lw, td, k_text=None, k_visual=None, release=True, ffn_shape=0):
     c = binding.FMoE(d_model=wl.d, n_experts=wl.E, d_ffn=wl.F, n_shared=wl.n_shared,
                      d_ffn_shared=wl.F_shared if wl.n_shared else 0,
                      k_text=wl.k_text if k_text is None else k_text,
@@ -64,6 +64,7 @@ def _make_ctx(binding, wl, lw, td, k_text=None, k_visual=None, release=True):
     c.set_weights(_dev(lw.router_w, td), _dev(lw.router_bias), _dev(lw.w_gate, td), _dev(lw.w_up, td),
                   _dev(lw.w_down, td), _dev(lw.ws_gate, td), _dev(lw.ws_up, td), _dev(lw.ws_down, td),
                   release_packed=release)
+    c.set_ffn_shape(ffn_shape)
     return c
 
 
@@ -126,14 +127,33 @@ def _kernel_table(kms, launches, work):
     return out
 
 
+def _gemm_names(names):
+    """{work-table key: kernel name} for the expert GEMM kernels among `names` (either shape of the kernel)."""
+    out = {}
+    for n in names:
+        if n.startswith("ffn_") and n.endswith("<true>"):
+            out[GEMM1] = n
+        if n.startswith("ffn_") and n.endswith("<false>"):
+            out[GEMM2] = n
+    return out
+
+
+def _named_work(work, names):
+    """The work table with the GEMM entries under the names of the kernels that ran."""
+    g = _gemm_names(names)
+    return {g.get(k, k): v for k, v in work.items()}
+
+
 def _roofline(kernels, work, launches, workload, bound):
-    k = kernels.get(GEMM1)
-    if not k or "GBps" not in k:
+    cands = [n for n in kernels if n.startswith("ffn_") and n.endswith("<true>") and "GBps" in kernels[n]]
+    if not cands:
         return None
-    n = max(launches.get(GEMM1, 1), 1)
-    r = {"kernel": GEMM1, "bound": bound, "us_per_launch": k["us"], "launches_per_step": n,
+    name = max(cands, key=lambda n: kernels[n]["us"] * kernels[n]["launches_per_step"])   # the dominant kernel
+    k = kernels[name]
+    n = max(launches.get(name, 1), 1)
+    r = {"kernel": name, "bound": bound, "us_per_launch": k["us"], "launches_per_step": n,
          "traffic": MEASURED_TRAFFIC_BYTES.get(workload),
-         "algo_bytes_per_launch": int(work[GEMM1]["bytes"] / n), "algo_flops_per_launch": work[GEMM1]["flops"] / n}
+         "algo_bytes_per_launch": int(work[name]["bytes"] / n), "algo_flops_per_launch": work[name]["flops"] / n}
     if bound == "mfma":
         r.update(achieved=k["TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=k["compute_frac"],
                  hbm_frac=k["hbm_frac"])
@@ -164,7 +184,7 @@ def run_layer(args, name, cpu_baseline):
     NL = args.weight_copies if args.weight_copies is not None else (4 if name == "c2" else 1)
     NL = max(1, min(NL, 64))
     lw = wl.weights
-    ctxs = [_make_ctx(binding, wl, lw, td) for _ in range(NL)]
+    ctxs = [_make_ctx(binding, wl, lw, td, ffn_shape=args.ffn_shape) for _ in range(NL)]
     m = ctxs[0]
     x, vis, cu = _dev(wl.x, td), _dev(wl.is_visual), _dev(wl.cu_seqlens)
     pp = binding.prune_params(retention=wl.retention, window=wl.window, gamma=args.gamma)
@@ -208,6 +228,7 @@ def run_layer(args, name, cpu_baseline):
     work = _layer_work(wl.d, wl.F, wl.E, wl.n_shared, wl.F_shared, es, Kmax, T, n_vis, n_kept, M, touched,
                        wl.retention < 1.0, wl.window, False, is_bf16)
     launches = {k: 1 for k in kms}
+    work = _named_work(work, kms)
     kernels = _kernel_table(kms, launches, work)
     rows_per_expert = M / max(touched, 1)
     res = {
@@ -256,7 +277,7 @@ def run_stack(args, cpu_baseline):
     with cf.ThreadPoolExecutor(max_workers=3) as ex:   # layers are drawn from independent seeded streams
         for l, lw in enumerate(ex.map(lambda l: wl.layers[l], range(n_layers))):
             kt, kv = wl.k_schedule[l]
-            layers.append(_make_ctx(binding, wl, lw, td, kt, kv))
+            layers.append(_make_ctx(binding, wl, lw, td, kt, kv, ffn_shape=args.ffn_shape))
             del lw
     setup_s = time.time() - t0
     sched = {wl.prune_after_layer: binding.prune_params(retention=wl.retention, window=wl.window, prune_mode=2)}
@@ -279,13 +300,15 @@ def run_stack(args, cpu_baseline):
     for c in layers:
         c.profile_enable(True)
     acc, cnt = {}, {}
+    layer_kernels = [set() for _ in layers]   # which kernels each layer launched (the GEMM shape is per call)
     nprof = max(1, min(args.profile_steps, args.steps))
     for _ in range(nprof):
         step()
-        for c in layers:
+        for l, c in enumerate(layers):
             for k, v in c.profile_read().items():
                 acc[k] = acc.get(k, 0.0) + v
                 cnt[k] = cnt.get(k, 0) + 1
+                layer_kernels[l].add(k)
     for c in layers:
         c.profile_enable(False)
     kms = {k: v / nprof for k, v in acc.items()}
@@ -312,7 +335,7 @@ def run_stack(args, cpu_baseline):
                           "rows_per_expert": round(M / wl.E, 1), "k": [kt, kv]})
         w = _layer_work(wl.d, wl.F, wl.E, wl.n_shared, wl.F_shared, es, max(kt, kv), T_in, nv_in, n_kept, M, wl.E,
                         stage, wl.window, True, True)
-        for k, v in w.items():
+        for k, v in _named_work(w, layer_kernels[l]).items():
             e = work.setdefault(k, dict(bytes=0.0, flops=0.0, peak=v["peak"]))
             e["bytes"] += v["bytes"]
             e["flops"] += v["flops"]
@@ -385,6 +408,8 @@ def main():
     ap.add_argument("--weight-copies", type=int, default=None,
                     help="single-layer workloads: cycle the steps over this many copies of the layer's weights, "
                          "each in device memory of its own (default 4 for c2, 1 elsewhere)")
+    ap.add_argument("--ffn-shape", type=int, default=0, choices=[0, 1, 2],
+                    help="shape of the bf16 expert GEMM kernel: 0 chosen by size (default), 1 weight-stream, 2 dense")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=20)
     ap.add_argument("--copy-calib", action="store_true",

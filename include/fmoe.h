@@ -124,6 +124,14 @@ int fmoe_set_topk(fmoe_ctx* ctx, int32_t k_text, int32_t k_visual);
  * FMOE_ERR_INVALID_ARG unless 0 <= strategy <= 2 and 0 <= k_base <= min(E, 16). */
 int fmoe_set_selection(fmoe_ctx* ctx, int32_t strategy, int32_t k_base, uint64_t seed);
 
+/* Tuning knob of the bf16 expert GEMMs (Eq.4).  The kernel has two shapes: the weight-stream shape (a
+ * workgroup = 128 rows x 4 column blocks) for calls that route few rows per expert, and the dense
+ * shape (128 rows x 8 column blocks, half the on-chip traffic per flop) from a capacity of 256 routed
+ * rows per expert (T * Kmax / E) on.  Both add the products of a dot product in ascending k, so their
+ * outputs are bit-identical.  shape 0 = choose by that rule (default), 1 = always weight-stream,
+ * 2 = always dense; anything else is FMOE_ERR_INVALID_ARG.  No effect on fp32 contexts. */
+int fmoe_set_ffn_shape(fmoe_ctx* ctx, int32_t shape);
+
 /* Register the layer's weights (Eq.1, Eq.4).  Pointers are borrowed until the next call or
  * fmoe_destroy.  router_w [E,H] dtype; router_bias [E] fp32 or NULL (added to the logits
  * before the softmax); w_gate, w_up [E,S_m,H]; w_down [E,H,S_m]; ws_gate, ws_up

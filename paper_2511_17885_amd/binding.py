@@ -24,7 +24,7 @@ EXPORTS = ["fmoe_version", "fmoe_last_error", "fmoe_create", "fmoe_destroy", "fm
            "fmoe_profile_slots", "fmoe_profile_name", "fmoe_profile_read", "fmoe_adjacent_similarity",
            "fmoe_magnitude_stability", "fmoe_row_cosine", "fmoe_gate_cosine", "fmoe_flops_ratios",
            "fmoe_kept_counts", "fmoe_stage_retention", "fmoe_stack_plan", "fmoe_stack_workspace_bytes",
-           "fmoe_stack_forward", "fmoe_permute_noalloc"]
+           "fmoe_stack_forward", "fmoe_permute_noalloc", "fmoe_set_ffn_shape"]
 
 
 class FmoeConfig(C.Structure):
@@ -76,6 +76,7 @@ def load():
     lib.fmoe_destroy.restype = None
     lib.fmoe_set_topk.argtypes = [vp, i32, i32]
     lib.fmoe_set_selection.argtypes = [vp, i32, i32, C.c_uint64]
+    lib.fmoe_set_ffn_shape.argtypes = [vp, i32]
     lib.fmoe_set_weights.argtypes = [vp] + [vp] * 8 + [vp]
     lib.fmoe_workspace_bytes.argtypes = [vp, i32, i32]
     lib.fmoe_workspace_bytes.restype = sz
@@ -182,6 +183,10 @@ class FMoE:
     def set_selection(self, strategy, k_base, seed=0):
         """Selection-strategy ablation: TOPK / RANDOMK / MINK among the token's top-k_base experts."""
         _check(self.lib.fmoe_set_selection(self._ctx, int(strategy), int(k_base), int(seed)))
+
+    def set_ffn_shape(self, shape):
+        """0: expert GEMM shape chosen by size, 1: weight-stream shape, 2: dense shape (fmoe_set_ffn_shape)."""
+        _check(self.lib.fmoe_set_ffn_shape(self._ctx, int(shape)))
 
     def set_weights(self, router_w, router_bias, w_gate, w_up, w_down, ws_gate=None, ws_up=None,
                     ws_down=None, release_packed=False):

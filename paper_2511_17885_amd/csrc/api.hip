@@ -212,6 +212,15 @@ int fmoe_set_selection(fmoe_ctx* ctx, int32_t strategy, int32_t k_base, uint64_t
   return FMOE_OK;
 }
 
+int fmoe_set_ffn_shape(fmoe_ctx* ctx, int32_t shape) {
+  int rc = check_ctx(ctx, false);
+  if (rc != FMOE_OK) return rc;
+  if (shape < 0 || shape > 2)
+    return fmoe_fail(FMOE_ERR_INVALID_ARG, "fmoe_set_ffn_shape: shape %d is not 0 (by size), 1 (weight-stream) or 2 (dense)", shape);
+  ctx->ffn_shape = shape;
+  return FMOE_OK;
+}
+
 int fmoe_set_weights(fmoe_ctx* ctx, const void* router_w, const float* router_bias,
                      const void* w_gate, const void* w_up, const void* w_down, const void* ws_gate,
                      const void* ws_up, const void* ws_down, void* stream) {

@@ -14,7 +14,7 @@
 #define FMOE_TILE_M 64        // rows per grouped-GEMM tile (tile list granularity)
 #define FMOE_TILE_RUN 8       // row tiles per run of a group in the tile lists
 #define FMOE_SEG_MIN_TILES 256   // tile entries from which each XCD takes a contiguous segment of the list
-#define FMOE_DENSE_MIN_ROWS 768  // routed-row capacity per expert from which the expert GEMMs take their dense shape
+#define FMOE_DENSE_MIN_ROWS 256  // routed-row capacity per expert from which the expert GEMMs take their dense shape
 
 // ---- optional per-kernel timing (instrumentation; off by default)
 enum fmoe_kernel_slot {
@@ -42,6 +42,7 @@ struct fmoe_ctx {
   bool weights_set;
   int sel_strategy, sel_k_base;   // selection-strategy ablation (fmoe_set_selection); 0 = off
   unsigned long long sel_seed;
+  int ffn_shape;                  // fmoe_set_ffn_shape: 0 by size, 1 weight-stream, 2 dense
   fmoe_prof* prof;           // nullptr unless fmoe_profile_enable was called
 };
 

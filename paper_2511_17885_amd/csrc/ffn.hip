@@ -30,7 +30,6 @@
 // The fp32 storage type (a correctness configuration) uses a plain LDS-tiled kernel on the fp32
 // MFMA with the caller's weight layout.
 
-#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -52,13 +51,16 @@ constexpr int SBM = 128;        // rows per tile: 8 MFMA row blocks of 16
 constexpr int SBK = 64;         // k per tile: two 32-wide MFMA steps; one LDS row = 128 bytes
 constexpr int A_STAGES = 4;     // LDS ring of activation k-tiles (weight-stream shape)
 constexpr int B_SLOTS = 4;      // register ring of weight k-tiles (weight-stream shape)
-// The dense shape of the kernel, for long row lists (hundreds of rows per expert, where the matrix pipes
-// and not the weight stream bound the kernel): a workgroup owns 128 rows x 16 column blocks, i.e. each
-// wavefront four column blocks instead of one, with one wavefront per SIMD and the whole register file.
-// A wavefront's activation fragments then feed four times as many matrix instructions, so the LDS reads
-// per flop drop to a quarter and the L2 reads per flop (one activation tile per 16 instead of 4 column
-// blocks) to about a half; since no second wavefront shares the SIMD, the fragments of the next group
-// of matrix instructions are fetched from LDS while the current group executes.
+// The dense shape of the kernel, for row lists of a few hundred rows per expert and more (where LDS and
+// the CU's load path rather than the weight stream hold the weight-stream shape back: it reads every
+// activation fragment from LDS once per column block and fetches every activation tile once per four
+// column blocks): a workgroup owns 128 rows x 8 column blocks, each wavefront DNCB = 2 column blocks.  A
+// wavefront's activation fragments then feed twice as many matrix instructions, which halves the LDS
+// reads and the activation fetches per flop.  Two workgroups still share a CU (one hides the other's
+// start-up and epilogue), so a wavefront has 256 registers: 128 accumulation registers that the kernel
+// names itself and 128 vector registers for a k-step ring of weights, one group of fragments and
+// addresses, which is why the wavefront-uniform part of every address is kept in scalar registers.
+constexpr int DNCB = 2;         // column blocks per wavefront
 constexpr int DA_STAGES = 4;    // LDS ring of activation k tiles (64 wide)
 constexpr int DB_SLOTS = 4;     // register ring of weight k steps (32 wide)
 
@@ -140,25 +142,10 @@ __device__ __forceinline__ void lds_read_frags(uint32_t addr, u32x4_t (&f)[NRB])
                  : "v"(addr) : "memory");
   }
 }
-// The same reads without the wait: lds_issue_frags starts them, lds_settle_frags waits for them and is
-// the point from which the compiler may use the registers (they are in/out operands of the wait).
-template <int NRB>
-__device__ __forceinline__ void lds_issue_frags(uint32_t addr, u32x4_t (&f)[NRB]) {
-  static_assert(NRB == 2 || NRB == 3 || NRB == 4, "supported fragment counts");
-  if constexpr (NRB == 2) {
-    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:2048"
-                 : "=&v"(f[0]), "=&v"(f[1]) : "v"(addr) : "memory");
-  } else if constexpr (NRB == 3) {
-    asm volatile("ds_read_b128 %0, %3\n\tds_read_b128 %1, %3 offset:2048\n\tds_read_b128 %2, %3 offset:4096"
-                 : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]) : "v"(addr) : "memory");
-  } else {
-    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:2048\n\t"
-                 "ds_read_b128 %2, %4 offset:4096\n\tds_read_b128 %3, %4 offset:6144"
-                 : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]), "=&v"(f[3]) : "v"(addr) : "memory");
-  }
-}
-// ... and with a compile-time byte offset OFF on top of the address register, so that one register serves
-// every stage of the ring
+// The same reads without the wait and with a compile-time byte offset OFF on top of the address register
+// (one register then serves every stage of the ring): lds_issue_frags_at starts them, lds_settle_frags
+// waits for them and is the point from which the compiler may use the registers (they are in/out
+// operands of the wait).
 template <int NRB, int OFF>
 __device__ __forceinline__ void lds_issue_frags_at(uint32_t addr, u32x4_t (&f)[NRB]) {
   static_assert(NRB == 2 || NRB == 4, "supported fragment counts");
@@ -175,10 +162,9 @@ __device__ __forceinline__ void lds_issue_frags_at(uint32_t addr, u32x4_t (&f)[N
 }
 template <int NRB>
 __device__ __forceinline__ void lds_settle_frags(u32x4_t (&f)[NRB]) {
+  static_assert(NRB == 2 || NRB == 4, "supported fragment counts");
   if constexpr (NRB == 2) {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]) : : "memory");
-  } else if constexpr (NRB == 3) {
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]) : : "memory");
   } else {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) : : "memory");
   }
@@ -523,14 +509,14 @@ __global__ __launch_bounds__(256, 2) void ffn_stream_kernel(StreamArgs a) {
   }
 }
 
-// The dense shape keeps its 64 accumulators (256 registers, the whole accumulation register file of a
-// wavefront) in registers it names itself: accumulator IDX is a[4*IDX : 4*IDX+3].  The compiler's
-// allocator cannot place that many accumulators (it moves them through the vector registers and
-// spills), and, being volatile, the instructions keep their place between the LDS reads that are
-// started before a group of them and waited for after it.  The compiler does not see these registers:
-// dense_claim_acc() tells it that the kernel owns them (so that a wavefront is given all 512
-// registers), the build scans the generated code of the dense kernel and fails if the compiler itself
-// placed anything in an accumulation register, and the parity tests run this shape on every size.
+// The dense shape keeps its 32 accumulators in accumulation registers that it names itself: accumulator
+// IDX is a[4*IDX : 4*IDX+3].  Left to the compiler, the accumulators share the vector register budget
+// with everything else and part of them travels through scratch memory; named, they cost the
+// allocator nothing, and, being volatile, the instructions keep their place in the step.  The compiler
+// does not see these registers: dense_claim_acc() tells it that the kernel owns a0..a127 (so that a
+// wavefront is given them and the compiler half of its 256 registers), the build scans the generated
+// code of the dense kernel and fails if the compiler itself placed anything in an accumulation
+// register, and the parity tests run this shape on every size.
 template <int IDX>
 __device__ __forceinline__ void mfma_at(bf16x8_t a, bf16x8_t b) {
   asm volatile("v_mfma_f32_16x16x32_bf16 a[%0:%1], %2, %3, a[%0:%1]" : : "n"(4 * IDX), "n"(4 * IDX + 3), "v"(a), "v"(b));
@@ -544,7 +530,7 @@ __device__ __forceinline__ f32x4_t read_acc() {
                : "n"(4 * IDX), "n"(4 * IDX + 1), "n"(4 * IDX + 2), "n"(4 * IDX + 3));
   return f32x4_t{r0, r1, r2, r3};
 }
-#include "dense_regs.inc"   // dense_claim_acc(): zeroes a0..a255 and lists them as written
+#include "dense_regs.inc"   // dense_claim_acc(): zeroes a0..a127 and lists them as written
 
 // ---- the dense shape: one (row tile, group of DNCB column tiles) work item per workgroup.
 // Wavefront w owns column block w of each of the DNCB column tiles nt4 .. nt4+DNCB-1 of the packing (so
@@ -557,10 +543,8 @@ __device__ __forceinline__ f32x4_t read_acc() {
 // unconditionally -- past the end of the reduction they fetch the last step / tile again, into slots
 // nobody reads -- so the number of loads in flight at every wait is a compile-time constant and there
 // is no separate code for the last steps.
-// Per step and group of HB row blocks a wavefront issues HB LDS reads for 2*HB*DNCB matrix instructions;
-// the reads of the next group are issued before the current group's matrix instructions and waited for
-// after them.
-template <bool SWIGLU, int NAB, int DNCB>
+// Per step and group of HB row blocks a wavefront issues HB LDS reads for 2*HB*DNCB matrix instructions.
+template <bool SWIGLU, int NAB>
 __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_tile& tile, int group, int nt4,
                                            int ct_limit, bf16_t* As) {
   constexpr int NRB = 2 * NAB;
@@ -592,7 +576,7 @@ __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_ti
   const int a_kc = ((lane & 7) ^ ((4 * wave + (lane >> 4)) & 7)) * 8;
   gather_offsets<NAB>(P, tile, a_src);
 
-  dense_claim_acc<DNCB * 64>();   // accumulator (j, rb, f) is number (j*NRB + rb)*2 + f, all zero now
+  dense_claim_acc();   // accumulator (j, rb, f) is number (j*NRB + rb)*2 + f, all zero now
 
   u32x4_t breg[DB_SLOTS][DNCB][2];   // [ring slot][column tile][fragment]
   // weights of k step ks (clamped to the last one): two fragments per column tile
@@ -627,10 +611,7 @@ __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_ti
   constexpr int NEWER_EVEN = (B_AHEAD - 1) * 2 * DNCB + ((B_AHEAD - 1) / 2) * NAB;        // before an even step
   constexpr int NEWER_ODD = (B_AHEAD - 1) * 2 * DNCB + (B_AHEAD / 2) * NAB;               // before an odd step
 
-  // With one wavefront per SIMD (DNCB 4) the next group's fragments are fetched while the current group
-  // multiplies; with two (DNCB 2) the other wavefront covers the LDS latency and registers are short.
-  constexpr bool PREFETCH = DNCB == 4;
-  u32x4_t fa[PREFETCH ? 2 : 1][HB];
+  u32x4_t fa[HB];
   // k step `ks` = round base + U (U static): products of the step, loads of the steps further on
   auto kstep = [&](auto uc, int ks) {
     constexpr int U = decltype(uc)::value;
@@ -641,25 +622,14 @@ __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_ti
     if constexpr (s == 0) {
       FMOE_WAIT_VM(NEWER_EVEN);
       block_barrier();   // every wavefront's share of the tile is in LDS; all are done with the tile before
-      if constexpr (PREFETCH) {
-        lds_issue_frags_at<HB, stage_off>(frag_a0, fa[0]);
-        lds_settle_frags<HB>(fa[0]);
-      }
     } else {
       FMOE_WAIT_VM(NEWER_ODD);
     }
     static_for<0, NH>([&](auto hc) {
       constexpr int h = decltype(hc)::value;
-      constexpr int g = s * NH + h;            // group within the tile
       constexpr int h0 = h * HB;
-      constexpr int cur = PREFETCH ? (g & 1) : 0;
-      if constexpr (!PREFETCH) {
-        lds_issue_frags_at<HB, stage_off + h0 * 2048>(s ? frag_a1 : frag_a0, fa[0]);
-        lds_settle_frags<HB>(fa[0]);
-      } else if constexpr (g + 1 < 2 * NH) {   // the next group's fragments travel while this group multiplies
-        constexpr int s1 = (g + 1) / NH, h1 = ((g + 1) % NH) * HB;
-        lds_issue_frags_at<HB, stage_off + h1 * 2048>(s1 ? frag_a1 : frag_a0, fa[(g + 1) & 1]);
-      }
+      lds_issue_frags_at<HB, stage_off + h0 * 2048>(s ? frag_a1 : frag_a0, fa);
+      lds_settle_frags<HB>(fa);
 #pragma unroll
       for (int i = 0; i < NL; ++i) {           // load i of the step goes out with group i*NH/NL
         if ((i * NH) / NL != h) continue;
@@ -672,12 +642,11 @@ __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_ti
         const bf16x8_t fb1 = __builtin_bit_cast(bf16x8_t, breg[slot][j][1]);
         static_for<0, HB>([&](auto rc) {
           constexpr int rb = decltype(rc)::value;
-          const bf16x8_t a8 = __builtin_bit_cast(bf16x8_t, fa[cur][rb]);
+          const bf16x8_t a8 = __builtin_bit_cast(bf16x8_t, fa[rb]);
           mfma_at<(j * NRB + h0 + rb) * 2>(a8, fb0);
           mfma_at<(j * NRB + h0 + rb) * 2 + 1>(a8, fb1);
         });
       });
-      if constexpr (PREFETCH && g + 1 < 2 * NH) lds_settle_frags<HB>(fa[(g + 1) & 1]);
     });
   };
 
@@ -721,8 +690,8 @@ __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_ti
 
 // Work decode as in ffn_stream_kernel, with column tiles taken DNCB at a time (a.cols = such groups per
 // tile entry, a.cols_entry = column tiles per tile entry).
-template <bool SWIGLU, int DNCB>
-__global__ __launch_bounds__(256, DNCB == 4 ? 1 : 2) void ffn_dense_kernel(StreamArgs a) {
+template <bool SWIGLU>
+__global__ __launch_bounds__(256, 2) void ffn_dense_kernel(StreamArgs a) {
   __shared__ __align__(16) bf16_t As[DA_STAGES * SBM * SBK];
   const int n_tiles = *a.n_tiles;
   const int item = blockIdx.x;
@@ -766,8 +735,8 @@ __global__ __launch_bounds__(256, DNCB == 4 ? 1 : 2) void ffn_dense_kernel(Strea
     P.A += (size_t)group * P.a_group_off;
     P.C += (size_t)group * P.c_group_off;
   }
-  if (tile.rows > 64) dense_tile<SWIGLU, 4, DNCB>(P, tile, group, nt4, ct_limit, As);   // uniform per block
-  else dense_tile<SWIGLU, 2, DNCB>(P, tile, group, nt4, ct_limit, As);
+  if (tile.rows > 64) dense_tile<SWIGLU, 4>(P, tile, group, nt4, ct_limit, As);   // uniform per block
+  else dense_tile<SWIGLU, 2>(P, tile, group, nt4, ct_limit, As);
 }
 
 // Packing: unit u (16 bytes = 8 consecutive k) -> (group, tile of 4 column blocks, 64-wide k tile,
@@ -1159,18 +1128,16 @@ int run_ffn_bf16(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, in
   g1.cols = g1.cols_entry = geo.cols1;
   g2.cols = g2.cols_entry = geo.cols2;
   // Shape of the kernel: the dense one when the rows this call can route average FMOE_DENSE_MIN_ROWS per
-  // expert or more (the matrix pipes bound the kernel there), else the weight-stream one.
-  // FMOE_FFN_SHAPE=stream|dense in the environment overrides the rule (for measurements).
-  int dense = ((long long)n_cap * ctx->kmax >= (long long)FMOE_DENSE_MIN_ROWS * E) ? 4 : 0;
-  static const char* shape_env = getenv("FMOE_FFN_SHAPE");
-  if (shape_env && shape_env[0] == 's') dense = 0;
-  if (shape_env && shape_env[0] == 'd') dense = shape_env[1] == '2' ? 2 : 4;   // "dense" / "d2"
+  // expert or more, else the weight-stream one; fmoe_set_ffn_shape overrides the rule.
+  bool dense = (long long)n_cap * ctx->kmax >= (long long)FMOE_DENSE_MIN_ROWS * E;
+  if (ctx->ffn_shape == 1) dense = false;
+  if (ctx->ffn_shape == 2) dense = true;
   // the dense shape addresses the packed weights with 32-bit byte offsets
   for (int w = 0; w < 4; ++w)
-    if (fmoe_packed_bytes(ctx, w) > 0xffffffffull) dense = 0;
+    if (fmoe_packed_bytes(ctx, w) > 0xffffffffull) dense = false;
   if (dense) {
-    g1.cols = (geo.cols1 + dense - 1) / dense;
-    g2.cols = (geo.cols2 + dense - 1) / dense;
+    g1.cols = (geo.cols1 + DNCB - 1) / DNCB;
+    g2.cols = (geo.cols2 + DNCB - 1) / DNCB;
   }
   {
     StreamProblem& p = g1.p0;
@@ -1203,15 +1170,13 @@ int run_ffn_bf16(const fmoe_ctx* ctx, const void* x, const int32_t* kept_idx, in
   {
     fmoe_prof_scope prof(ctx, dense ? SLOT_GEMM1_DENSE : SLOT_GEMM1, stream);
     const unsigned items = batches * 8 * g1.cols;
-    if (dense == 4) hipLaunchKernelGGL((ffn_dense_kernel<true, 4>), dim3(items), dim3(256), 0, stream, g1);
-    else if (dense == 2) hipLaunchKernelGGL((ffn_dense_kernel<true, 2>), dim3(items), dim3(256), 0, stream, g1);
+    if (dense) hipLaunchKernelGGL((ffn_dense_kernel<true>), dim3(items), dim3(256), 0, stream, g1);
     else hipLaunchKernelGGL((ffn_stream_kernel<true>), dim3(items), dim3(256), 0, stream, g1);
   }
   {
     fmoe_prof_scope prof(ctx, dense ? SLOT_GEMM2_DENSE : SLOT_GEMM2, stream);
     const unsigned items = batches * 8 * g2.cols;
-    if (dense == 4) hipLaunchKernelGGL((ffn_dense_kernel<false, 4>), dim3(items), dim3(256), 0, stream, g2);
-    else if (dense == 2) hipLaunchKernelGGL((ffn_dense_kernel<false, 2>), dim3(items), dim3(256), 0, stream, g2);
+    if (dense) hipLaunchKernelGGL((ffn_dense_kernel<false>), dim3(items), dim3(256), 0, stream, g2);
     else hipLaunchKernelGGL((ffn_stream_kernel<false>), dim3(items), dim3(256), 0, stream, g2);
   }
   return FMOE_OK;

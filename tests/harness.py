@@ -24,7 +24,7 @@ def torch_dtype(wl):
     return torch.bfloat16 if wl.dtype == W.BF16 else torch.float32
 
 
-def make_layer(wl, layer=0, k_text=None, k_visual=None, renormalize=True):
+def make_layer(wl, layer=0, k_text=None, k_visual=None, renormalize=True, ffn_shape=0):
     lw = wl.layers[layer]
     td = torch_dtype(wl)
     m = binding.FMoE(d_model=wl.d, n_experts=wl.E, d_ffn=wl.F, n_shared=wl.n_shared,
@@ -34,6 +34,7 @@ def make_layer(wl, layer=0, k_text=None, k_visual=None, renormalize=True):
                      dtype=wl.dtype, renormalize=renormalize)
     m.set_weights(dev(lw.router_w, td), dev(lw.router_bias), dev(lw.w_gate, td), dev(lw.w_up, td),
                   dev(lw.w_down, td), dev(lw.ws_gate, td), dev(lw.ws_up, td), dev(lw.ws_down, td))
+    m.set_ffn_shape(ffn_shape)
     return m
 
 

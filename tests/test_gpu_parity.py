@@ -286,14 +286,24 @@ def test_permute_many_blocks_and_device_count():
 
 
 # ---------------------------------------------------------------- experts + combine
+SHAPES = [pytest.param(1, id="stream"), pytest.param(2, id="dense")]   # fmoe_set_ffn_shape (bf16 expert GEMMs)
+
+
+def _skip_fp32_duplicate(wl, shape):
+    if wl.dtype == W.F32 and shape == 2:
+        pytest.skip("the GEMM shape only exists for bf16")
+
+
+@pytest.mark.parametrize("shape", SHAPES)
 @pytest.mark.parametrize("seed,kw", SMALL)
-def test_expert_ffn_and_combine(seed, kw):
+def test_expert_ffn_and_combine(seed, kw, shape):
     wl = _wl(seed, kw)
+    _skip_fp32_duplicate(wl, shape)
     o = _oracle(wl, add_residual=True)
     n = len(o["kept_idx"])
     if n == 0:
         pytest.skip("empty")
-    m = make_layer(wl)
+    m = make_layer(wl, ffn_shape=shape)
     x, vis, cu = inputs(wl)
     kept = dev(o["kept_idx"])
     y, ysh = m.expert_ffn(x, kept, n, dev(o["expert_offsets"]), dev(o["perm_src"]))
@@ -312,11 +322,13 @@ def test_expert_ffn_and_combine(seed, kw):
 
 
 # ---------------------------------------------------------------- whole layer
+@pytest.mark.parametrize("shape", SHAPES)
 @pytest.mark.parametrize("seed,kw", SMALL)
-def test_layer_forward(seed, kw):
+def test_layer_forward(seed, kw, shape):
     wl = _wl(seed, kw)
+    _skip_fp32_duplicate(wl, shape)
     o = _oracle(wl, add_residual=True)
-    m = make_layer(wl)
+    m = make_layer(wl, ffn_shape=shape)
     x, vis, cu = inputs(wl)
     pp = binding.prune_params(retention=wl.retention, window=wl.window)
     out, kept, new_cu, vis_out = m.layer_forward(x, vis, cu, pp, add_residual=True, want_mask=True)
@@ -508,6 +520,35 @@ def _check_config(wl):
     o = _check_layer(m, wl, wl.x, wl.is_visual, wl.cu_seqlens, wl.weights, wl.k_text, wl.k_visual,
                      do_prune=wl.retention < 1.0, what=wl.name)
     return len(o["kept_idx"])
+
+
+@pytest.mark.parametrize("cfg", ["c2", "s108", "kloop"])
+def test_expert_gemm_shapes_agree_bit_for_bit(cfg):
+    """Both shapes of the bf16 expert GEMM add the products of a dot product in ascending k: whatever the
+    size, they must give the same bits (fmoe_set_ffn_shape)."""
+    wl = {"c2": W.config2, "s108": lambda: _wl(108, SMALL[8].values[1]),
+          "kloop": lambda: W.small_random(8123, T_v=[150, 40], T_t=[30, 7], d=712, E=12, F=456, k_text=4, k_visual=2,
+                                          retention=0.5, window=3, dtype=W.BF16, n_shared=1, F_shared=392,
+                                          bias_std=1.5)}[cfg]()
+    x, vis, cu = inputs(wl)
+    pp = binding.prune_params(retention=wl.retention, window=wl.window)
+    outs = []
+    for shape in (1, 2):
+        m = make_layer(wl, ffn_shape=shape)
+        out, kept, new_cu, _ = m.layer_forward(x, vis, cu, pp)
+        n = int(host(new_cu)[-1])
+        outs.append(out[:n].clone())
+    assert torch.equal(outs[0], outs[1])
+    with pytest.raises(RuntimeError):
+        m.set_ffn_shape(3)
+
+
+def test_config2_dsvl2_tiny_dense_shape():
+    wl = W.config2()
+    m = make_layer(wl, ffn_shape=2)
+    o = _check_layer(m, wl, wl.x, wl.is_visual, wl.cu_seqlens, wl.weights, wl.k_text, wl.k_visual, do_prune=True,
+                     what="c2, dense shape")
+    assert len(o["kept_idx"]) == 768 + 64
 
 
 def test_config1_tiny_fp32():
@@ -938,16 +979,18 @@ def _random_case(seed):
     return kw, extra
 
 
+@pytest.mark.parametrize("shape", SHAPES)
 @pytest.mark.parametrize("seed", range(32))
-def test_randomized_layer_sweep(seed):
+def test_randomized_layer_sweep(seed, shape):
     kw, extra = _random_case(seed)
     wl = W.small_random(7000 + seed, **kw)
+    _skip_fp32_duplicate(wl, shape)
     rng = np.random.default_rng(9000 + seed)
     attn = (rng.random(wl.T).astype(np.float32) ** 2) if extra["use_attn"] else None
     alpha = extra["alpha"] if attn is not None else 1.0
     over = dict(add_residual=True, gamma=extra["gamma"], alpha=alpha, attn=attn, sim_mode=extra["sim_mode"])
     o = _oracle(wl, **over)
-    m = make_layer(wl)
+    m = make_layer(wl, ffn_shape=shape)
     x, vis, cu = inputs(wl)
     pp = binding.prune_params(retention=wl.retention, window=wl.window, alpha=alpha, gamma=extra["gamma"],
                               sim_mode=extra["sim_mode"])
@@ -989,14 +1032,15 @@ def test_layer_forward_at_the_small_batch_limits(T_v, T_t, window):
     assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
 
 
-def test_layer_forward_general_chain_at_the_widest_routing():
+@pytest.mark.parametrize("shape", SHAPES)
+def test_layer_forward_general_chain_at_the_widest_routing(shape):
     """The largest expert count and top-k the library takes (256 experts, 16 per text token), shared experts,
     bf16, several ragged sequences and more tokens than the single-workgroup kernel handles."""
     wl = W.small_random(5151, T_v=[2500, 1, 1800, 700], T_t=[40, 3, 0, 77], d=96, E=256, F=40, k_text=16, k_visual=7,
                         retention=0.4, window=5, dtype=W.BF16, n_shared=2, F_shared=24, bias_std=1.0, n_components=40)
     assert wl.T > 4096
     o = _oracle(wl, add_residual=True)
-    m = make_layer(wl)
+    m = make_layer(wl, ffn_shape=shape)
     x, vis, cu = inputs(wl)
     out, kept, new_cu, _ = m.layer_forward(x, vis, cu, binding.prune_params(retention=wl.retention, window=wl.window),
                                            add_residual=True)
@@ -1010,15 +1054,18 @@ def test_layer_forward_general_chain_at_the_widest_routing():
     assert_outputs_close(host(out2)[:n], _oracle(wl)["out_f64"], wl.dtype, "widest routing, expert term")
 
 
-@pytest.mark.parametrize("d,F", [(448, 576), (576, 640), (640, 704), (832, 960), (960, 448)])
-def test_expert_ffn_k_loop_lengths(d, F):
-    # bf16 expert GEMMs at reduction lengths of 7..15 k-tiles of 64: every combination of steady-loop
-    # iterations and left-over steps (3, 4, 5, 6) of the streaming kernel's k loop, ragged row counts
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("d,F", [(448, 576), (576, 640), (640, 704), (832, 960), (960, 448), (72, 1032), (1032, 72)])
+def test_expert_ffn_k_loop_lengths(d, F, shape):
+    # bf16 expert GEMMs at reduction lengths of 2..17 k-tiles of 64: every combination of steady-loop
+    # iterations and left-over steps of both kernel shapes' k loops (the weight-stream shape: rounds of 4
+    # tiles + 3..6 left over; the dense shape: rounds of 8 half-tiles + 0, 2, 4 or 6 left over), reduction
+    # lengths that are not a multiple of 64, ragged row counts
     wl = W.small_random(8000 + d, T_v=[150, 40], T_t=[30, 7], d=d, E=12, F=F, k_text=4, k_visual=2,
                         retention=0.5, window=3, dtype=W.BF16, n_shared=1, F_shared=F - 64, bias_std=1.5)
     o = _oracle(wl, add_residual=True)
     n = len(o["kept_idx"])
-    m = make_layer(wl)
+    m = make_layer(wl, ffn_shape=shape)
     x, vis, cu = inputs(wl)
     out, kept, new_cu, _ = m.layer_forward(x, vis, cu, binding.prune_params(retention=0.5, window=3),
                                            add_residual=True)
