@@ -126,7 +126,7 @@ template <> struct XStage<bf16_t> {
   u32x4_t v[UNITS];
   // Unpredicated: a token past T re-reads the last token (its logits are never used) and k past d
   // re-reads the row's last chunk (the packed weights are zero there).
-  __device__ __forceinline__ void load(const bf16_t* x, int t0, int T, int d, int c0, int tid) {
+  __device__ __forceinline__ void load(const bf16_t* x, int t0, int T, int d, int c0, int tid) {   // t0: the tile's first token
     const int tok = tid >> 4, cu = tid & 15;
     int k = c0 + 8 * cu, t = t0 + tok;
     k = k < d ? k : d - 8;
@@ -191,36 +191,43 @@ __device__ __forceinline__ unsigned long long splitmix64_nth(unsigned long long 
   return z ^ (z >> 31);
 }
 
-template <typename XT, int NB, int PF, bool SEL>
+// TT = token tiles of 16 per block (1 or 2).  With two tiles every wavefront runs two independent
+// accumulation chains on the same weight fragments: a logit's own chain keeps its order (so its bits),
+// the matrix pipe gets a second instruction to issue while the first chain's next link waits for its
+// predecessor, and a token costs half the weight loads.  Taken for large batches, where there are
+// enough blocks to fill the chip either way.
+template <typename XT, int NB, int PF, bool SEL, int TT>
 __global__ __launch_bounds__(256) void route_kernel(
     const XT* __restrict__ x, const fx4_t* __restrict__ wp, const float* __restrict__ bias,
     const uint8_t* __restrict__ is_visual, int T, int d, int E, int Eb, int G, int nch, int k_text,
     int k_visual, int Kmax, int renorm, float* __restrict__ probs, int32_t* __restrict__ topk_idx,
     float* __restrict__ topk_gate, int route_blocks, fmoe_ordinals_job ord, const int32_t* __restrict__ T_dev,
     fmoe_selection selp) {
-  __shared__ __align__(16) float xs[64 * RS];
-  __shared__ float zs[TOKB][4 * NB * 16 + 1];
+  __shared__ __align__(16) float xs[TT][64 * RS];
+  __shared__ float zs[TT * TOKB][4 * NB * 16 + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if ((int)blockIdx.x >= route_blocks) {   // rider blocks: per-sequence visual ordinals for the pruning stage
     seq_ordinals_block(is_visual, ord.cu, (int)blockIdx.x - route_blocks, T, ord.vis_ord, ord.vis_tok,
-                       ord.seq_nv, reinterpret_cast<int*>(xs));
+                       ord.seq_nv, reinterpret_cast<int*>(&xs[0][0]));
     return;
   }
-  const int t0 = blockIdx.x * TOKB;
+  const int t0 = blockIdx.x * (TT * TOKB);
   if (T_dev != nullptr) {   // the batch holds fewer tokens than its capacity
     const int Td = *T_dev;
     T = Td < T ? Td : T;
     if (t0 >= T) return;
   }
 
-  f32x4_t acc[NB];
+  f32x4_t acc[TT][NB];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[tt][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   // PF chunks of operands are kept in flight in registers (the block's wavefronts are often alone
   // on their SIMDs, so memory latency has to be covered inside the wavefront)
   fx4_t wbuf[PF][NG][NB];
-  XStage<XT> xbuf[PF];
+  XStage<XT> xbuf[PF][TT];
   const fx4_t* wsrc[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
@@ -229,7 +236,8 @@ __global__ __launch_bounds__(256) void route_kernel(
     wsrc[nb] = wp + (size_t)eb * G * 64 + lane;
   }
   auto load_chunk = [&](int slot, int c0) {
-    xbuf[slot].load(x, t0, T, d, c0, tid);
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) xbuf[slot][tt].load(x, t0 + tt * TOKB, T, d, c0, tid);
 #pragma unroll
     for (int gl = 0; gl < NG; ++gl)
 #pragma unroll
@@ -240,18 +248,22 @@ __global__ __launch_bounds__(256) void route_kernel(
   // counted exactly: chunk c is multiplied while chunks c+1 .. c+PF are in flight.
   const int xrow = ((lane >> 4) * 16 + (lane & 15)) * RS;
   auto step = [&](int p) {
-    xbuf[p].store(xs, tid);
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) xbuf[p][tt].store(xs[tt], tid);
     __syncthreads();
 #pragma unroll
     for (int gl = 0; gl < NG; ++gl) {
-      const fx4_t xa = *reinterpret_cast<const fx4_t*>(&xs[xrow + gl * 4]);
+      fx4_t xa[TT];
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) xa[tt] = *reinterpret_cast<const fx4_t*>(&xs[tt][xrow + gl * 4]);
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         const fx4_t wv = wbuf[p][gl][nb];
-        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], wv[0], acc[nb], 0, 0, 0);
-        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[1], wv[1], acc[nb], 0, 0, 0);
-        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[2], wv[2], acc[nb], 0, 0, 0);
-        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[3], wv[3], acc[nb], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)   // each chain in ascending k; the chains of the tiles alternate
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt)
+            acc[tt][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[tt][q], wv[q], acc[tt][nb], 0, 0, 0);
       }
     }
   };
@@ -274,199 +286,206 @@ __global__ __launch_bounds__(256) void route_kernel(
 
   // accumulator register v of lane l: token 4*(l/16) + v, expert (block)*16 + l%16
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    const int e = (wave * NB + nb) * 16 + (lane & 15);
+  for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) zs[4 * (lane >> 4) + v][e] = acc[nb][v];
-  }
+    for (int nb = 0; nb < NB; ++nb) {
+      const int e = (wave * NB + nb) * 16 + (lane & 15);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) zs[tt * TOKB + 4 * (lane >> 4) + v][e] = acc[tt][nb][v];
+    }
   __syncthreads();
 
   // softmax, top-k and gates: lanes <-> experts (expert e lives in lane e%64, register e/64).
   // The wavefront's four tokens are processed side by side so that the cross-lane reduction
   // chains of different tokens overlap.
-  constexpr int TQ = 4;
-  float P[TQ][NB], part[TQ], mx[TQ];
-  int tt[TQ];
-  bool tv[TQ];
-#pragma unroll
-  for (int tq = 0; tq < TQ; ++tq) {
-    const int tok = wave * TQ + tq;
-    tv[tq] = (t0 + tok) < T;
-    tt[tq] = tv[tq] ? t0 + tok : T - 1;
-    mx[tq] = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const int e = lane + 64 * i;
-      float v = -INFINITY;
-      if (e < E) {
-        v = zs[tok][e];
-        if (bias != nullptr) v = v + bias[e];
-      }
-      P[tq][i] = v;
-      mx[tq] = (v > mx[tq]) ? v : mx[tq];
-    }
-  }
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1)
-#pragma unroll
+  for (int tile = 0; tile < TT; ++tile) {   // four tokens per wavefront at a time
+    constexpr int TQ = 4;
+    float P[TQ][NB], part[TQ], mx[TQ];
+    int tt[TQ];
+    bool tv[TQ];
+  #pragma unroll
     for (int tq = 0; tq < TQ; ++tq) {
-      const float o = __shfl_xor(mx[tq], s, 64);
-      mx[tq] = (o > mx[tq]) ? o : mx[tq];
-    }
-#pragma unroll
-  for (int tq = 0; tq < TQ; ++tq) {
-    part[tq] = 0.0f;
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const int e = lane + 64 * i;
-      float q = 0.0f;
-      if (e < E) {
-        q = exp_fixed(P[tq][i] - mx[tq]);
-        part[tq] = part[tq] + q;
-      }
-      P[tq][i] = q;
-    }
-  }
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1)
-#pragma unroll
-    for (int tq = 0; tq < TQ; ++tq) part[tq] = part[tq] + __shfl_xor(part[tq], s, 64);
-#pragma unroll
-  for (int tq = 0; tq < TQ; ++tq)
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const int e = lane + 64 * i;
-      P[tq][i] = (e < E) ? P[tq][i] / part[tq] : -1.0f;   // -1 ranks below every probability
-      if (probs != nullptr && tv[tq] && e < E) probs[(size_t)tt[tq] * E + e] = P[tq][i];
-    }
-
-  // Top-k as k rounds of "take the largest remaining probability" (ties: lowest expert index), which
-  // yields the list in the order (probability desc, index asc) directly.  The maximum over the
-  // wavefront is order-free, so it uses the cheap lane-crossing modifiers (two quad permutes, two
-  // mirrors) inside a row of 16 lanes and four lane reads across rows.  The four tokens run side by
-  // side and a token that needs fewer than Kmax experts idles branch-free.
-  float work[TQ][NB];
-  int sel[TQ][NB];     // position of this lane's expert in the token's list, -1: not selected
-  float den[TQ];
-  int kk[TQ];
-#pragma unroll
-  for (int tq = 0; tq < TQ; ++tq) {
-    kk[tq] = is_visual[tt[tq]] ? k_visual : k_text;
-    den[tq] = 0.0f;
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      work[tq][i] = P[tq][i];
-      sel[tq][i] = -1;
-    }
-  }
-  // with a selection strategy a token with k < k_base first lists its k_base candidates
-  int kc[TQ];
-#pragma unroll
-  for (int tq = 0; tq < TQ; ++tq) kc[tq] = (SEL && kk[tq] < selp.k_base) ? selp.k_base : kk[tq];
-  const int rounds = (SEL && selp.k_base > Kmax) ? selp.k_base : Kmax;
-  for (int r = 0; r < rounds; ++r) {
-#pragma unroll
-    for (int tq = 0; tq < TQ; ++tq) {
-      float v = work[tq][0];
-#pragma unroll
-      for (int i = 1; i < NB; ++i) v = (work[tq][i] > v) ? work[tq][i] : v;
-      const float m = wave_max_all(v);
-      const bool active = r < kc[tq];
-      bool taken = false;
-#pragma unroll
-      for (int i = 0; i < NB; ++i) {   // lowest expert index first: register i holds experts 64i..64i+63
-        const unsigned long long eq = __ballot(work[tq][i] == m);
-        const int owner = __ffsll((long long)eq) - 1;
-        if (active && !taken && lane == owner) {
-          sel[tq][i] = r;
-          work[tq][i] = -2.0f;
-        }
-        taken = taken || (eq != 0ull);
-      }
-      den[tq] = den[tq] + (active ? m : 0.0f);   // list order, sequential (Eq.5)
-    }
-  }
-  if constexpr (SEL) {
-    // random strategy: lane 16q + r holds the key of candidate position r of the wavefront's q-th
-    // token; a position is kept when fewer than k keys of its token are smaller (ties: lower position)
-    unsigned long long random_masks = 0ull;
-    if (selp.strategy == 1) {
-      const int q = lane >> 4, r = lane & 15;
-      const int tq_t = q == 0 ? tt[0] : (q == 1 ? tt[1] : (q == 2 ? tt[2] : tt[3]));
-      const int tq_k = q == 0 ? kk[0] : (q == 1 ? kk[1] : (q == 2 ? kk[2] : kk[3]));
-      const unsigned long long key = splitmix64_nth(selp.seed, (unsigned long long)tq_t * 16ull + (unsigned long long)r + 1ull);
-      int rank = 0;
-      for (int o = 0; o < 16; ++o) {
-        const int src = (lane & 48) + o;
-        const unsigned int lo = (unsigned int)__shfl((int)(unsigned int)key, src, 64);
-        const unsigned int hi = (unsigned int)__shfl((int)(unsigned int)(key >> 32), src, 64);
-        const unsigned long long ok = ((unsigned long long)hi << 32) | lo;
-        rank += (o < selp.k_base && (ok < key || (ok == key && o < r))) ? 1 : 0;
-      }
-      random_masks = __ballot(r < selp.k_base && rank < tq_k);
-    }
-#pragma unroll
-    for (int tq = 0; tq < TQ; ++tq) {
-      if (kk[tq] >= selp.k_base) continue;   // not reduced: the list stands (uniform over the wavefront)
-      const int k = kk[tq];
-      unsigned int mask;   // kept candidate positions
-      if (selp.strategy == 1) mask = (unsigned int)(random_masks >> (16 * tq)) & 0xffffu;
-      else if (selp.strategy == 2) mask = ((1u << k) - 1u) << (selp.k_base - k);
-      else mask = (1u << k) - 1u;
-#pragma unroll
+      const int tok = tile * TOKB + wave * TQ + tq;
+      tv[tq] = (t0 + tok) < T;
+      tt[tq] = tv[tq] ? t0 + tok : T - 1;
+      mx[tq] = -INFINITY;
+  #pragma unroll
       for (int i = 0; i < NB; ++i) {
-        const int p = sel[tq][i];
-        if (p >= 0) sel[tq][i] = ((mask >> p) & 1u) ? __popc(mask & ((1u << p) - 1u)) : -1;
-      }
-      float d2 = 0.0f;   // Eq.5 over the kept experts, in list order
-      for (int sl = 0; sl < k; ++sl) {
-        float v = -1.0f;
-#pragma unroll
-        for (int i = 0; i < NB; ++i) v = (sel[tq][i] == sl) ? P[tq][i] : v;
-        d2 = d2 + wave_max_all(v);
-      }
-      den[tq] = d2;
-    }
-  }
-#pragma unroll
-  for (int tq = 0; tq < TQ; ++tq) {
-    if (!tv[tq]) continue;
-    int32_t* oi = topk_idx + (size_t)tt[tq] * Kmax;
-    float* og = topk_gate + (size_t)tt[tq] * Kmax;
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      if (sel[tq][i] >= 0) {
-        oi[sel[tq][i]] = lane + 64 * i;
-        og[sel[tq][i]] = renorm ? P[tq][i] / den[tq] : P[tq][i];
+        const int e = lane + 64 * i;
+        float v = -INFINITY;
+        if (e < E) {
+          v = zs[tok][e];
+          if (bias != nullptr) v = v + bias[e];
+        }
+        P[tq][i] = v;
+        mx[tq] = (v > mx[tq]) ? v : mx[tq];
       }
     }
-    if (lane < Kmax && lane >= kk[tq]) {   // unused tail of the list
-      oi[lane] = -1;
-      og[lane] = 0.0f;
+  #pragma unroll
+    for (int s = 32; s >= 1; s >>= 1)
+  #pragma unroll
+      for (int tq = 0; tq < TQ; ++tq) {
+        const float o = __shfl_xor(mx[tq], s, 64);
+        mx[tq] = (o > mx[tq]) ? o : mx[tq];
+      }
+  #pragma unroll
+    for (int tq = 0; tq < TQ; ++tq) {
+      part[tq] = 0.0f;
+  #pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const int e = lane + 64 * i;
+        float q = 0.0f;
+        if (e < E) {
+          q = exp_fixed(P[tq][i] - mx[tq]);
+          part[tq] = part[tq] + q;
+        }
+        P[tq][i] = q;
+      }
+    }
+  #pragma unroll
+    for (int s = 32; s >= 1; s >>= 1)
+  #pragma unroll
+      for (int tq = 0; tq < TQ; ++tq) part[tq] = part[tq] + __shfl_xor(part[tq], s, 64);
+  #pragma unroll
+    for (int tq = 0; tq < TQ; ++tq)
+  #pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const int e = lane + 64 * i;
+        P[tq][i] = (e < E) ? P[tq][i] / part[tq] : -1.0f;   // -1 ranks below every probability
+        if (probs != nullptr && tv[tq] && e < E) probs[(size_t)tt[tq] * E + e] = P[tq][i];
+      }
+
+    // Top-k as k rounds of "take the largest remaining probability" (ties: lowest expert index), which
+    // yields the list in the order (probability desc, index asc) directly.  The maximum over the
+    // wavefront is order-free, so it uses the cheap lane-crossing modifiers (two quad permutes, two
+    // mirrors) inside a row of 16 lanes and four lane reads across rows.  The four tokens run side by
+    // side and a token that needs fewer than Kmax experts idles branch-free.
+    float work[TQ][NB];
+    int sel[TQ][NB];     // position of this lane's expert in the token's list, -1: not selected
+    float den[TQ];
+    int kk[TQ];
+  #pragma unroll
+    for (int tq = 0; tq < TQ; ++tq) {
+      kk[tq] = is_visual[tt[tq]] ? k_visual : k_text;
+      den[tq] = 0.0f;
+  #pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        work[tq][i] = P[tq][i];
+        sel[tq][i] = -1;
+      }
+    }
+    // with a selection strategy a token with k < k_base first lists its k_base candidates
+    int kc[TQ];
+  #pragma unroll
+    for (int tq = 0; tq < TQ; ++tq) kc[tq] = (SEL && kk[tq] < selp.k_base) ? selp.k_base : kk[tq];
+    const int rounds = (SEL && selp.k_base > Kmax) ? selp.k_base : Kmax;
+    for (int r = 0; r < rounds; ++r) {
+  #pragma unroll
+      for (int tq = 0; tq < TQ; ++tq) {
+        float v = work[tq][0];
+  #pragma unroll
+        for (int i = 1; i < NB; ++i) v = (work[tq][i] > v) ? work[tq][i] : v;
+        const float m = wave_max_all(v);
+        const bool active = r < kc[tq];
+        bool taken = false;
+  #pragma unroll
+        for (int i = 0; i < NB; ++i) {   // lowest expert index first: register i holds experts 64i..64i+63
+          const unsigned long long eq = __ballot(work[tq][i] == m);
+          const int owner = __ffsll((long long)eq) - 1;
+          if (active && !taken && lane == owner) {
+            sel[tq][i] = r;
+            work[tq][i] = -2.0f;
+          }
+          taken = taken || (eq != 0ull);
+        }
+        den[tq] = den[tq] + (active ? m : 0.0f);   // list order, sequential (Eq.5)
+      }
+    }
+    if constexpr (SEL) {
+      // random strategy: lane 16q + r holds the key of candidate position r of the wavefront's q-th
+      // token; a position is kept when fewer than k keys of its token are smaller (ties: lower position)
+      unsigned long long random_masks = 0ull;
+      if (selp.strategy == 1) {
+        const int q = lane >> 4, r = lane & 15;
+        const int tq_t = q == 0 ? tt[0] : (q == 1 ? tt[1] : (q == 2 ? tt[2] : tt[3]));
+        const int tq_k = q == 0 ? kk[0] : (q == 1 ? kk[1] : (q == 2 ? kk[2] : kk[3]));
+        const unsigned long long key = splitmix64_nth(selp.seed, (unsigned long long)tq_t * 16ull + (unsigned long long)r + 1ull);
+        int rank = 0;
+        for (int o = 0; o < 16; ++o) {
+          const int src = (lane & 48) + o;
+          const unsigned int lo = (unsigned int)__shfl((int)(unsigned int)key, src, 64);
+          const unsigned int hi = (unsigned int)__shfl((int)(unsigned int)(key >> 32), src, 64);
+          const unsigned long long ok = ((unsigned long long)hi << 32) | lo;
+          rank += (o < selp.k_base && (ok < key || (ok == key && o < r))) ? 1 : 0;
+        }
+        random_masks = __ballot(r < selp.k_base && rank < tq_k);
+      }
+  #pragma unroll
+      for (int tq = 0; tq < TQ; ++tq) {
+        if (kk[tq] >= selp.k_base) continue;   // not reduced: the list stands (uniform over the wavefront)
+        const int k = kk[tq];
+        unsigned int mask;   // kept candidate positions
+        if (selp.strategy == 1) mask = (unsigned int)(random_masks >> (16 * tq)) & 0xffffu;
+        else if (selp.strategy == 2) mask = ((1u << k) - 1u) << (selp.k_base - k);
+        else mask = (1u << k) - 1u;
+  #pragma unroll
+        for (int i = 0; i < NB; ++i) {
+          const int p = sel[tq][i];
+          if (p >= 0) sel[tq][i] = ((mask >> p) & 1u) ? __popc(mask & ((1u << p) - 1u)) : -1;
+        }
+        float d2 = 0.0f;   // Eq.5 over the kept experts, in list order
+        for (int sl = 0; sl < k; ++sl) {
+          float v = -1.0f;
+  #pragma unroll
+          for (int i = 0; i < NB; ++i) v = (sel[tq][i] == sl) ? P[tq][i] : v;
+          d2 = d2 + wave_max_all(v);
+        }
+        den[tq] = d2;
+      }
+    }
+  #pragma unroll
+    for (int tq = 0; tq < TQ; ++tq) {
+      if (!tv[tq]) continue;
+      int32_t* oi = topk_idx + (size_t)tt[tq] * Kmax;
+      float* og = topk_gate + (size_t)tt[tq] * Kmax;
+  #pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        if (sel[tq][i] >= 0) {
+          oi[sel[tq][i]] = lane + 64 * i;
+          og[sel[tq][i]] = renorm ? P[tq][i] / den[tq] : P[tq][i];
+        }
+      }
+      if (lane < Kmax && lane >= kk[tq]) {   // unused tail of the list
+        oi[lane] = -1;
+        og[lane] = 0.0f;
+      }
     }
   }
 }
 
-template <typename XT, int NB, int PF>
+template <typename XT, int NB, int PF, bool TT2 = (NB <= 2)>
 int launch_route_t(const fmoe_ctx* ctx, const void* x, const uint8_t* is_visual, int T, float* probs,
                    int32_t* topk_idx, float* topk_gate, const fmoe_ordinals_job& ord, hipStream_t stream, const int32_t* T_dev) {
   const int d = ctx->cfg.d_model, E = ctx->cfg.n_experts;
   const int Eb = (E + 15) / 16, G = router_groups(d);
   const int nch = (((d + KC - 1) / KC + PF - 1) / PF) * PF;   // <= G / NG by construction
-  const int grid = (T + TOKB - 1) / TOKB;
+  // two token tiles per block once that still leaves every CU several blocks (and only for the default
+  // selection strategy and up to 128 experts, where the registers allow it)
+  const bool two = TT2 && T >= FMOE_ROUTE_TT2_MIN_TOKENS && ctx->sel_strategy == 0;
+  const int per_block = two ? 2 * TOKB : TOKB;
+  const int grid = (T + per_block - 1) / per_block;
   fmoe_prof_scope prof(ctx, SLOT_ROUTE, stream);
   const int riders = ord.cu != nullptr ? ord.B : 0;
   const fmoe_selection selp{ctx->sel_strategy, ctx->sel_k_base, ctx->sel_seed};
-  if (ctx->sel_strategy != 0)
-    hipLaunchKernelGGL((route_kernel<XT, NB, PF, true>), dim3(grid + riders), dim3(256), 0, stream,
-                       static_cast<const XT*>(x), reinterpret_cast<const fx4_t*>(ctx->router_wp),
-                       ctx->router_bias, is_visual, T, d, E, Eb, G, nch, ctx->cfg.k_text, ctx->cfg.k_visual,
-                       ctx->kmax, ctx->cfg.renormalize, probs, topk_idx, topk_gate, grid, ord, T_dev, selp);
-  else
-    hipLaunchKernelGGL((route_kernel<XT, NB, PF, false>), dim3(grid + riders), dim3(256), 0, stream,
-                       static_cast<const XT*>(x), reinterpret_cast<const fx4_t*>(ctx->router_wp),
-                       ctx->router_bias, is_visual, T, d, E, Eb, G, nch, ctx->cfg.k_text, ctx->cfg.k_visual,
-                       ctx->kmax, ctx->cfg.renormalize, probs, topk_idx, topk_gate, grid, ord, T_dev, selp);
+#define FMOE_ROUTE_LAUNCH(SEL, TT)                                                                              \
+  hipLaunchKernelGGL((route_kernel<XT, NB, PF, SEL, TT>), dim3(grid + riders), dim3(256), 0, stream,            \
+                     static_cast<const XT*>(x), reinterpret_cast<const fx4_t*>(ctx->router_wp),                 \
+                     ctx->router_bias, is_visual, T, d, E, Eb, G, nch, ctx->cfg.k_text, ctx->cfg.k_visual,      \
+                     ctx->kmax, ctx->cfg.renormalize, probs, topk_idx, topk_gate, grid, ord, T_dev, selp)
+  if (ctx->sel_strategy != 0) FMOE_ROUTE_LAUNCH(true, 1);
+  else if constexpr (TT2) { if (two) FMOE_ROUTE_LAUNCH(false, 2); else FMOE_ROUTE_LAUNCH(false, 1); }
+  else FMOE_ROUTE_LAUNCH(false, 1);
+#undef FMOE_ROUTE_LAUNCH
   FMOE_HIP_CHECK(hipGetLastError());
   return FMOE_OK;
 }
