@@ -48,7 +48,7 @@ def check_accumulation_registers(asm_path):
             continue
         if not inside:
             continue
-        if "s_endpgm" in line:
+        if line.startswith(".Lfunc_end"):   # not s_endpgm: a kernel has one per early exit
             inside = False
         elif "ASMSTART" in line:
             in_asm = True

@@ -148,11 +148,15 @@ __device__ __forceinline__ void lds_read_frags(uint32_t addr, u32x4_t (&f)[NRB])
 // operands of the wait).
 template <int NRB, int OFF>
 __device__ __forceinline__ void lds_issue_frags_at(uint32_t addr, u32x4_t (&f)[NRB]) {
-  static_assert(NRB == 2 || NRB == 4, "supported fragment counts");
+  static_assert(NRB == 2 || NRB == 3 || NRB == 4, "supported fragment counts");
   static_assert(OFF >= 0 && OFF + (NRB - 1) * 2048 < 65536, "offset field of an LDS instruction");
   if constexpr (NRB == 2) {
     asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4"
                  : "=&v"(f[0]), "=&v"(f[1]) : "v"(addr), "n"(OFF), "n"(OFF + 2048) : "memory");
+  } else if constexpr (NRB == 3) {
+    asm volatile("ds_read_b128 %0, %3 offset:%4\n\tds_read_b128 %1, %3 offset:%5\n\tds_read_b128 %2, %3 offset:%6"
+                 : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2])
+                 : "v"(addr), "n"(OFF), "n"(OFF + 2048), "n"(OFF + 4096) : "memory");
   } else {
     asm volatile("ds_read_b128 %0, %4 offset:%5\n\tds_read_b128 %1, %4 offset:%6\n\t"
                  "ds_read_b128 %2, %4 offset:%7\n\tds_read_b128 %3, %4 offset:%8"
@@ -162,9 +166,11 @@ __device__ __forceinline__ void lds_issue_frags_at(uint32_t addr, u32x4_t (&f)[N
 }
 template <int NRB>
 __device__ __forceinline__ void lds_settle_frags(u32x4_t (&f)[NRB]) {
-  static_assert(NRB == 2 || NRB == 4, "supported fragment counts");
+  static_assert(NRB == 2 || NRB == 3 || NRB == 4, "supported fragment counts");
   if constexpr (NRB == 2) {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]) : : "memory");
+  } else if constexpr (NRB == 3) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]) : : "memory");
   } else {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) : : "memory");
   }
@@ -513,14 +519,14 @@ __global__ __launch_bounds__(256, 2) void ffn_stream_kernel(StreamArgs a) {
 // IDX is a[4*IDX : 4*IDX+3].  Left to the compiler, the accumulators share the vector register budget
 // with everything else and part of them travels through scratch memory; named, they cost the
 // allocator nothing, and, being volatile, the instructions keep their place in the step.  The compiler
-// does not see these registers: dense_claim_acc() tells it that the kernel owns a0..a127 (so that a
-// wavefront is given them and the compiler half of its 256 registers), the build scans the generated
-// code of the dense kernel and fails if the compiler itself placed anything in an accumulation
-// register, and the parity tests run this shape on every size.
-template <int IDX>
-__device__ __forceinline__ void mfma_at(bf16x8_t a, bf16x8_t b) {
-  asm volatile("v_mfma_f32_16x16x32_bf16 a[%0:%1], %2, %3, a[%0:%1]" : : "n"(4 * IDX), "n"(4 * IDX + 3), "v"(a), "v"(b));
-}
+// does not see what these instructions do, so it is told: dense_claim_acc() lists a0..a127 as written
+// (a wavefront is then given them, and the compiler half of its 256 registers), and every matrix
+// instruction lists its four registers as destroyed (mfma_at<IDX>), so that the compiler cannot keep a
+// value of its own in one of them across the k loop -- it did once: a row index of the epilogue, which
+// came back as accumulator bits and sent the output store to a wild address.  On top of that the build
+// reads the generated code of the dense kernels from the first to the last line and fails if the
+// compiler itself placed anything in an accumulation register, and the parity tests run this shape on
+// every size.
 template <int IDX>
 __device__ __forceinline__ f32x4_t read_acc() {
   float r0, r1, r2, r3;
@@ -530,7 +536,7 @@ __device__ __forceinline__ f32x4_t read_acc() {
                : "n"(4 * IDX), "n"(4 * IDX + 1), "n"(4 * IDX + 2), "n"(4 * IDX + 3));
   return f32x4_t{r0, r1, r2, r3};
 }
-#include "dense_regs.inc"   // dense_claim_acc(): zeroes a0..a127 and lists them as written
+#include "dense_regs.inc"   // dense_claim_acc(): zeroes a0..a127 and lists them as written; mfma_at<IDX>()
 
 // ---- the dense shape: one (row tile, group of DNCB column tiles) work item per workgroup.
 // Wavefront w owns column block w of each of the DNCB column tiles nt4 .. nt4+DNCB-1 of the packing (so
@@ -735,8 +741,12 @@ __global__ __launch_bounds__(256, 2) void ffn_dense_kernel(StreamArgs a) {
     P.A += (size_t)group * P.a_group_off;
     P.C += (size_t)group * P.c_group_off;
   }
-  if (tile.rows > 64) dense_tile<SWIGLU, 4>(P, tile, group, nt4, ct_limit, As);   // uniform per block
-  else dense_tile<SWIGLU, 2>(P, tile, group, nt4, ct_limit, As);
+  switch ((tile.rows + 31) >> 5) {   // live 32-row bands of the tile, uniform per block
+    case 1: dense_tile<SWIGLU, 1>(P, tile, group, nt4, ct_limit, As); break;
+    case 2: dense_tile<SWIGLU, 2>(P, tile, group, nt4, ct_limit, As); break;
+    case 3: dense_tile<SWIGLU, 3>(P, tile, group, nt4, ct_limit, As); break;
+    default: dense_tile<SWIGLU, 4>(P, tile, group, nt4, ct_limit, As); break;
+  }
 }
 
 // Packing: unit u (16 bytes = 8 consecutive k) -> (group, tile of 4 column blocks, 64-wide k tile,

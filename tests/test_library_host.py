@@ -361,19 +361,22 @@ def test_build_check_catches_compiler_use_of_hand_placed_accumulation_registers(
     """The dense-shape GEMM kernels name their accumulation registers themselves; the build reads the
     compiler's assembly and must refuse any a<N> operand the compiler placed inside those kernels."""
     from paper_2511_17885_amd import build
-    ok = ("_ZN1x16ffn_dense_kernelILb1ELi2EEEv:\n\tv_add_u32 v1, v2, v3\n\t;;#ASMSTART\n"
-          "\tv_mfma_f32_16x16x32_bf16 a[0:3], v[4:7], v[8:11], a[0:3]\n\t;;#ASMEND\n\ts_endpgm\n"
-          "_ZN1x17ffn_stream_kernelILb1EEEv:\n\tv_accvgpr_write_b32 a7, v0\n\ts_endpgm\n")
+    ok = ("_ZN1x16ffn_dense_kernelILb1ELi2EEEv:\n\ts_cbranch_scc1 .LBB0_2\n\ts_endpgm\n.LBB0_2:\n"   # an early exit
+          "\tv_add_u32 v1, v2, v3\n\t;;#ASMSTART\n"
+          "\tv_mfma_f32_16x16x32_bf16 a[0:3], v[4:7], v[8:11], a[0:3]\n\t;;#ASMEND\n\ts_endpgm\n.Lfunc_end0:\n"
+          "_ZN1x17ffn_stream_kernelILb1EEEv:\n\tv_accvgpr_write_b32 a7, v0\n\ts_endpgm\n.Lfunc_end1:\n")
     p = tmp_path / "ok.s"
     p.write_text(ok)
     assert build.check_accumulation_registers(str(p)) == 1
-    for planted in ("\tv_accvgpr_write_b32 a5, v102\n", "\tbuffer_load_dwordx4 a[8:11], v1, s[0:3], 0 offen\n"):
+    # planted after the kernel's first s_endpgm: the whole kernel is read, not only the code before its first exit
+    for planted in ("\tv_accvgpr_write_b32 a5, v102\n", "\tbuffer_load_dwordx4 a[8:11], v1, s[0:3], 0 offen\n",
+                    "\tv_accvgpr_read_b32 v101, a0\n"):
         bad = tmp_path / "bad.s"
         bad.write_text(ok.replace("\tv_add_u32 v1, v2, v3\n", planted))
         with pytest.raises(RuntimeError):
             build.check_accumulation_registers(str(bad))
     none = tmp_path / "none.s"
-    none.write_text("_ZN1x17ffn_stream_kernelILb1EEEv:\n\ts_endpgm\n")
+    none.write_text("_ZN1x17ffn_stream_kernelILb1EEEv:\n\ts_endpgm\n.Lfunc_end0:\n")
     with pytest.raises(RuntimeError):
         build.check_accumulation_registers(str(none))
     # and the assembly of the library as built passes

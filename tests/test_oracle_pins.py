@@ -803,7 +803,7 @@ def flops_table_rows():
 
 def test_flops_ratios_reproduce_every_saving_the_paper_prints():
     rows = flops_table_rows()
-    assert len(rows) == 12
+    assert len(rows) == 13
     for model, keep, beta, lv, kv, saving in rows:
         m = dict(FLOPS_MODELS[model])
         shared = m.pop("shared")
