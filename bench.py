@@ -40,11 +40,17 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 MFMA_F32_PEAK_TFLOPS = 157.3
 VALU_F32_PEAK_TFLOPS = 157.3
 GEMM1, GEMM2 = "gate_up_gemm", "down_gemm"   # work-table keys; the kernel that ran is named by the profile slots
-# HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs per workload
-# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch; the factors are what a 256 MiB device copy
-# reads on the same counters), averaged over the launches of one step -- profiles/*_hbm_traffic.md.
-# A workload without an entry has not been measured (traffic: null).
-MEASURED_TRAFFIC_BYTES = {"c2": int((84611.9 * 2.0 + 7616.0) * 1024)}
+# Bytes between the L2 caches and memory per launch of the dominant kernel, from two rocprofv3 --pmc runs per
+# workload (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch; the factors are what a 256 MiB device
+# copy reads on the same counters), averaged over the launches of one step --
+# profiles/expert_gemm_hbm_traffic_c5_stack_c2_c3_c4.md.  The figures belong to the kernels as they
+# were when that file was written; a workload without an entry has not been measured (traffic: null).
+MEASURED_TRAFFIC_BYTES = {   # workload -> (the kernel the figure belongs to, bytes per launch)
+    "c5_stack": ("ffn_dense_kernel<true>", int((1491196.8 * 2.0 + 219765.3) * 1024)),
+    "c2": ("ffn_stream_kernel<true>", int((84773.1 * 2.0 + 7616.0) * 1024)),
+    "c3": ("ffn_dense_kernel<true>", int((481586.9 * 2.0 + 32032.0) * 1024)),
+    "c4": ("ffn_dense_kernel<true>", int((419921.0 * 2.0 + 26880.0) * 1024)),
+}
 
 
 def _dev(a, t=None):
@@ -151,8 +157,9 @@ def _roofline(kernels, work, launches, workload, bound):
     name = max(cands, key=lambda n: kernels[n]["us"] * kernels[n]["launches_per_step"])   # the dominant kernel
     k = kernels[name]
     n = max(launches.get(name, 1), 1)
+    measured = MEASURED_TRAFFIC_BYTES.get(workload)
     r = {"kernel": name, "bound": bound, "us_per_launch": k["us"], "launches_per_step": n,
-         "traffic": MEASURED_TRAFFIC_BYTES.get(workload),
+         "traffic": measured[1] if measured and measured[0] == name else None,
          "algo_bytes_per_launch": int(work[name]["bytes"] / n), "algo_flops_per_launch": work[name]["flops"] / n}
     if bound == "mfma":
         r.update(achieved=k["TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=k["compute_frac"],
@@ -240,7 +247,8 @@ def run_layer(args, name, cpu_baseline):
                    "experts_touched": touched, "weight_copies": NL,
                    **({"gamma": args.gamma} if args.gamma > 0 else {})},
         "dtype": "bf16" if is_bf16 else "f32",
-        "roofline": _roofline(kernels, work, launches, name, "mfma" if rows_per_expert >= 315 else "hbm"),
+        "roofline": _roofline(kernels, work, launches, name if args.gamma == 0 else None,
+                              "mfma" if rows_per_expert >= 315 else "hbm"),
         "kernel_sum_us": round(sum(kms.values()) * 1e3, 2), "kernels": kernels,
     }
     if cpu_baseline:
