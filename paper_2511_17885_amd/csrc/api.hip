@@ -125,6 +125,7 @@ fmoe_ws_layout fmoe_layout(const fmoe_ctx* ctx, int32_t max_tokens, int32_t max_
   L.win_a = take(T * 4);
   L.drop_from = take(T * 4);
   L.keep_prefix = take((T + 1) * 4);
+  L.compact_blk = take((T / 1024 + 2) * 4);
   L.rank_c = take(T * 4);
   L.win_merged = take(T * 4);
   L.merged_before = take(T * 4);
@@ -572,7 +573,7 @@ int fmoe_profile_slots(void) { return SLOT_COUNT; }
 const char* fmoe_profile_name(int slot) {
   // kernel symbols (the two expert GEMMs: bf16 symbol; fp32 contexts run grouped_gemm_kernel)
   static const char* names[SLOT_COUNT] = {
-      "route_kernel", "seq_ordinals_kernel", "window_score_kernel", "select_kernel", "compact_kernel",
+      "route_kernel", "seq_ordinals_kernel", "window_score_kernel", "select_kernel", "compact_flag_kernel+compact_write_kernel",
       "prune_dispatch_small_kernel", "permute_count_kernel", "permute_scan_kernel",
       "permute_scatter_kernel", "build_tiles_kernel", "ffn_stream_kernel<true>",
       "ffn_stream_kernel<false>", "combine_kernel", "ffn_dense_kernel<true>", "ffn_dense_kernel<false>"};

@@ -72,6 +72,7 @@ struct fmoe_ws_layout {
   size_t probs, topk_idx, topk_gate;            // layer_forward intermediates
   size_t vis_tok, vis_ord, seq_nv;              // prune
   size_t win_s, win_a, drop_from, keep_prefix;  // prune
+  size_t compact_blk;                           // prune: kept tokens per block of the compaction
   size_t rank_c, win_merged, merged_before;     // prune with window merging
   size_t is_merged, vis_out, x_merged;          // layer_forward with window merging
   size_t slot_rank, blk_count;                  // permute

@@ -34,24 +34,47 @@ __global__ __launch_bounds__(256) void seq_ordinals_kernel(
   seq_ordinals_block(is_visual, cu, blockIdx.x, T, vis_ord, vis_tok, seq_nv, wave_tot);
 }
 
-// ---- B: window scores.  One wavefront per slot g in [0,T); lanes <-> experts.
-// win_s[g] = S_i (Eq.10 or Eq.8), win_a[g] = raw window attention sum (Eq.11) if attn.
+// ---- B: window scores.  One wavefront per window; lanes <-> experts.
+// win_s[g] = S_i (Eq.10 or Eq.8), win_a[g] = raw window attention sum (Eq.11) if attn, g = the window's slot.
+// Launch over window units: sequence b owns the units cu[b]/W + b ... (it has at most
+// floor(cu[b+1]/W) - floor(cu[b]/W) + 1 windows, so consecutive sequences never overlap and
+// floor(T/W) + B units cover every window); a unit finds its sequence by binary search.
+// STAGED: the wavefront copies the window's routing-probability rows into its own LDS tile once (coalesced
+// row reads) and both passes over the window -- the mean row, then the cosines (Eq.9-10), or all pairs
+// (Eq.8) -- read the tile; a lane only ever reads back the columns it stored itself, so no
+// synchronisation is involved.  Windows whose rows do not fit the tile (W*E > WS_TILE) take the
+// instantiation that re-reads global memory.  The arithmetic and its order are the same either way.
+constexpr int WS_TILE = 2048;   // floats of LDS per wavefront
+__device__ __forceinline__ int unit_base(const int32_t* cu, int b, int T, int W) {
+  return clampi(cu[b], 0, T) / W + b;
+}
+template <bool STAGED>
 __global__ __launch_bounds__(256) void window_score_kernel(
     const float* __restrict__ probs, const int32_t* __restrict__ cu, int B, int T, int E, int W,
     int sim_mode, const int32_t* __restrict__ vis_tok, const int32_t* __restrict__ seq_nv,
     const float* __restrict__ attn, float* __restrict__ win_s, float* __restrict__ win_a,
     int32_t* __restrict__ precede, int32_t* __restrict__ rank_c) {
+  __shared__ float tile_all[STAGED ? 4 * WS_TILE : 1];
   const int lane = threadIdx.x & 63;
-  const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (g >= T) return;
-  if (lane == 0) precede[g] = 0;   // accumulated by select_kernel
-  if (lane == 0 && rank_c != nullptr) rank_c[g] = 0;
-  const int b = find_seq(cu, B, g);
+  // counters of the drop order (accumulated by select_kernel), cleared for every slot
+  for (int g = blockIdx.x * 256 + threadIdx.x; g < T; g += gridDim.x * 256) {
+    precede[g] = 0;
+    if (rank_c != nullptr) rank_c[g] = 0;
+  }
+  const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int lo = 0, hi = B - 1;   // largest b with unit_base(b) <= u
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (unit_base(cu, mid, T, W) <= u) lo = mid; else hi = mid - 1;
+  }
+  const int b = lo;
   int s, e;
   seq_range(cu, b, T, s, e);
-  const int i = g - s;
-  const int nv = seq_nv[b];
+  const int i = u - unit_base(cu, b, T, W);
+  int nv = seq_nv[b];
+  nv = nv < e - s ? nv : e - s;                 // a sequence has no more visual tokens than tokens
   if (i < 0 || (long long)i * W >= nv) return;  // not a window of this sequence
+  const int g = s + i;                          // < s + nv <= T
   const int first = i * W;
   const int w = (nv - first < W) ? (nv - first) : W;
   const int32_t* toks = vis_tok + s + first;
@@ -65,6 +88,17 @@ __global__ __launch_bounds__(256) void window_score_kernel(
     if (lane == 0) win_s[g] = 1.0f;
     return;
   }
+  float* tile = tile_all + (STAGED ? (threadIdx.x >> 6) * WS_TILE : 0);
+  if (STAGED) {
+    for (int j = 0; j < w; ++j) {
+      const float* src = probs + (size_t)toks[j] * E;
+      for (int ex = lane; ex < E; ex += 64) tile[j * E + ex] = src[ex];
+    }
+  }
+  // element ex of the window's row j
+  auto row = [&](int j, int ex) -> float {
+    return STAGED ? tile[j * E + ex] : probs[(size_t)toks[j] * E + ex];
+  };
   float S;
   if (sim_mode == 0) {
     // Eq.9: mean row (sequential over the window, one divide), Eq.10: mean cosine to it
@@ -74,8 +108,8 @@ __global__ __launch_bounds__(256) void window_score_kernel(
       const int ex = lane + 64 * r;
       float acc = 0.0f;
       if (ex < E) {
-        acc = probs[(size_t)toks[0] * E + ex];
-        for (int j = 1; j < w; ++j) acc = acc + probs[(size_t)toks[j] * E + ex];
+        acc = row(0, ex);
+        for (int j = 1; j < w; ++j) acc = acc + row(j, ex);
         acc = acc / (float)w;
       }
       mean[r] = acc;
@@ -92,7 +126,7 @@ __global__ __launch_bounds__(256) void window_score_kernel(
       for (int r = 0; r < 4; ++r) {
         const int ex = lane + 64 * r;
         if (ex < E) {
-          const float v = probs[(size_t)toks[j] * E + ex];
+          const float v = row(j, ex);
           pd = fmaf(v, mean[r], pd);
           pn = fmaf(v, v, pn);
         }
@@ -112,7 +146,7 @@ __global__ __launch_bounds__(256) void window_score_kernel(
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int ex = lane + 64 * r;
-        rj[r] = (ex < E) ? probs[(size_t)toks[j] * E + ex] : 0.0f;
+        rj[r] = (ex < E) ? row(j, ex) : 0.0f;
         if (ex < E) pn = fmaf(rj[r], rj[r], pn);
       }
       const float nj = sqrtf(wave_sum_butterfly(pn));
@@ -122,7 +156,7 @@ __global__ __launch_bounds__(256) void window_score_kernel(
         for (int r = 0; r < 4; ++r) {
           const int ex = lane + 64 * r;
           if (ex < E) {
-            const float v = probs[(size_t)toks[q] * E + ex];
+            const float v = row(q, ex);
             pd = fmaf(rj[r], v, pd);
             pq = fmaf(v, v, pq);
           }
@@ -272,138 +306,144 @@ __global__ __launch_bounds__(256) void merge_decide_kernel(
   win_merged[g] = m;
 }
 
-// ---- D: budget + compaction.  A single block walks the tokens in order, keeps text tokens and the
-// leading tokens of each window, and writes ascending kept indices; keep_prefix[t] = kept tokens
-// before t.
-__global__ __launch_bounds__(1024) void compact_kernel(
-    const uint8_t* __restrict__ is_visual, const int32_t* __restrict__ cu, int B, int T, int W,
-    float retention, const int32_t* __restrict__ vis_ord, const int32_t* __restrict__ seq_nv,
-    const int32_t* __restrict__ precede, int32_t* __restrict__ keep_prefix,
-    int32_t* __restrict__ kept_idx,
-    int32_t* __restrict__ new_cu, uint8_t* __restrict__ is_visual_out,
-    float gamma, const int32_t* __restrict__ rank_c, const int32_t* __restrict__ win_merged,
-    const int32_t* __restrict__ merged_before, uint8_t* __restrict__ is_merged_out) {
-  // gamma > 0 (window merging): a merged window keeps exactly its first token; the others follow the
-  // drop rule with the merged windows taken out of the walk and the budget merging left.
-  // win_merged == nullptr (no attention term: drop order and merge order are the same order): which
-  // windows merge and how many merged windows precede a window follow in closed form from the
-  // window's place rank_c in that order and the place of the sequence's last window.
-  // CQ chunks of 1024 tokens per round.  A token's decision is a chain of dependent loads (its visual
-  // ordinal -> its window's counters); the round issues each link of the chain for all its chunks
-  // before using any of them, so that the memory latencies overlap, and the sequence bounds are
-  // searched in LDS.  One barrier pair serves the round's prefix sums.
-  constexpr int CQ = 4;
-  constexpr int CB = 1024;   // sequences whose bounds are cached in LDS
-  __shared__ int wave_tot[CQ][16];
-  __shared__ int s_cu[CB + 1], s_nv[CB];
-  const bool cached = B <= CB;
-  if (cached) {
-    for (int b = threadIdx.x; b <= B; b += 1024) s_cu[b] = clampi(cu[b], 0, T);
-    for (int b = threadIdx.x; b < B; b += 1024) s_nv[b] = seq_nv[b];
+// ---- D: budget + compaction, in two launches over blocks of CP_BLOCK positions (a position is a token
+// index, or T itself, which only carries the total).
+//   compact_flag_kernel:  every position decides keep / drop on its own (text tokens and the leading tokens
+//                         of each window stay) and stores (kept positions before it in its block) * 4 +
+//                         merged * 2 + keep in keep_code; every block stores its number of kept tokens.
+//   compact_write_kernel: a block's first output index is the sum of the counts of the blocks before it;
+//                         kept tokens write their ascending index lists; new_cu[b] = kept tokens before
+//                         cu[b], read off the same two arrays.
+// The decision is a chain of dependent loads per token (its visual ordinal -> its sequence -> its
+// window's counters), which is why it is spread over the chip instead of walked by one block.
+constexpr int CP_BLOCK = 1024;
+
+struct CompactArgs {
+  const uint8_t* is_visual;
+  const int32_t* cu;
+  int B, T, W;
+  float retention, gamma;
+  const int32_t* vis_ord;
+  const int32_t* seq_nv;
+  const int32_t* precede;
+  const int32_t* rank_c;          // gamma > 0
+  const int32_t* win_merged;      // gamma > 0 with an attention term; nullptr: closed form (see below)
+  const int32_t* merged_before;
+  int32_t* keep_code;             // [T + 1]
+  int32_t* blk_kept;              // [ceil((T + 1) / CP_BLOCK)]
+  int32_t* kept_idx;
+  int32_t* new_cu;
+  uint8_t* is_visual_out;         // or nullptr
+  uint8_t* is_merged_out;         // or nullptr
+};
+
+// largest b in [0,n) with clamp(cu[b]) <= g
+__device__ __forceinline__ int find_seq_clamped(const int32_t* cu, int n, int T, int g) {
+  int lo = 0, hi = n - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (clampi(cu[mid], 0, T) <= g) lo = mid; else hi = mid - 1;
   }
-  __syncthreads();
-  const int32_t* cuc = cached ? s_cu : cu;   // clamping a clamped bound changes nothing
-  const int32_t* nvc = cached ? s_nv : seq_nv;
-  const int t_end = clampi(cuc[B], 0, T);
-  const bool merging = gamma > 0.0f;
-  const bool closed = merging && win_merged == nullptr;
+  return lo;
+}
+
+// bit 0: token t survives, bit 1: it is the token a merged window collapses into.
+// gamma > 0 (window merging): a merged window keeps exactly its first token; the others follow the
+// drop rule with the merged windows taken out of the walk and the budget merging left.
+// win_merged == nullptr (no attention term: drop order and merge order are the same order): which
+// windows merge and how many merged windows precede a window follow in closed form from the
+// window's place rank_c in that order and the place of the sequence's last window.
+__device__ __forceinline__ int keep_decision(const CompactArgs& a, int t, int t_end) {
+  // tokens past the last sequence have no ordinal and count as text
+  const int ord = t < t_end ? a.vis_ord[t] : -1;
+  if (ord < 0) return 1;
+  const int T = a.T, W = a.W;
+  const int b = find_seq_clamped(a.cu, a.B, T, t);
+  const int s = clampi(a.cu[b], 0, T);
+  const int nv = a.seq_nv[b];
+  const int n = (nv + W - 1) / W;
+  const int last = T - 1;
+  int slot = s + ord / W;
+  slot = slot < last ? slot : last;            // (always inside for the ordinals seq_ordinals writes)
+  int slot_last = s + n - 1;
+  slot_last = slot_last < 0 ? 0 : (slot_last < last ? slot_last : last);
+  const int pc = a.precede[slot];
+  const int in_win = ord % W;
+  const bool merging = a.gamma > 0.0f;
+  if (!merging) return in_win < window_keep_lead(ord, nv, W, a.retention, pc) ? 1 : 0;
+  const bool closed = a.win_merged == nullptr;
+  const int rl = a.rank_c[slot_last];
+  const bool short_last = nv - (n - 1) * W < W;
+  const int L = short_last ? rl : n;
+  const fmoe_merge_plan p = merge_plan(nv, W, a.retention, a.gamma, L);
+  int is_m, mb, last_m;
+  if (closed) {
+    const int r = a.rank_c[slot];                                  // place of this window
+    const int k = r - ((short_last && L < r) ? 1 : 0);             // full-size windows ahead of it
+    const bool is_last = short_last && (ord / W == n - 1);
+    is_m = is_last ? p.last_m : (k < p.q_full ? 1 : 0);
+    last_m = short_last ? p.last_m : (rl < p.q_full ? 1 : 0);
+    mb = (k < p.q_full ? k : p.q_full) + ((short_last && p.last_m && L < r) ? 1 : 0);
+  } else {
+    is_m = a.win_merged[slot];
+    mb = a.merged_before[slot];
+    last_m = a.win_merged[slot_last];
+  }
+  if (is_m) return in_win == 0 ? 3 : 0;
+  return in_win < window_keep_lead_merge(ord, nv, W, pc, mb, last_m != 0, p.u_rem) ? 1 : 0;
+}
+
+__global__ __launch_bounds__(CP_BLOCK) void compact_flag_kernel(CompactArgs a) {
+  __shared__ int wave_tot[CP_BLOCK / 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int running = 0;
-  for (int base = 0; base < T; base += CQ * 1024) {
-    int ord_q[CQ], s_q[CQ], nv_q[CQ], pc_q[CQ], wm_q[CQ], mb_q[CQ], rl_q[CQ], lm_q[CQ];
-#pragma unroll
-    for (int q = 0; q < CQ; ++q) {
-      const int t = base + q * 1024 + threadIdx.x;
-      // -2: past the end, -1: text; tokens past the last sequence have no ordinal and count as text
-      ord_q[q] = (t < T) ? (t < t_end ? vis_ord[t] : -1) : -2;
-    }
-#pragma unroll
-    for (int q = 0; q < CQ; ++q) {
-      const int t = base + q * 1024 + threadIdx.x;
-      s_q[q] = 0; nv_q[q] = 0; pc_q[q] = 0; wm_q[q] = 0; mb_q[q] = 0; rl_q[q] = 0; lm_q[q] = 0;
-      if (ord_q[q] >= 0) {
-        const int b = find_seq(cuc, B, t);
-        s_q[q] = clampi(cuc[b], 0, T);
-        nv_q[q] = nvc[b];
-        const int slot = s_q[q] + ord_q[q] / W;
-        pc_q[q] = precede[slot];
-        if (merging) {
-          const int n = (nv_q[q] + W - 1) / W;
-          rl_q[q] = rank_c[s_q[q] + n - 1];
-          if (closed) {
-            wm_q[q] = rank_c[slot];   // the window's place; turned into the merged flag below
-          } else {
-            wm_q[q] = win_merged[slot];
-            mb_q[q] = merged_before[slot];
-            lm_q[q] = win_merged[s_q[q] + n - 1];
-          }
-        }
-      }
-    }
-    bool keep_q[CQ], merged_q[CQ];
-#pragma unroll
-    for (int q = 0; q < CQ; ++q) {
-      const int ord = ord_q[q];
-      bool keep = (ord == -1), merged_tok = false;
-      if (ord >= 0) {
-        const int nv = nv_q[q];
-        const int in_win = ord % W;
-        if (!merging) {
-          keep = in_win < window_keep_lead(ord, nv, W, retention, pc_q[q]);
-        } else {
-          const int n = (nv + W - 1) / W;
-          const bool short_last = nv - (n - 1) * W < W;
-          const int L = short_last ? rl_q[q] : n;
-          const fmoe_merge_plan p = merge_plan(nv, W, retention, gamma, L);
-          int is_m = wm_q[q], mb = mb_q[q], last_m = lm_q[q];
-          if (closed) {
-            const int r = wm_q[q];                                   // place of this window
-            const int k = r - ((short_last && L < r) ? 1 : 0);       // full-size windows ahead of it
-            const bool is_last = short_last && (ord / W == n - 1);
-            is_m = is_last ? p.last_m : (k < p.q_full ? 1 : 0);
-            last_m = short_last ? p.last_m : (rl_q[q] < p.q_full ? 1 : 0);
-            mb = (k < p.q_full ? k : p.q_full) + ((short_last && p.last_m && L < r) ? 1 : 0);
-          }
-          if (is_m) keep = merged_tok = in_win == 0;
-          else keep = in_win < window_keep_lead_merge(ord, nv, W, pc_q[q], mb, last_m != 0, p.u_rem);
-        }
-      }
-      keep_q[q] = keep;
-      merged_q[q] = merged_tok;
-    }
-    int before_q[CQ];
-#pragma unroll
-    for (int q = 0; q < CQ; ++q) {
-      const unsigned long long mask = __ballot(keep_q[q]);
-      before_q[q] = __popcll(mask & ((1ull << lane) - 1ull));
-      if (lane == 0) wave_tot[q][wave] = __popcll(mask);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < CQ; ++q) {
-      int wave_base = 0, total = 0;
-#pragma unroll
-      for (int w = 0; w < 16; ++w) {
-        if (w < wave) wave_base += wave_tot[q][w];
-        total += wave_tot[q][w];
-      }
-      const int t = base + q * 1024 + threadIdx.x;
-      if (t < T) {
-        const int pos = running + wave_base + before_q[q];
-        keep_prefix[t] = pos;
-        if (keep_q[q]) {
-          kept_idx[pos] = t;
-          if (is_visual_out != nullptr) is_visual_out[pos] = is_visual[t];
-          if (is_merged_out != nullptr) is_merged_out[pos] = merged_q[q] ? 1 : 0;
-        }
-      }
-      running += total;
-    }
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) keep_prefix[T] = running;
+  const int t = blockIdx.x * CP_BLOCK + threadIdx.x;
+  const int t_end = clampi(a.cu[a.B], 0, a.T);
+  const int bits = t < a.T ? keep_decision(a, t, t_end) : 0;
+  const unsigned long long mask = __ballot(bits & 1);
+  const int before = __popcll(mask & ((1ull << lane) - 1ull));
+  if (lane == 0) wave_tot[wave] = __popcll(mask);
   __syncthreads();
-  for (int b = threadIdx.x; b <= B; b += 1024) new_cu[b] = keep_prefix[clampi(cu[b], 0, T)];
+  int wave_base = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < CP_BLOCK / 64; ++w) {
+    if (w < wave) wave_base += wave_tot[w];
+    total += wave_tot[w];
+  }
+  if (t <= a.T) a.keep_code[t] = ((wave_base + before) << 2) | bits;
+  if (threadIdx.x == 0) a.blk_kept[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(CP_BLOCK) void compact_write_kernel(CompactArgs a) {
+  __shared__ int part[CP_BLOCK / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // kept tokens in the blocks before this one
+  int sum = 0;
+  for (int k = threadIdx.x; k < (int)blockIdx.x; k += CP_BLOCK) sum += a.blk_kept[k];
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
+  if (lane == 0) part[wave] = sum;
+  __syncthreads();
+  int first = 0;
+#pragma unroll
+  for (int w = 0; w < CP_BLOCK / 64; ++w) first += part[w];
+  const int t = blockIdx.x * CP_BLOCK + threadIdx.x;
+  if (t < a.T) {
+    const int code = a.keep_code[t];
+    const int pos = first + (code >> 2);
+    if ((code & 1) && pos >= 0 && pos < a.T) {   // pos <= t by construction
+      a.kept_idx[pos] = t;
+      if (a.is_visual_out != nullptr) a.is_visual_out[pos] = a.is_visual[t];
+      if (a.is_merged_out != nullptr) a.is_merged_out[pos] = (code >> 1) & 1;
+    }
+  }
+  // sequence bounds of the kept tokens: kept tokens before cu[b]
+  for (int b = blockIdx.x * CP_BLOCK + threadIdx.x; b <= a.B; b += gridDim.x * CP_BLOCK) {
+    const int c = clampi(a.cu[b], 0, a.T);
+    const int blk = c / CP_BLOCK;
+    int before = 0;
+    for (int k = 0; k < blk; ++k) before += a.blk_kept[k];
+    a.new_cu[b] = before + (a.keep_code[c] >> 2);
+  }
 }
 
 // ---- D2: the layer input after merging (Eq.16-18).  One block per kept position: an ordinary token's
@@ -838,6 +878,20 @@ __global__ __launch_bounds__(SB_THREADS) void prune_dispatch_small_kernel(SmallA
   }
 }
 
+// One wavefront per window unit (floor(T/W) + B units cover every window), four per block.
+void launch_window_scores(const float* probs, const int32_t* cu_seqlens, int B, int T, int E, int W,
+                          int sim_mode, const int32_t* vis_tok, const int32_t* seq_nv, const float* attn,
+                          float* win_s, float* win_a, int32_t* precede, int32_t* rank_c, hipStream_t stream) {
+  const int n_units = T / W + B;
+  const dim3 grid((n_units + 3) / 4);
+  if ((long long)W * E <= WS_TILE)
+    hipLaunchKernelGGL(window_score_kernel<true>, grid, dim3(256), 0, stream, probs, cu_seqlens, B, T, E, W,
+                       sim_mode, vis_tok, seq_nv, attn, win_s, win_a, precede, rank_c);
+  else
+    hipLaunchKernelGGL(window_score_kernel<false>, grid, dim3(256), 0, stream, probs, cu_seqlens, B, T, E, W,
+                       sim_mode, vis_tok, seq_nv, attn, win_s, win_a, precede, rank_c);
+}
+
 }  // namespace
 
 int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* probs,
@@ -870,9 +924,8 @@ int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* 
   }
   {
     fmoe_prof_scope prof(ctx, SLOT_SCORES, stream);
-    hipLaunchKernelGGL(window_score_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, probs, cu_seqlens,
-                       B, T, E, pp->window, pp->sim_mode, vis_tok, seq_nv, attn, win_s, win_a, drop_from,
-                       rank_c);
+    launch_window_scores(probs, cu_seqlens, B, T, E, pp->window, pp->sim_mode, vis_tok, seq_nv, attn, win_s,
+                         win_a, drop_from, rank_c, stream);
   }
   const int n_max = (T + pp->window - 1) / pp->window;   // no sequence has more windows
   const int gy = (n_max + SEL_JC - 1) / SEL_JC;
@@ -893,11 +946,17 @@ int launch_prune(const fmoe_ctx* ctx, const fmoe_prune_params* pp, const float* 
   }
   {
     fmoe_prof_scope prof(ctx, SLOT_COMPACT, stream);
-    hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, stream, is_visual, cu_seqlens, B, T,
-                       pp->window, pp->retention, vis_ord, seq_nv, drop_from, keep_prefix, kept_idx,
-                       new_cu_seqlens, is_visual_out, pp->gamma, rank_c,
-                       closed_form ? static_cast<int32_t*>(nullptr) : win_merged, merged_before,
-                       merging ? is_merged : static_cast<uint8_t*>(nullptr));
+    CompactArgs ca;
+    ca.is_visual = is_visual; ca.cu = cu_seqlens; ca.B = B; ca.T = T; ca.W = pp->window;
+    ca.retention = pp->retention; ca.gamma = pp->gamma;
+    ca.vis_ord = vis_ord; ca.seq_nv = seq_nv; ca.precede = drop_from; ca.rank_c = rank_c;
+    ca.win_merged = closed_form ? nullptr : win_merged; ca.merged_before = merged_before;
+    ca.keep_code = keep_prefix; ca.blk_kept = reinterpret_cast<int32_t*>(base + L.compact_blk);
+    ca.kept_idx = kept_idx; ca.new_cu = new_cu_seqlens; ca.is_visual_out = is_visual_out;
+    ca.is_merged_out = merging ? is_merged : nullptr;
+    const dim3 cgrid((T + 1 + CP_BLOCK - 1) / CP_BLOCK);
+    hipLaunchKernelGGL(compact_flag_kernel, cgrid, dim3(CP_BLOCK), 0, stream, ca);
+    hipLaunchKernelGGL(compact_write_kernel, cgrid, dim3(CP_BLOCK), 0, stream, ca);
   }
   if (merging) {
     if (ctx->cfg.dtype == FMOE_BF16)
@@ -947,9 +1006,8 @@ int launch_prune_dispatch_small(const fmoe_ctx* ctx, const fmoe_prune_params* pp
   const int E = ctx->cfg.n_experts;
   if (prune) {   // the visual ordinals were produced in the router's launch
     fmoe_prof_scope prof(ctx, SLOT_SCORES, stream);
-    hipLaunchKernelGGL(window_score_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, probs, cu_seqlens,
-                       B, T, E, pp->window, pp->sim_mode, vis_tok, seq_nv, attn, win_s, win_a, drop_from,
-                       static_cast<int32_t*>(nullptr));
+    launch_window_scores(probs, cu_seqlens, B, T, E, pp->window, pp->sim_mode, vis_tok, seq_nv, attn, win_s,
+                         win_a, drop_from, nullptr, stream);
   }
   SmallArgs a;
   a.prune = prune ? 1 : 0;

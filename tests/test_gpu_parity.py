@@ -135,6 +135,62 @@ def test_prune(seed, kw, sim_mode):
     assert np.array_equal(got, o_scores)
 
 
+@pytest.mark.parametrize("E,window", [(256, 9), (64, 40), (100, 21), (256, 8)])
+@pytest.mark.parametrize("sim_mode", [0, 1])
+def test_prune_windows_around_the_size_of_the_staging_tile(E, window, sim_mode):
+    """The scoring kernel stages a window's probability rows in a tile of 2048 floats per wavefront and
+    re-reads global memory for wider windows (W*E > 2048): both sides of that limit, ragged sequences, a
+    ragged last window, with the attention term; scores, kept set and bounds bit for bit."""
+    wl = W.small_random(140 + window, T_v=[3 * window + 2, 1, 7 * window, window - 1], T_t=[3, 2, 0, 5], d=32, E=E,
+                        F=16, k_text=4, k_visual=2, retention=0.6, window=window, n_components=7, bias_std=1.0,
+                        interleave=True)
+    rng = np.random.default_rng(77)
+    attn = rng.random(wl.T).astype(np.float32) ** 2
+    o_probs, _, _ = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias, 4, 2)
+    o_kept, o_cu, o_scores = oracle.prune(o_probs, wl.is_visual, wl.cu_seqlens, wl.retention, window, alpha=0.7,
+                                          attn=attn, sim_mode=sim_mode)
+    m = make_layer(wl)
+    pp = binding.prune_params(retention=wl.retention, window=window, alpha=0.7, sim_mode=sim_mode)
+    kept, new_cu, scores = m.prune(pp, dev(o_probs), dev(wl.is_visual), dev(wl.cu_seqlens), attn=dev(attn),
+                                   want_scores=True)
+    torch.cuda.synchronize()
+    new_cu = host(new_cu)
+    assert np.array_equal(new_cu, o_cu)
+    assert np.array_equal(host(kept)[:new_cu[-1]], o_kept)
+    scores = host(scores)
+    got = []
+    for b in range(wl.B):
+        s, e = wl.cu_seqlens[b], wl.cu_seqlens[b + 1]
+        nv = int(wl.is_visual[s:e].sum())
+        got.append(scores[s:s + (nv + window - 1) // window])
+    assert np.array_equal(np.concatenate(got), o_scores)
+
+
+@pytest.mark.parametrize("T_v,T_t", [([1023], [0]), ([1000], [24]), ([1024], [1]), ([700, 0, 2500, 1, 1900], [30, 5, 0, 0, 9])])
+@pytest.mark.parametrize("gamma", [0.0, 0.2])
+def test_prune_over_several_compaction_blocks(T_v, T_t, gamma):
+    """The compaction runs over blocks of 1024 positions (position T carries the total): batches that end
+    just below, at and above a block boundary and one of several ragged sequences over five blocks, with
+    and without window merging; kept set, merged flags and sequence bounds bit for bit."""
+    wl = W.small_random(171, T_v=T_v, T_t=T_t, d=32, E=16, F=16, k_text=3, k_visual=2, retention=0.45, window=3,
+                        n_components=9, bias_std=1.0, interleave=True)
+    o_probs, _, _ = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias, 3, 2)
+    o_kept, o_cu, _, o_mrg, _ = oracle.prune(o_probs, wl.is_visual, wl.cu_seqlens, wl.retention, 3, gamma=gamma,
+                                             x=wl.x)
+    m = make_layer(wl)
+    pp = binding.prune_params(retention=wl.retention, window=3, gamma=gamma)
+    if gamma > 0:
+        kept, new_cu, _, mrg, _ = m.prune(pp, dev(o_probs), dev(wl.is_visual), dev(wl.cu_seqlens), x=dev(wl.x))
+    else:
+        kept, new_cu, _ = m.prune(pp, dev(o_probs), dev(wl.is_visual), dev(wl.cu_seqlens))
+    torch.cuda.synchronize()
+    new_cu = host(new_cu)
+    assert np.array_equal(new_cu, o_cu)
+    assert np.array_equal(host(kept)[:new_cu[-1]], o_kept)
+    if gamma > 0:
+        assert np.array_equal(host(mrg)[:new_cu[-1]], o_mrg)
+
+
 @pytest.mark.parametrize("alpha", [0.3, 0.6, 1.0])
 def test_prune_with_attention_importance(alpha):
     wl = W.small_random(112, T_v=[75, 31], T_t=[6, 5], d=64, E=24, F=32, k_text=4, k_visual=2,
