@@ -549,7 +549,7 @@ __device__ __forceinline__ f32x4_t read_acc() {
 // unconditionally -- past the end of the reduction they fetch the last step / tile again, into slots
 // nobody reads -- so the number of loads in flight at every wait is a compile-time constant and there
 // is no separate code for the last steps.
-// Per step and group of HB row blocks a wavefront issues HB LDS reads for 2*HB*DNCB matrix instructions.
+// Per step and pair of row blocks a wavefront issues 2 LDS reads for 4*DNCB matrix instructions.
 template <bool SWIGLU, int NAB>
 __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_tile& tile, int group, int nt4,
                                            int ct_limit, bf16_t* As) {
@@ -606,8 +606,11 @@ __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_ti
   const uint32_t frag_a0 = frag_row + (uint32_t)(((lane >> 4)) ^ ((lane & 15) >> 1)) * 16;
   const uint32_t frag_a1 = frag_row + (uint32_t)(((lane >> 4) + 4) ^ ((lane & 15) >> 1)) * 16;
 
-  constexpr int HB = (NRB > 4) ? NRB / 2 : NRB;   // row blocks whose operands are fetched together
-  constexpr int NH = NRB / HB;                    // such groups per k step
+  // Row blocks are taken two at a time: the operands of the next pair are requested from LDS before the
+  // matrix instructions of the current pair are issued and awaited after them, so that a wavefront meets
+  // the LDS latency once per k step instead of once per group.
+  constexpr int HB = 2;                           // row blocks per group
+  constexpr int NH = NRB / HB;                    // groups per k step (= NAB)
   constexpr int B_AHEAD = DB_SLOTS - 1, A_AHEAD = DA_STAGES - 1;
   constexpr int UNROLL = 2 * DA_STAGES;           // k steps per round: ring indices are compile-time
   static_assert(UNROLL % DB_SLOTS == 0, "ring indices must be static");
@@ -617,7 +620,7 @@ __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_ti
   constexpr int NEWER_EVEN = (B_AHEAD - 1) * 2 * DNCB + ((B_AHEAD - 1) / 2) * NAB;        // before an even step
   constexpr int NEWER_ODD = (B_AHEAD - 1) * 2 * DNCB + (B_AHEAD / 2) * NAB;               // before an odd step
 
-  u32x4_t fa[HB];
+  u32x4_t fa[2][HB];
   // k step `ks` = round base + U (U static): products of the step, loads of the steps further on
   auto kstep = [&](auto uc, int ks) {
     constexpr int U = decltype(uc)::value;
@@ -631,11 +634,14 @@ __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_ti
     } else {
       FMOE_WAIT_VM(NEWER_ODD);
     }
+    lds_issue_frags_at<HB, stage_off>(s ? frag_a1 : frag_a0, fa[0]);
+    lds_settle_frags<HB>(fa[0]);
     static_for<0, NH>([&](auto hc) {
       constexpr int h = decltype(hc)::value;
       constexpr int h0 = h * HB;
-      lds_issue_frags_at<HB, stage_off + h0 * 2048>(s ? frag_a1 : frag_a0, fa);
-      lds_settle_frags<HB>(fa);
+      constexpr int cur = h & 1, nxt = cur ^ 1;
+      if constexpr (h + 1 < NH)
+        lds_issue_frags_at<HB, stage_off + (h0 + HB) * 2048>(s ? frag_a1 : frag_a0, fa[nxt]);
 #pragma unroll
       for (int i = 0; i < NL; ++i) {           // load i of the step goes out with group i*NH/NL
         if ((i * NH) / NL != h) continue;
@@ -648,11 +654,12 @@ __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_ti
         const bf16x8_t fb1 = __builtin_bit_cast(bf16x8_t, breg[slot][j][1]);
         static_for<0, HB>([&](auto rc) {
           constexpr int rb = decltype(rc)::value;
-          const bf16x8_t a8 = __builtin_bit_cast(bf16x8_t, fa[rb]);
+          const bf16x8_t a8 = __builtin_bit_cast(bf16x8_t, fa[cur][rb]);
           mfma_at<(j * NRB + h0 + rb) * 2>(a8, fb0);
           mfma_at<(j * NRB + h0 + rb) * 2 + 1>(a8, fb1);
         });
       });
+      if constexpr (h + 1 < NH) lds_settle_frags<HB>(fa[nxt]);
     });
   };
 
