@@ -607,13 +607,16 @@ __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_ti
   const uint32_t frag_a1 = frag_row + (uint32_t)(((lane >> 4) + 4) ^ ((lane & 15) >> 1)) * 16;
 
   // Row blocks are taken two at a time: the operands of the next pair are requested from LDS before the
-  // matrix instructions of the current pair are issued and awaited after them, so that a wavefront meets
-  // the LDS latency once per k step instead of once per group.
-  constexpr int HB = 2;                           // row blocks per group
-  constexpr int NH = NRB / HB;                    // groups per k step (= NAB)
+  // matrix instructions of the current pair are issued and awaited after them -- also from the first step
+  // of a k tile into its second (same tile, no barrier between them) -- so that a wavefront meets the LDS
+  // latency once per k tile, behind the barrier that opens it.  Pair number U*NH + h (step U of the round,
+  // pair h) alternates between the two operand buffers.
+  constexpr int HB = 2;                           // row blocks per pair
+  constexpr int NH = NRB / HB;                    // pairs per k step (= NAB)
   constexpr int B_AHEAD = DB_SLOTS - 1, A_AHEAD = DA_STAGES - 1;
   constexpr int UNROLL = 2 * DA_STAGES;           // k steps per round: ring indices are compile-time
   static_assert(UNROLL % DB_SLOTS == 0, "ring indices must be static");
+  static_assert((UNROLL * NH) % 2 == 0, "operand buffers alternate consistently from round to round");
   static_assert(2 * A_AHEAD >= B_AHEAD, "a tile's activations are issued before its weights");
   // loads newer than the weights of the step about to run: those of the last B_AHEAD-1 steps, of which
   // every second one also carries a tile of activations
@@ -634,16 +637,19 @@ __device__ __forceinline__ void dense_tile(const StreamProblem& P, const fmoe_ti
     } else {
       FMOE_WAIT_VM(NEWER_ODD);
     }
-    lds_issue_frags_at<HB, stage_off>(s ? frag_a1 : frag_a0, fa[0]);
-    lds_settle_frags<HB>(fa[0]);
+    // (an odd step's first operands were requested by the step before)
+    if constexpr (s == 0) lds_issue_frags_at<HB, stage_off>(frag_a0, fa[(U * NH) & 1]);
+    lds_settle_frags<HB>(fa[(U * NH) & 1]);
     static_for<0, NH>([&](auto hc) {
       constexpr int h = decltype(hc)::value;
       constexpr int h0 = h * HB;
-      constexpr int cur = h & 1, nxt = cur ^ 1;
+      constexpr int cur = (U * NH + h) & 1, nxt = cur ^ 1;
       if constexpr (h + 1 < NH)
         lds_issue_frags_at<HB, stage_off + (h0 + HB) * 2048>(s ? frag_a1 : frag_a0, fa[nxt]);
+      else if constexpr (s == 0)
+        lds_issue_frags_at<HB, stage_off>(frag_a1, fa[nxt]);   // first pair of the tile's second step
 #pragma unroll
-      for (int i = 0; i < NL; ++i) {           // load i of the step goes out with group i*NH/NL
+      for (int i = 0; i < NL; ++i) {           // load i of the step goes out with pair i*NH/NL
         if ((i * NH) / NL != h) continue;
         if (s == 0 && i < NAB) loadA1(new_stage, (ks >> 1) + A_AHEAD, i);
         else loadB1(new_slot, ks + B_AHEAD, i - (s == 0 ? NAB : 0));
