@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(int n_cap, const int3
   if (e < E) {
     // SC blocks at a time: their counts are fetched together (independent loads), then turned into
     // bases -- one memory latency per SC blocks instead of one per block
-    constexpr int SC = 64;
+    constexpr int SC = 16;
     int running = 0;
     for (int b0 = 0; b0 < nblk; b0 += SC) {
       int c[SC];
