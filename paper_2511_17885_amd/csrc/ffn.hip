@@ -268,7 +268,9 @@ __device__ __forceinline__ void store_tile(const StreamProblem& P, const fmoe_ti
     const bf16_t* src = &As[row * CS + (tid % CPR) * 8];
     bf16_t* dst = P.C + (size_t)(tile.row0 + row) * P.ldc + col;
     if (vec_ok) {
-      *reinterpret_cast<u32x4_t*>(dst) = *reinterpret_cast<const u32x4_t*>(src);
+      // streaming store: the next kernel reads the tile, this one never does, and in L2 it would only
+      // displace the weights and activation tiles the other workgroups are sharing
+      __builtin_nontemporal_store(*reinterpret_cast<const u32x4_t*>(src), reinterpret_cast<u32x4_t*>(dst));
     } else {
       for (int i = 0; i < 8 && col + i < N; ++i) dst[i] = src[i];
     }
