@@ -46,10 +46,10 @@ GEMM1, GEMM2 = "gate_up_gemm", "down_gemm"   # work-table keys; the kernel that 
 # profiles/expert_gemm_hbm_traffic_c5_stack_c2_c3_c4.md.  The figures belong to the kernels as they
 # were when that file was written; a workload without an entry has not been measured (traffic: null).
 MEASURED_TRAFFIC_BYTES = {   # workload -> (the kernel the figure belongs to, bytes per launch)
-    "c5_stack": ("ffn_dense_kernel<true>", int((1502883.8 * 2.0 + 219765.3) * 1024)),
-    "c2": ("ffn_stream_kernel<true>", int((84361.8 * 2.0 + 7616.0) * 1024)),
-    "c3": ("ffn_dense_kernel<true>", int((483972.8 * 2.0 + 32032.0) * 1024)),
-    "c4": ("ffn_dense_kernel<true>", int((421758.6 * 2.0 + 26880.0) * 1024)),
+    "c5_stack": ("ffn_dense_kernel<true>", int((1492851.1 * 2.0 + 219765.4) * 1024)),
+    "c2": ("ffn_stream_kernel<true>", int((84300.2 * 2.0 + 7616.0) * 1024)),
+    "c3": ("ffn_dense_kernel<true>", int((483120.4 * 2.0 + 32032.0) * 1024)),
+    "c4": ("ffn_dense_kernel<true>", int((420595.5 * 2.0 + 26880.0) * 1024)),
 }
 
 
