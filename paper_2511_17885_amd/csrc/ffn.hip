@@ -45,6 +45,11 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // one 16-byte c
 __device__ __forceinline__ float silu_mul(float g, float u) {
   return g * __frcp_rn(1.0f + __expf(-g)) * u;
 }
+// The same for values that are rounded to bf16 next: the hardware reciprocal (1 ulp of fp32) instead of
+// the correctly rounded one, a third of the instructions (1.7 % of the gate/up kernel at 2064 rows per expert).
+__device__ __forceinline__ float silu_mul_bf16(float g, float u) {
+  return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
+}
 
 // ======================================================================== bf16: weight-stream kernel
 constexpr int SBM = 128;        // rows per tile: 8 MFMA row blocks of 16
@@ -248,7 +253,7 @@ __device__ __forceinline__ void store_tile(const StreamProblem& P, const fmoe_ti
     for (int v = 0; v < 4; ++v) {
       const int row = rb * 16 + 4 * (lane >> 4) + v;
       if (SWIGLU) {
-        As[row * CS + wave * 16 + (lane & 15)] = f32_to_bf16(silu_mul(c0[v], c1[v]));
+        As[row * CS + wave * 16 + (lane & 15)] = f32_to_bf16(silu_mul_bf16(c0[v], c1[v]));
       } else {
         As[row * CS + wave * 32 + (lane & 15)] = f32_to_bf16(c0[v]);
         As[row * CS + wave * 32 + 16 + (lane & 15)] = f32_to_bf16(c1[v]);
