@@ -346,14 +346,19 @@ __global__ __launch_bounds__(256) void route_kernel(
     for (int s = 32; s >= 1; s >>= 1)
   #pragma unroll
       for (int tq = 0; tq < TQ; ++tq) part[tq] = part[tq] + __shfl_xor(part[tq], s, 64);
+    // Inside the fused layer (the launch that also carries the ordinal blocks) the probabilities only feed
+    // the window scores, which read visual tokens: text rows are not written.
+    const bool visual_rows_only = ord.cu != nullptr;
   #pragma unroll
-    for (int tq = 0; tq < TQ; ++tq)
+    for (int tq = 0; tq < TQ; ++tq) {
+      const bool store_row = probs != nullptr && tv[tq] && (!visual_rows_only || is_visual[tt[tq]] != 0);
   #pragma unroll
       for (int i = 0; i < NB; ++i) {
         const int e = lane + 64 * i;
         P[tq][i] = (e < E) ? P[tq][i] / part[tq] : -1.0f;   // -1 ranks below every probability
-        if (probs != nullptr && tv[tq] && e < E) probs[(size_t)tt[tq] * E + e] = P[tq][i];
+        if (store_row && e < E) probs[(size_t)tt[tq] * E + e] = P[tq][i];
       }
+    }
 
     // Top-k as k rounds of "take the largest remaining probability" (ties: lowest expert index), which
     // yields the list in the order (probability desc, index asc) directly.  The maximum over the
