@@ -777,6 +777,55 @@ def test_stack_ragged_12_layers_fp32():
     assert out.shape[0] == binding.kept_count(nv, nt, wl.retention) == ref.shape[0] == kept.shape[0]
 
 
+def test_stack_stages_take_their_attention_importance():
+    """fmoe_stack_forward hands attn[l] (Eq.7, one vector per stage, sized for the tokens that reach the
+    stage) to the stage of layer l: with alpha < 1 the stack must equal the chained single-layer calls
+    bit for bit, differ from the stack run without attention, and the first stage must keep the
+    oracle's set."""
+    wl = W.config5(n_layers=6, d=128, E=64, F=64, len_div=32, text_len=96, dtype=W.F32)
+    layers = _gpu_layers(wl)
+    sched = binding.stage_schedule(0.5, [1, 3], window=3, alpha=0.5)
+    nv, nt = _lens(wl)
+    T1 = wl.T
+    T2 = binding.kept_count(nv, nt, sched[1].retention)
+    rng = np.random.default_rng(31)
+    attn = {1: dev(rng.random(T1).astype(np.float32) ** 2), 3: dev(rng.random(T2).astype(np.float32) ** 2)}
+    stack = binding.FMoEStack(layers, wl.k_schedule, prune_schedule=sched)
+    x, vis, cu = inputs(wl)
+    out, kept, new_cu = stack.forward(x, vis, cu, nv, nt, attn=attn)
+    out0, kept0, _ = stack.forward(x, vis, cu, nv, nt)
+    torch.cuda.synchronize()
+    # the same stack as chained calls with the same attention vectors
+    xc, visc, cuc = x, vis, cu
+    kept_total = None
+    for l, m in enumerate(layers):
+        m.set_topk(*wl.k_schedule[l])
+        pp = sched.get(l)
+        o, k, ncu, vout = m.layer_forward(xc, visc, cuc, pp, attn=attn.get(l), add_residual=True, want_mask=pp is not None)
+        if pp is not None:
+            n = int(host(ncu)[-1])
+            assert n == (T2 if l == 1 else out.shape[0])
+            kept_total = k[:n].clone() if kept_total is None else kept_total[k[:n].long()]
+            xc, visc, cuc = o[:n].clone(), vout[:n].clone(), ncu.clone()
+        else:
+            xc = o[:xc.shape[0]].clone()
+    assert torch.equal(out, xc) and torch.equal(kept, kept_total) and torch.equal(new_cu, cuc)
+    assert not torch.equal(kept, kept0)                       # the attention term changed the kept set
+    # first stage against the oracle (layer 0 without pruning, then layer 1 with the attention term)
+    lw0, lw1 = wl.layers[0], wl.layers[1]
+    o0 = oracle.layer_forward(wl.x, wl.is_visual, wl.cu_seqlens, lw0, k_text=wl.k_schedule[0][0],
+                              k_visual=wl.k_schedule[0][1], is_bf16=False, add_residual=True, do_prune=False,
+                              retention=1.0, window=3)
+    m1 = layers[1]
+    m1.set_topk(*wl.k_schedule[1])
+    _, k1, ncu1, _ = m1.layer_forward(dev(o0["out"]), vis, cu, sched[1], attn=attn[1], add_residual=True)
+    o1 = oracle.layer_forward(o0["out"], wl.is_visual, wl.cu_seqlens, lw1, k_text=wl.k_schedule[1][0],
+                              k_visual=wl.k_schedule[1][1], is_bf16=False, add_residual=True, do_prune=True,
+                              retention=sched[1].retention, window=3, alpha=0.5, attn=host(attn[1]))
+    n1 = int(host(ncu1)[-1])
+    assert np.array_equal(host(ncu1), o1["new_cu_seqlens"]) and np.array_equal(host(k1)[:n1], o1["kept_idx"])
+
+
 def test_stack_without_stages_returns_the_identity_index_list():
     wl = W.config5(n_layers=2, d=64, E=16, F=32, len_div=64, text_len=64, dtype=W.F32)
     layers = _gpu_layers(wl)
