@@ -414,10 +414,11 @@ class FMoEStack:
         return int(load().fmoe_stack_workspace_bytes(self._ctxs, self.plan, len(self.layers), max_tokens, max_seqs))
 
     def forward(self, x, is_visual, cu_seqlens, visual_lens, text_lens, attn=None, out=None, kept_idx=None,
-                new_cu=None):
+                new_cu=None, want_mask=False):
         """visual_lens / text_lens: per-sequence token counts on the host.  attn: {layer: importance
         [T at that layer]} for stages that use the attention term.  Returns (x_out [T', d], kept_idx
-        [T'] indices into the input batch, new_cu_seqlens)."""
+        [T'] indices into the input batch, new_cu_seqlens), with want_mask also the modality mask of the
+        output rows."""
         m0 = self.layers[0]
         T, B, n = x.shape[0], cu_seqlens.shape[0] - 1, len(self.layers)
         need = self.workspace_bytes(T, B)
@@ -436,9 +437,12 @@ class FMoEStack:
             attn_ptrs = (C.c_void_p * n)(*[attn[l].data_ptr() if attn.get(l) is not None else None
                                            for l in range(n)])
         n_out = C.c_int32()
+        vis_out = torch.empty(max(T, 1), dtype=torch.uint8, device=m0.device) if want_mask else None
         _check(load().fmoe_stack_forward(self._ctxs, self.plan, n, _ptr(x), _ptr(is_visual), _ptr(cu_seqlens),
-                                         nv, nt, B, T, attn_ptrs, _ptr(out), _ptr(kept_idx), _ptr(new_cu), None,
-                                         C.byref(n_out), _ptr(self._ws), self._ws.numel(), _stream()))
+                                         nv, nt, B, T, attn_ptrs, _ptr(out), _ptr(kept_idx), _ptr(new_cu),
+                                         _ptr(vis_out), C.byref(n_out), _ptr(self._ws), self._ws.numel(), _stream()))
         for l, m in enumerate(self.layers):   # the contexts' top-k now is the last layer's plan
             m.cfg.k_text, m.cfg.k_visual = self.plan[l].k_text, self.plan[l].k_visual
+        if want_mask:
+            return out[:n_out.value], kept_idx[:n_out.value], new_cu, vis_out[:n_out.value]
         return out[:n_out.value], kept_idx[:n_out.value], new_cu

@@ -811,6 +811,12 @@ def test_stack_stages_take_their_attention_importance():
             xc = o[:xc.shape[0]].clone()
     assert torch.equal(out, xc) and torch.equal(kept, kept_total) and torch.equal(new_cu, cuc)
     assert not torch.equal(kept, kept0)                       # the attention term changed the kept set
+    # the stack's modality mask of its output rows (with and without stages)
+    _, kept_m, _, mask = stack.forward(x, vis, cu, nv, nt, attn=attn, want_mask=True)
+    assert torch.equal(kept_m, kept) and np.array_equal(host(mask), wl.is_visual[host(kept)])
+    plain = binding.FMoEStack(layers[:2], wl.k_schedule[:2], prune_schedule={})
+    _, kept_p, _, mask_p = plain.forward(x, vis, cu, nv, nt, want_mask=True)
+    assert np.array_equal(host(kept_p), np.arange(wl.T)) and np.array_equal(host(mask_p), wl.is_visual)
     # first stage against the oracle (layer 0 without pruning, then layer 1 with the attention term)
     lw0, lw1 = wl.layers[0], wl.layers[1]
     o0 = oracle.layer_forward(wl.x, wl.is_visual, wl.cu_seqlens, lw0, k_text=wl.k_schedule[0][0],
