@@ -191,6 +191,43 @@ def test_prune_over_several_compaction_blocks(T_v, T_t, gamma):
         assert np.array_equal(host(mrg)[:new_cu[-1]], o_mrg)
 
 
+@pytest.mark.parametrize("window,gamma", [(3, 0.0), (5, 0.0), (2, 0.25)])
+def test_prune_many_short_sequences(window, gamma):
+    """Several hundred sequences of zero to a dozen tokens, some without a visual token, some empty: every
+    sequence owns its own window slots and window units, sequence bounds are found by binary search, and the
+    compaction blocks cut through many sequences; kept set, scores and bounds bit for bit."""
+    rng = np.random.default_rng(404)
+    n_seq = 700
+    T_v = [int(v) for v in rng.choice([0, 0, 1, 2, 3, 4, 5, 7, 11], size=n_seq)]
+    T_t = [int(v) for v in rng.choice([0, 0, 1, 2], size=n_seq)]
+    wl = W.small_random(405, T_v=T_v, T_t=T_t, d=32, E=12, F=16, k_text=3, k_visual=2, retention=0.5, window=window,
+                        n_components=5, bias_std=1.0, interleave=True)
+    assert wl.B == n_seq and wl.T > 2048
+    o_probs, _, _ = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias, 3, 2)
+    res = oracle.prune(o_probs, wl.is_visual, wl.cu_seqlens, wl.retention, window, gamma=gamma,
+                       x=wl.x if gamma > 0 else None)
+    m = make_layer(wl)
+    pp = binding.prune_params(retention=wl.retention, window=window, gamma=gamma)
+    if gamma > 0:
+        kept, new_cu, scores, mrg, _ = m.prune(pp, dev(o_probs), dev(wl.is_visual), dev(wl.cu_seqlens), x=dev(wl.x),
+                                               want_scores=True)
+    else:
+        kept, new_cu, scores = m.prune(pp, dev(o_probs), dev(wl.is_visual), dev(wl.cu_seqlens), want_scores=True)
+    torch.cuda.synchronize()
+    new_cu = host(new_cu)
+    assert np.array_equal(new_cu, res[1])
+    assert np.array_equal(host(kept)[:new_cu[-1]], res[0])
+    if gamma > 0:
+        assert np.array_equal(host(mrg)[:new_cu[-1]], res[3])
+    scores = host(scores)
+    got = []
+    for b in range(wl.B):
+        s0, e0 = wl.cu_seqlens[b], wl.cu_seqlens[b + 1]
+        nv = int(wl.is_visual[s0:e0].sum())
+        got.append(scores[s0:s0 + (nv + window - 1) // window])
+    assert np.array_equal(np.concatenate(got), res[2])
+
+
 @pytest.mark.parametrize("alpha", [0.3, 0.6, 1.0])
 def test_prune_with_attention_importance(alpha):
     wl = W.small_random(112, T_v=[75, 31], T_t=[6, 5], d=64, E=24, F=32, k_text=4, k_visual=2,
