@@ -1180,6 +1180,31 @@ def test_layer_forward_at_the_small_batch_limits(T_v, T_t, window):
     assert max_rel_err(host(out)[:n], o["out_f64"]) <= TOL[wl.dtype]
 
 
+def test_layer_forward_general_chain_over_many_sequences():
+    """More than 4096 tokens in 1500 sequences of a few tokens each (empty ones among them): the fused layer
+    takes the general kernel chain, the router's launch carries one ordinal block per sequence, and every
+    window-indexed array is cut into 1500 pieces; kept set, bounds, mask and outputs against the oracle."""
+    rng = np.random.default_rng(77)
+    n_seq = 1500
+    T_v = [int(v) for v in rng.choice([0, 1, 2, 3, 4, 6, 9], size=n_seq)]
+    T_t = [int(v) for v in rng.choice([0, 0, 1, 2], size=n_seq)]
+    wl = W.small_random(515, T_v=T_v, T_t=T_t, d=64, E=16, F=32, k_text=3, k_visual=2, retention=0.55, window=3,
+                        dtype=W.F32, n_components=6, bias_std=1.0, interleave=True)
+    assert wl.T > 4096 and wl.B == n_seq
+    o = _oracle(wl, add_residual=True)
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    out, kept, new_cu, vis_out = m.layer_forward(x, vis, cu, binding.prune_params(retention=wl.retention, window=3),
+                                                 add_residual=True, want_mask=True)
+    torch.cuda.synchronize()
+    new_cu = host(new_cu)
+    n = int(new_cu[-1])
+    assert np.array_equal(new_cu, o["new_cu_seqlens"])
+    assert np.array_equal(host(kept)[:n], o["kept_idx"])
+    assert np.array_equal(host(vis_out)[:n], wl.is_visual[o["kept_idx"]])
+    assert_residual_outputs_close(host(out)[:n], o["out_f64"], _x_rows(wl, o), wl.dtype, "1500 sequences")
+
+
 @pytest.mark.parametrize("shape", SHAPES)
 def test_layer_forward_general_chain_at_the_widest_routing(shape):
     """The largest expert count and top-k the library takes (256 experts, 16 per text token), shared experts,
