@@ -12,13 +12,9 @@
 #define FMOE_MAX_WINDOW 64
 #define FMOE_PERM_BLOCK 256   // kept positions per block in the permutation kernels
 #define FMOE_TILE_M 64        // rows per grouped-GEMM tile (tile list granularity)
-#ifndef FMOE_TILE_RUN
 #define FMOE_TILE_RUN 8       // row tiles per run of a group in the tile lists
-#endif
 #define FMOE_SEG_MIN_TILES 256   // tile entries from which each XCD takes a contiguous segment of the list
-#ifndef FMOE_ROUTE_TT2_MIN_TOKENS
 #define FMOE_ROUTE_TT2_MIN_TOKENS 16384  // tokens from which a router block takes two tiles of 16 tokens
-#endif
 #define FMOE_DENSE_MIN_ROWS 256  // routed-row capacity per expert from which the expert GEMMs take their dense shape
 
 // ---- optional per-kernel timing (instrumentation; off by default)
