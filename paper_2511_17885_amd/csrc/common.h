@@ -15,6 +15,7 @@
 #define FMOE_TILE_RUN 8       // row tiles per run of a group in the tile lists
 #define FMOE_SEG_MIN_TILES 256   // tile entries from which each XCD takes a contiguous segment of the list
 #define FMOE_ROUTE_TT2_MIN_TOKENS 16384  // tokens from which a router block takes two tiles of 16 tokens
+#define FMOE_ROUTE_SHALLOW_MIN_TOKENS 4096  // tokens from which the router keeps two instead of four chunks in flight
 #define FMOE_DENSE_MIN_ROWS 256  // routed-row capacity per expert from which the expert GEMMs take their dense shape
 
 // ---- optional per-kernel timing (instrumentation; off by default)
