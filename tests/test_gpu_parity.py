@@ -73,6 +73,28 @@ def test_route(seed, kw):
     assert np.abs(host(gate) - o_gate).max() <= 1e-6
 
 
+@pytest.mark.parametrize("dtype,d,E,T_v,T_t", [
+    (W.F32, 512, 24, [4100], [37]),        # fp32, four chunks of 128: the shallow operand pipeline from 4096 tokens on
+    (W.BF16, 1280, 64, [3000, 1200], [50, 13]),   # bf16, ten chunks (five in flight below 4096 tokens)
+    (W.BF16, 640, 40, [4095], [0]),        # five chunks: an odd count, one token below the switch
+    (W.BF16, 640, 40, [4096], [3]),        # ... and above it (the chunk count is rounded up to an even one)
+    (W.F32, 384, 16, [16500], [20]),       # three chunks, two token tiles per block
+])
+def test_route_large_batches(dtype, d, E, T_v, T_t):
+    """The router's launch shapes for large batches (operand pipeline two chunks deep from 4096 tokens on,
+    two token tiles per block from 16384): probabilities and expert lists bit for bit, gates to 1e-6."""
+    wl = W.small_random(620 + d, T_v=T_v, T_t=T_t, d=d, E=E, F=16, k_text=4, k_visual=2, retention=0.5, window=3,
+                        dtype=dtype, bias_std=1.0, n_components=12)
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    probs, idx, gate = m.route(x, vis)
+    torch.cuda.synchronize()
+    o_probs, o_idx, o_gate = oracle.route(wl.x, wl.is_visual, wl.weights.router_w, wl.weights.router_bias, 4, 2)
+    assert np.array_equal(host(idx), o_idx)
+    assert np.array_equal(host(probs), o_probs)
+    assert np.abs(host(gate) - o_gate).max() <= 1e-6
+
+
 def test_route_ties_duplicated_router_rows():
     wl = W.small_random(110, T_v=[20], T_t=[12], d=64, E=10, F=32, k_text=10, k_visual=4,
                         retention=0.5, window=3)
