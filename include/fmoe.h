@@ -69,7 +69,9 @@ typedef struct {
   float alpha;        /* weight of routing similarity in the redundancy score (Eq.13)      */
   float gamma;        /* merge rate in [0,1) (Eq.14): at most floor(eta*gamma) windows merged; 0 = off */
   int32_t sim_mode;   /* 0: similarity to the window mean (Eq.9-10); 1: all pairs (Eq.8)   */
-  int32_t prune_mode; /* 0: none; 1 or 2: prune between routing and the experts            */
+  int32_t prune_mode; /* 0: none; 1: before the experts; 2: after the layer.  Without merging the two give
+                         the same result (see fmoe_layer_forward); with gamma > 0 mode 1 merges the
+                         layer input, mode 2 the layer output                                      */
   int32_t merge_mode; /* merged token: 0 = MLERP (Eq.16-18: mean rescaled to the largest token norm),
                          1 = plain mean (the alternative of the merge-method ablation, Sec. 4)  */
 } fmoe_prune_params;
@@ -250,9 +252,12 @@ int fmoe_combine(fmoe_ctx* ctx, const void* y, const void* y_shared, const int32
  * Because an MoE layer acts on every token independently, dropping a token before the experts
  * gives the kept tokens the same outputs as dropping it after the layer; both prune modes
  * therefore run the experts on the kept tokens only.
- * Window merging (params->gamma > 0; prune_mode 1 only, FMOE_ERR_UNSUPPORTED otherwise): the rows of
- * x are merged (fmoe_prune's x_merged), every kept token is routed again on the merged input, the
- * experts run on it and add_residual adds the merged rows.
+ * Window merging (params->gamma > 0) is where the two modes differ.  prune_mode 1: the rows of x are
+ * merged (fmoe_prune's x_merged), every kept token is routed again on the merged input, the experts
+ * run on it and add_residual adds the merged rows.  prune_mode 2: the layer runs on all T tokens, the
+ * windows are scored on this layer's probabilities and the OUTPUT rows are compacted, a merged window
+ * replaced by the merged row of its tokens' outputs (Eq.16-18 on the layer output, residual included
+ * when add_residual != 0).
  * bf16: x (T*H*2 bytes) and the hidden buffers (T*Kmax*S_m*2, T*N_s*S_s*2 bytes) must each stay
  * below 4 GiB, else FMOE_ERR_UNSUPPORTED (32-bit row offsets in the expert GEMMs).  T > 0 with
  * B == 0 is FMOE_ERR_INVALID_ARG. */

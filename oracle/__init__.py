@@ -294,10 +294,15 @@ def token_outputs(x, tokens, topk_idx, topk_gate, w, is_bf16, add_residual=False
 def layer_forward(x, is_visual, cu_seqlens, w, *, k_text, k_visual, is_bf16, retention=1.0,
                   window=1, alpha=1.0, gamma=0.0, sim_mode=0, attn=None, add_residual=False,
                   renormalize=True, do_prune=True, ffn=True, merge_mean=False, strategy=TOPK, k_base=0,
-                  seed=0):
+                  seed=0, after_layer=False):
     """The whole path: route -> prune -> permute -> experts -> combine (the steps chained, nothing
     else).  Returns a dict with every intermediate.  strategy / k_base / seed: the selection-strategy
-    ablation (route_select); merge_mean: plain mean instead of MLERP for merged tokens."""
+    ablation (route_select); merge_mean: plain mean instead of MLERP for merged tokens.
+    after_layer: pruning acts on the layer's output instead of its input.  Without merging that is the
+    same thing (a token's output does not depend on the other tokens); with gamma > 0 the layer runs on
+    every token and Sec. 3.2.3 (Eq.14-18) is applied to the output rows: "out" then holds the compacted
+    rows with merged windows replaced by their merged output row, "out_full" / "out_full_f64" the
+    layer's output before compaction."""
     T = x.shape[0]
     E = w.router_w.shape[0]
     d = x.shape[1]
@@ -309,6 +314,19 @@ def layer_forward(x, is_visual, cu_seqlens, w, *, k_text, k_visual, is_bf16, ret
                             renormalize)
 
     probs, idx, gate = _route(x, is_visual)
+    if do_prune and retention < 1.0 and gamma > 0.0 and after_layer:
+        every = np.arange(T, dtype=np.int32)
+        offs, perm, inv = permute(idx, every, E)
+        y = expert_ffn(x, every, offs, perm, w.w_gate, w.w_up, w.w_down, is_bf16)
+        ysh = None
+        if w.ws_gate is not None:
+            ysh = shared_ffn(x, every, T, w.ws_gate, w.ws_up, w.ws_down, is_bf16)
+        full, full64 = combine(y, ysh, inv, gate, every, d, x if add_residual else None, is_bf16)
+        kept, new_cu, scores, is_merged, out_m = prune(probs, is_visual, cu_seqlens, retention, window,
+                                                       alpha, gamma, sim_mode, attn, x=full, is_bf16=is_bf16,
+                                                       merge_mean=merge_mean)
+        return dict(probs=probs, topk_idx=idx, topk_gate=gate, kept_idx=kept, new_cu_seqlens=new_cu,
+                    scores=scores, is_merged=is_merged, out=out_m, out_full=full, out_full_f64=full64)
     if do_prune and retention < 1.0 and gamma > 0.0:
         # window merging changes the layer input: the kept rows are gathered (merged windows replaced by
         # their merged token), every kept token is routed again on that tensor (only the merged ones can

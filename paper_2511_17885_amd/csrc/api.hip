@@ -400,9 +400,7 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
   void* y_shared = ctx->cfg.n_shared > 0 ? base + L.y_shared : nullptr;
 
   const bool merging = do_prune && params->gamma > 0.0f;
-  if (merging && params->prune_mode != 1)
-    return fmoe_fail(FMOE_ERR_UNSUPPORTED, "fmoe_layer_forward: window merging (gamma > 0) is built for prune_mode 1 "
-                     "(merge the layer input, route the kept tokens again)");
+  const bool merge_after = merging && params->prune_mode == 2;
   const bool small = !merging && T > 0 && dispatch_small_fits(T, do_prune ? params->window : 1, do_prune);
   // with merging the pruning decisions take the general kernels, but a small batch still gets its
   // permutation and tile lists from the single-workgroup kernel
@@ -431,6 +429,24 @@ int fmoe_layer_forward(fmoe_ctx* ctx, const fmoe_prune_params* params, const voi
       return rc;
     return launch_combine(ctx, y, y_shared, inv_perm, topk_gate, kept, T, n_dev, add_residual ? x : nullptr,
                           out, s);
+  }
+  if (merge_after) {
+    // Window merging after the layer (Sec. 3.2.3 applied to the layer's output, the tensor that is
+    // compacted here): a merged token is built from the output rows of all tokens of its window, so
+    // the experts run on every token; the windows are then scored on this layer's probabilities and
+    // the output rows are compacted, merged windows replaced by their merged row (Eq.16-18).
+    if (T == 0)
+      return launch_identity_kept(is_visual, cu_seqlens, B, T, kept_idx, new_cu_seqlens, is_visual_out, s);
+    void* full = base + L.x_merged;   // [T,d]: the layer's output before compaction
+    if ((rc = launch_permute(ctx, topk_idx, nullptr, T, nullptr, expert_offsets, perm_src, inv_perm, ws, L, true, s)) != FMOE_OK)
+      return rc;
+    if ((rc = launch_expert_ffn(ctx, x, nullptr, T, nullptr, expert_offsets, perm_src, y, y_shared, ws, L, true, s)) != FMOE_OK)
+      return rc;
+    if ((rc = launch_combine(ctx, y, y_shared, inv_perm, topk_gate, nullptr, T, nullptr, add_residual ? x : nullptr,
+                             full, s)) != FMOE_OK)
+      return rc;
+    return launch_prune(ctx, params, probs, is_visual, cu_seqlens, B, T, attn_importance, kept_idx,
+                        new_cu_seqlens, nullptr, is_visual_out, full, out, nullptr, ws, L, s, true);
   }
   if (merging) {
     // Window merging changes the layer input: the kept rows are gathered into a compact tensor (merged

@@ -9,8 +9,8 @@ import torch
 import oracle
 from paper_2511_17885_amd import binding
 from paper_2511_17885_amd import workloads as W
-from harness import (TOL, assert_outputs_close, assert_residual_outputs_close, dev, host, inputs, make_layer,
-                     max_rel_err, torch_dtype)
+from harness import (HALF_ULP, TOL, assert_outputs_close, assert_residual_outputs_close, dev, host, inputs,
+                     make_layer, max_rel_err, torch_dtype)
 
 pytestmark = pytest.mark.gpu
 
@@ -511,12 +511,56 @@ def test_layer_forward_merge(seed, kw):
             assert_outputs_close(host(out2)[:n], _oracle(wl, gamma=gamma)["out_f64"], wl.dtype, f"gamma {gamma}")
 
 
-def test_layer_forward_merge_rejects_router_only_mode():
-    wl = _wl(100, SMALL[0].values[1])
+def _check_after_layer_rows(got, o, x_all, dtype, what):
+    """Output rows of a layer that merges after the layer (oracle record `o` of after_layer=True; x_all:
+    the layer input when the residual was added, else None).  Ordinary kept rows: the un-pruned layer's
+    rows at the dtype's tolerance.  Merged rows: each side merges its own stored output rows (which
+    differ by the GEMM's rounding) with one rounding of an fp64 result at the end, and the rescaling to
+    the largest row norm can stretch a difference by the ratio of that norm to the mean's."""
+    k = o["kept_idx"]
+    plain = o["is_merged"] == 0
+    ref64 = o["out_full_f64"]
+    if x_all is not None:
+        assert_residual_outputs_close(got[plain], ref64[k[plain]], x_all[k[plain]], dtype, what)
+        scale = np.abs(ref64 - x_all).max()
+    else:
+        assert_outputs_close(got[plain], ref64[k[plain]], dtype, what)
+        scale = np.abs(ref64).max()
+    if (~plain).any():
+        g = got[~plain].astype(np.float64)
+        r = o["out"][~plain].astype(np.float64)
+        bound = 4 * TOL[dtype] * scale + 4 * HALF_ULP[dtype] * np.maximum(np.abs(g), np.abs(r))
+        assert (np.abs(g - r) <= bound).all(), (what, float(np.abs(g - r).max()), float(scale))
+
+
+@pytest.mark.parametrize("seed,kw", SMALL)
+def test_layer_forward_merge_after_the_layer(seed, kw):
+    """Sec. 3.2.3 applied to the layer's output (prune_mode 2 with gamma > 0): the experts run on every
+    token, the windows are scored on this layer's probabilities, and the output rows are compacted with
+    merged windows replaced by the merged row of their tokens' outputs (Eq.16-18)."""
+    wl = _wl(seed, kw)
     m = make_layer(wl)
     x, vis, cu = inputs(wl)
-    with pytest.raises(RuntimeError):
-        m.layer_forward(x, vis, cu, binding.prune_params(retention=0.5, window=3, gamma=0.1, prune_mode=2))
+    for residual in (True, False):
+        full_gpu = host(m.layer_forward(x, vis, cu, None, add_residual=residual)[0]).copy()
+        for gamma in _merge_gammas(wl)[-2:]:
+            o = _oracle(wl, add_residual=residual, gamma=gamma, after_layer=True)
+            pp = binding.prune_params(retention=wl.retention, window=wl.window, gamma=gamma, prune_mode=2)
+            out, kept, new_cu, vis_out = m.layer_forward(x, vis, cu, pp, add_residual=residual, want_mask=True)
+            torch.cuda.synchronize()
+            new_cu = host(new_cu)
+            n = int(new_cu[-1])
+            what = f"gamma {gamma} residual {residual}"
+            assert np.array_equal(new_cu, o["new_cu_seqlens"]), what
+            assert np.array_equal(host(kept)[:n], o["kept_idx"]), what
+            assert np.array_equal(host(vis_out)[:n], wl.is_visual[o["kept_idx"]]), what
+            if not n:
+                continue
+            got = host(out)[:n]
+            k = o["kept_idx"]
+            # an ordinary kept row is the un-pruned layer's row, bit for bit on the GPU
+            assert np.array_equal(got[o["is_merged"] == 0], full_gpu[k[o["is_merged"] == 0]]), what
+            _check_after_layer_rows(got, o, wl.x if residual else None, wl.dtype, what)
 
 
 @pytest.mark.parametrize("dtype", [W.F32, W.BF16])
@@ -532,7 +576,8 @@ def test_empty_batch(dtype, B):
     vis0 = torch.empty(0, dtype=torch.uint8, device="cuda")
     cu0 = torch.zeros(B + 1, dtype=torch.int32, device="cuda")
     for pp in (None, binding.prune_params(retention=0.5, window=3),
-               binding.prune_params(retention=0.5, window=3, gamma=0.1)):
+               binding.prune_params(retention=0.5, window=3, gamma=0.1),
+               binding.prune_params(retention=0.5, window=3, gamma=0.1, prune_mode=2)):
         new_cu = torch.full((B + 1,), 7, dtype=torch.int32, device="cuda")
         m.layer_forward(x0, vis0, cu0, pp, new_cu=new_cu)
         torch.cuda.synchronize()
@@ -772,8 +817,9 @@ def _teacher_forced(wl, layers, records, only=None):
         m.set_topk(kt, kv)
         pp = None
         if st is not None:
+            after = st.get("after_layer", False) or not st.get("gamma", 0.0) > 0
             pp = binding.prune_params(retention=st["retention"], window=st["window"], alpha=st.get("alpha", 1.0),
-                                      gamma=st.get("gamma", 0.0), prune_mode=1 if st.get("gamma", 0.0) > 0 else 2)
+                                      gamma=st.get("gamma", 0.0), prune_mode=2 if after else 1)
         out, kept, new_cu, _ = m.layer_forward(x, vis, cu, pp, add_residual=True)
         torch.cuda.synchronize()
         o = r["o"]
@@ -784,7 +830,10 @@ def _teacher_forced(wl, layers, records, only=None):
         _, idx, gate = m.route(x, vis, want_probs=False)
         if "x_merged" not in o:                       # (with merging the list is that of the merged input)
             assert np.array_equal(host(idx), o["topk_idx"]), l
-        assert_residual_outputs_close(host(out)[:n], o["out_f64"], _x_rows_of(r), wl.dtype, f"layer {l}")
+        if "out_full_f64" in o:                       # merging after the layer
+            _check_after_layer_rows(host(out)[:n], o, r["x"], wl.dtype, f"layer {l}")
+        else:
+            assert_residual_outputs_close(host(out)[:n], o["out_f64"], _x_rows_of(r), wl.dtype, f"layer {l}")
 
 
 def _x_rows_of(r):
@@ -792,14 +841,16 @@ def _x_rows_of(r):
     return o["x_merged"] if "x_merged" in o else r["x"][o["kept_idx"]]
 
 
-@pytest.mark.parametrize("gamma", [0.0, 0.05])
-def test_stack_three_stage_schedule_fp32(gamma):
+@pytest.mark.parametrize("gamma,prune_mode", [(0.0, 1), (0.05, 1), (0.05, 2)])
+def test_stack_three_stage_schedule_fp32(gamma, prune_mode):
     # App. D: r = 0.5 reached in three stages of beta = r^(1/3) after layers 2, 5, 8 (the DeepSeek-VL2
-    # setting of App. A: W = 3, gamma = 0.05), reduced top-k from layer 2 on
+    # setting of App. A: W = 3, gamma = 0.05), reduced top-k from layer 2 on; merging on the layer input
+    # (mode 1) or on the layer output (mode 2)
     wl = W.config5(n_layers=10, d=128, E=64, F=64, len_div=32, text_len=128, dtype=W.F32)
-    sched = binding.stage_schedule(0.5, [2, 5, 8], window=3, gamma=gamma)
+    sched = binding.stage_schedule(0.5, [2, 5, 8], window=3, gamma=gamma, prune_mode=prune_mode)
     assert abs(sched[2].retention ** 3 - 0.5) < 1e-6
-    o_sched = {l: dict(retention=p.retention, window=p.window, alpha=p.alpha, gamma=p.gamma)
+    o_sched = {l: dict(retention=p.retention, window=p.window, alpha=p.alpha, gamma=p.gamma,
+                       after_layer=prune_mode == 2)
                for l, p in sched.items()}
     layers = _gpu_layers(wl)
     ref, ref_kept, ref_cu, records = _oracle_stack(wl, o_sched)
@@ -1225,6 +1276,37 @@ def test_layer_forward_general_chain_over_many_sequences():
     assert np.array_equal(host(kept)[:n], o["kept_idx"])
     assert np.array_equal(host(vis_out)[:n], wl.is_visual[o["kept_idx"]])
     assert_residual_outputs_close(host(out)[:n], o["out_f64"], _x_rows(wl, o), wl.dtype, "1500 sequences")
+
+
+@pytest.mark.parametrize("with_attention", [False, True])
+def test_layer_forward_merge_after_the_layer_over_several_compaction_blocks(with_attention):
+    """Merging on the layer output at a size where the experts run in several row tiles per expert, the
+    compaction in several blocks and the merge order (redundancy) differs from the drop order (attention
+    first): decisions bit for bit, ordinary and merged rows against the oracle."""
+    wl = W.small_random(616, T_v=[2200, 3, 1500, 900], T_t=[30, 2, 0, 50], d=128, E=32, F=64, k_text=4, k_visual=2,
+                        retention=0.5, window=3, dtype=W.BF16, n_shared=1, F_shared=32, bias_std=1.0,
+                        n_components=24)
+    assert wl.T > 4096
+    attn = None
+    if with_attention:
+        attn = np.random.default_rng(6).random(wl.T).astype(np.float32)
+    gamma = 0.1
+    o = _oracle(wl, add_residual=True, gamma=gamma, alpha=0.6 if with_attention else 1.0, attn=attn,
+                after_layer=True)
+    assert o["is_merged"].sum() > 50
+    m = make_layer(wl)
+    x, vis, cu = inputs(wl)
+    pp = binding.prune_params(retention=wl.retention, window=wl.window, gamma=gamma, prune_mode=2,
+                              alpha=0.6 if with_attention else 1.0)
+    out, kept, new_cu, vis_out = m.layer_forward(x, vis, cu, pp, add_residual=True, want_mask=True,
+                                                 attn=None if attn is None else dev(attn))
+    torch.cuda.synchronize()
+    new_cu = host(new_cu)
+    n = int(new_cu[-1])
+    assert np.array_equal(new_cu, o["new_cu_seqlens"])
+    assert np.array_equal(host(kept)[:n], o["kept_idx"])
+    assert np.array_equal(host(vis_out)[:n], wl.is_visual[o["kept_idx"]])
+    _check_after_layer_rows(host(out)[:n], o, wl.x, wl.dtype, f"attention {with_attention}")
 
 
 @pytest.mark.parametrize("shape", SHAPES)

@@ -777,6 +777,33 @@ def test_merge_mean_mode_is_the_numpy_mean():
     assert np.array_equal(xm[is_m == 0], xm2[is_m == 0])
 
 
+def test_after_layer_merging_is_eq16_18_on_the_output_rows():
+    # pruning after the layer with merging: the decisions are those of this layer's probabilities (the same
+    # as before the experts), an ordinary kept row is the un-pruned layer's output row, and a merged row is
+    # the mean of its window's OUTPUT rows rescaled to the largest output-row norm of the window
+    wl = W.config1()
+    kw = dict(k_text=wl.k_text, k_visual=wl.k_visual, is_bf16=False, add_residual=True)
+    full = oracle.layer_forward(wl.x, wl.is_visual, wl.cu_seqlens, wl.weights, do_prune=False, **kw)
+    for gamma in (0.05, 0.1):
+        pre = oracle.layer_forward(wl.x, wl.is_visual, wl.cu_seqlens, wl.weights, retention=wl.retention,
+                                   window=wl.window, gamma=gamma, **kw)
+        aft = oracle.layer_forward(wl.x, wl.is_visual, wl.cu_seqlens, wl.weights, retention=wl.retention,
+                                   window=wl.window, gamma=gamma, after_layer=True, **kw)
+        assert np.array_equal(aft["out_full"], full["out"])
+        assert np.array_equal(aft["kept_idx"], pre["kept_idx"]) and np.array_equal(aft["is_merged"], pre["is_merged"])
+        assert np.array_equal(aft["new_cu_seqlens"], pre["new_cu_seqlens"]) and aft["is_merged"].sum() >= 1
+        kept, is_m = aft["kept_idx"], aft["is_merged"]
+        assert np.array_equal(aft["out"][is_m == 0], full["out"][kept[is_m == 0]])
+        vis_tokens = np.nonzero(wl.is_visual)[0]            # config 1 is one sequence
+        for p_ in np.nonzero(is_m)[0]:
+            j = int(np.nonzero(vis_tokens == kept[p_])[0][0])
+            assert j % wl.window == 0                        # a merged token sits at its window's first token
+            rows = full["out"][vis_tokens[j:j + wl.window]].astype(np.float64)
+            mean = rows.mean(0)
+            ref = mean * (np.linalg.norm(rows, axis=1).max() / np.linalg.norm(mean))
+            assert np.abs(aft["out"][p_] - ref).max() <= 1e-6 * np.abs(ref).max()
+
+
 # ---------------------------------------------------------------- App. E: theoretical FLOPs ratios
 # Readings the printed savings fix (the paper states neither the dimensions nor the length behind them):
 # the public dimensions of the two models, 2048 vision tokens, K counting the shared experts, the rounded
